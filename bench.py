@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the change-based convolution path on one MI355X.
+
+A step is one video frame through the whole hot path (change detection, index extraction,
+dilation, gathered matrix multiplication with output update, change propagation through
+pooling) of the 320x240 scene-labeling workload.  Frames are synthetic, seeded and already
+resident in HBM when the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg1] [--rate R]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+MI355X_HBM_GBS = 8000.0
+MI355X_FP32_MFMA_TFLOPS = 157.3
+
+
+def frame_order(n_frames: int, count: int, start: int = 0):
+    """Ping-pong through the sequence so that any number of steps sees ordinary motion."""
+    period = 2 * (n_frames - 1)
+    for i in range(start, start + count):
+        u = i % period
+        yield u if u < n_frames else period - u
+
+
+def build_workload(args):
+    from workloads import get_config
+    if args.workload == "cfg1":
+        cfg = get_config(1)
+    elif args.workload == "cfg2":
+        cfg = get_config(2)
+    elif args.workload == "cfg3":
+        cfg = get_config(3, change_rate=args.rate, sigma=args.sigma, n_frames=args.frames or 24)
+    else:
+        raise SystemExit("unknown workload " + args.workload)
+    if args.frames:
+        cfg.n_frames = args.frames
+    return cfg
+
+
+def time_steps(net, frames_dev, out, order):
+    import torch
+    ptrs = [frames_dev[t].data_ptr() for t in order]
+    optr = out.data_ptr()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for p in ptrs:
+        net.process_frame_ptr(p, optr)
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def cpu_baseline(cfg, budget_s: float):
+    """The oracle's change-based evaluation, as it stands, on the host cores: frame 0 (dense)
+    is processed untimed, then frames 1.. are timed until the budget is used."""
+    import oracle
+    params = cfg.weights()
+    video = cfg.video()
+    net = oracle.OracleCBNet(cfg.layers, params, cfg.tau)
+    net.process_frame(video.frame(0))
+    n, spent = 0, 0.0
+    while (spent < budget_s and n < cfg.n_frames - 1) or n == 0:
+        f = video.frame(n + 1)
+        t0 = time.perf_counter()
+        net.process_frame(f)
+        spent += time.perf_counter() - t0
+        n += 1
+    return {"value": n / spent, "unit": "frames/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": "%s frames 1..%d of the same video, change-based oracle (C, double accumulation, "
+                      "OpenMP over output positions), frame 0 untimed" % (cfg.name, n)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--rate", type=float, default=0.02, help="cfg3: nominal changed-pixel share")
+    ap.add_argument("--sigma", type=float, default=None, help="override sensor noise")
+    ap.add_argument("--frames", type=int, default=0, help="frames generated (default: the workload's)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg (0: skip)")
+    ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel timing pass")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one process, one MI355X); --gpus %d is not "
+              "supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1704_04313_amd as cb
+    from workloads import dense_flops
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+
+    cfg = build_workload(args)
+    params = cfg.weights()
+    video = cfg.video()
+    frames = np.stack([video.frame(t) for t in range(cfg.n_frames)])
+    frames_dev = torch.from_numpy(frames).cuda()
+    in_shape = (cfg.channels, cfg.height, cfg.width)
+    net = cb.CBInfer(cfg.layers, params, in_shape, cfg.tau)
+    out = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
+
+    W, K = args.warmup, args.steps
+    # ---- change-based: warm-up (includes the dense first frame), then exactly K timed steps
+    for t in frame_order(cfg.n_frames, W):
+        net.process_frame(frames_dev[t], out)
+    sec_cb = time_steps(net, frames_dev, out, list(frame_order(cfg.n_frames, K, W)))
+
+    # ---- dense HIP baseline: same kernels, identity lists, no change detection
+    net.set_mode(True)
+    for t in frame_order(cfg.n_frames, W):
+        net.process_frame(frames_dev[t], out)
+    sec_dense = time_steps(net, frames_dev, out, list(frame_order(cfg.n_frames, K, W)))
+    net.set_mode(False)
+
+    result = {
+        "metric": "frames/s and speed-up vs dense HIP conv at 1/5/20% change rate; HBM GB/s",
+        "value": K / sec_cb, "unit": "frames/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": 1e3 * sec_cb / K, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "frame": "%dx%dx%d" % (cfg.width, cfg.height, cfg.channels),
+                   "tau": cfg.tau, "sigma": cfg.sigma, "n_frames": cfg.n_frames, "n_streams": 1,
+                   "reference_update": "previous frame"},
+        "dense_hip_frames_per_s": K / sec_dense,
+        "speedup_vs_dense_hip": sec_dense / sec_cb,
+        "paper_context": "8.6x (Tegra X1) / 7.6x (GTX 1080) over cuDNN, 327.6 GOp/s/W; other hardware, other data",
+    }
+
+    # ---- per-kernel timing pass (HIP events around every launch, on the library's stream)
+    if not args.no_profile:
+        n_ops = len(cfg.layers)
+        conv_ids = [l for l, L in enumerate(cfg.layers) if L.kind == "conv"]
+        net.reset()
+        for t in frame_order(cfg.n_frames, W):
+            net.process_frame(frames_dev[t], out)
+        net.set_profiling(True)
+        P = min(K, 100)
+        sums = {l: np.zeros(2) for l in range(n_ops)}
+        for t in frame_order(cfg.n_frames, P, W):
+            net.process_frame(frames_dev[t], out)
+            for l in range(n_ops):
+                sums[l] += np.maximum(np.array(net.layer_counts(l), dtype=np.float64), 0)
+        prof = {}
+        for l in range(n_ops):
+            for s, name in enumerate(cb.STEP_NAMES):
+                ms, n = net.read_profile(l, s)
+                if n:
+                    prof[(l, name)] = (ms / n, n)
+        net.set_profiling(False)
+        shapes = [in_shape] + [net.layer_shape(l) for l in range(n_ops)]
+        rates, kernels = {}, {}
+        for l in range(n_ops):
+            L = cfg.layers[l]
+            c_in, h_in, w_in = shapes[l]
+            c_out, h_out, w_out = shapes[l + 1]
+            n_c, n_u = sums[l] / P
+            if L.kind == "conv":
+                rates["L%d" % l] = {"changed_in": n_c / (h_in * w_in), "updated_out": n_u / (h_out * w_out)}
+            else:
+                rates["L%d" % l] = {"updated_pooled": n_u / (h_out * w_out)}
+            for (ll, name), (ms, n) in prof.items():
+                if ll != l:
+                    continue
+                e = {"us": 1e3 * ms}
+                if name == "detect":
+                    by = 12.0 * c_in * h_in * w_in + h_in * w_in / 8.0
+                    e.update(bytes=by, GBps=by / (ms * 1e-3) / 1e9, frac_hbm=by / (ms * 1e-3) / 1e9 / MI355X_HBM_GBS)
+                elif name == "gemm":
+                    fl = 2.0 * L.cout * L.cin * L.kh * L.kw * n_u
+                    e.update(flops=fl, TFLOPs=fl / (ms * 1e-3) / 1e12,
+                             frac_mfma=fl / (ms * 1e-3) / 1e12 / MI355X_FP32_MFMA_TFLOPS)
+                elif name == "compact":
+                    by = (h_in * w_in + h_out * w_out) / 8.0 + 4.0 * (n_c + n_u)
+                    e.update(bytes=by, GBps=by / (ms * 1e-3) / 1e9)
+                elif name == "pool":
+                    by = 4.0 * n_u + 5.0 * 4.0 * c_out * n_u
+                    e.update(bytes=by, GBps=by / (ms * 1e-3) / 1e9)
+                kernels["L%d.%s" % (l, name)] = e
+        dom = max(kernels, key=lambda k: kernels[k]["us"])
+        d = kernels[dom]
+        if "TFLOPs" in d:
+            roof = {"bound": "mfma", "achieved": d["TFLOPs"], "peak": MI355X_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": d["frac_mfma"], "traffic": None}
+        else:
+            roof = {"bound": "hbm", "achieved": d.get("GBps"), "peak": MI355X_HBM_GBS, "unit": "GB/s",
+                    "frac": (d.get("GBps") or 0.0) / MI355X_HBM_GBS, "traffic": None}
+        roof["kernel"] = dom
+        roof["avg_us"] = d["us"]
+        roof["sum_kernel_us_per_frame"] = sum(k["us"] for k in kernels.values())
+        result["roofline"] = roof
+        result["kernels"] = kernels
+        result["change_rates"] = rates
+        result["dense_gflop_per_frame"] = sum(dense_flops(cfg.layers, *in_shape)) / 1e9
+    else:
+        result["roofline"] = None
+
+    net.destroy()
+    result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds) if args.cpu_seconds > 0 else None
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

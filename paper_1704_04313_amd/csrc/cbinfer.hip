@@ -1,0 +1,638 @@
+// C ABI, network plan, per-layer state and the per-frame schedule.
+// Every step of the path runs in the kernels declared in kernels.h; this file validates the
+// network description, lays out device memory, uploads the filter matrices and enqueues the
+// kernels of a frame on the caller's stream without ever waiting for the device.
+#include "../../include/cbinfer.h"
+#include "kernels.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+namespace {
+
+thread_local std::string g_err = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+inline int words_for(long long bits) { return (int)((bits + 63) / 64); }
+
+struct Op {
+    int kind = 0;
+    // input map
+    int C = 0, Cs = 0, H = 0, W = 0;
+    // output map
+    int M = 0, Ms = 0, Ho = 0, Wo = 0;
+    int kh = 1, kw = 1, stride = 1, pad = 0, relu = 0, dense = 0;
+    float tau = 0.f;
+    int K = 0, Kpad = 0, Mpad = 0;
+    int pool_after = -1; // CONV: index of the pooling op that directly follows, or -1
+    int conv_before = -1; // MAXPOOL: index of the conv it follows
+    // workspace offsets (bytes); SIZE_MAX = absent
+    size_t o_ref = SIZE_MAX, o_cur = SIZE_MAX, o_out = SIZE_MAX, o_wt = SIZE_MAX, o_bias = SIZE_MAX,
+           o_taps = SIZE_MAX, o_chg = SIZE_MAX, o_upd = SIZE_MAX, o_pool = SIZE_MAX, o_clist = SIZE_MAX,
+           o_ulist = SIZE_MAX, o_counts = SIZE_MAX;
+};
+
+struct Plan {
+    std::vector<Op> ops;
+    int S = 1, in_c = 0, in_h = 0, in_w = 0;
+    bool hold = false;
+    size_t o_iota = 0, o_const = 0;
+    int iota_len = 0;
+    size_t bytes = 0;
+};
+
+struct Carver {
+    size_t off = 0;
+    size_t take(size_t bytes)
+    {
+        const size_t o = off;
+        off += align_up(bytes ? bytes : 1);
+        return o;
+    }
+};
+
+// Validates the description and lays out the workspace.  Touches no device.
+int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, Plan &P)
+{
+    if (!net) return fail(CBINFER_EINVAL, "network description is NULL");
+    if (net->n_layers <= 0 || !net->layers) return fail(CBINFER_EINVAL, "network has no layers");
+    if (net->in_c <= 0 || net->in_h <= 0 || net->in_w <= 0)
+        return fail(CBINFER_EINVAL, "frame shape must be positive (got %d x %d x %d)", net->in_c, net->in_h,
+                    net->in_w);
+    if (net->n_streams <= 0) return fail(CBINFER_EINVAL, "n_streams must be >= 1");
+    if (net->dtype != CBINFER_F32)
+        return fail(net->dtype == CBINFER_BF16 ? CBINFER_EUNSUPPORTED : CBINFER_EINVAL,
+                    "only CBINFER_F32 storage is implemented");
+    if (net->flags & ~(uint32_t)CBINFER_FLAG_HOLD_REFERENCE) return fail(CBINFER_EINVAL, "unknown flag bits");
+    if (need_threshold && !(threshold >= 0.0f && std::isfinite(threshold))) {
+        bool all_own = true;
+        for (int l = 0; l < net->n_layers; ++l)
+            if (net->layers[l].kind == CBINFER_OP_CONV && !(net->layers[l].threshold >= 0.0f)) all_own = false;
+        if (!all_own) return fail(CBINFER_EINVAL, "global threshold must be finite and >= 0");
+    }
+    P.S = net->n_streams;
+    P.in_c = net->in_c;
+    P.in_h = net->in_h;
+    P.in_w = net->in_w;
+    P.hold = (net->flags & CBINFER_FLAG_HOLD_REFERENCE) != 0;
+    P.ops.clear();
+    int c = net->in_c, h = net->in_h, w = net->in_w;
+    const long long lim = (1ll << 31) - 1;
+    long long max_px = 0;
+    for (int l = 0; l < net->n_layers; ++l) {
+        const cbinfer_layer &L = net->layers[l];
+        Op op;
+        op.kind = L.kind;
+        op.C = c;
+        op.Cs = round_up(c, 4);
+        op.H = h;
+        op.W = w;
+        if (L.kind == CBINFER_OP_CONV) {
+            if (L.cin != c) return fail(CBINFER_EINVAL, "layer %d: cin %d does not match incoming %d channels", l, L.cin, c);
+            if (L.cout <= 0) return fail(CBINFER_EINVAL, "layer %d: cout must be positive", l);
+            if (L.kh <= 0 || L.kw <= 0 || L.stride <= 0) return fail(CBINFER_EINVAL, "layer %d: kernel size and stride must be positive", l);
+            if (L.pad < 0 || L.pad >= L.kh || L.pad >= L.kw) return fail(CBINFER_EINVAL, "layer %d: need 0 <= pad < kernel size", l);
+            if (L.kh > 64 || L.kw > 64) return fail(CBINFER_EUNSUPPORTED, "layer %d: kernels larger than 64 are not supported", l);
+            if (h + 2 * L.pad < L.kh || w + 2 * L.pad < L.kw) return fail(CBINFER_EINVAL, "layer %d: kernel larger than padded input", l);
+            if (!L.weight) return fail(CBINFER_EINVAL, "layer %d: weight pointer is NULL", l);
+            if (std::isnan(L.threshold) || std::isinf(L.threshold)) return fail(CBINFER_EINVAL, "layer %d: threshold must be finite", l);
+            op.kh = L.kh;
+            op.kw = L.kw;
+            op.stride = L.stride;
+            op.pad = L.pad;
+            op.relu = L.relu != 0;
+            op.dense = L.dense != 0;
+            op.tau = L.threshold >= 0.0f ? L.threshold : threshold;
+            op.M = L.cout;
+            op.Ms = round_up(op.M, 4);
+            op.Ho = (h + 2 * L.pad - L.kh) / L.stride + 1;
+            op.Wo = (w + 2 * L.pad - L.kw) / L.stride + 1;
+            op.K = L.kh * L.kw * op.Cs;
+            op.Kpad = round_up(op.K, cbk::gemm_k_multiple());
+            op.Mpad = round_up(op.M, cbk::gemm_channel_tile(op.M));
+            c = op.M;
+        } else if (L.kind == CBINFER_OP_MAXPOOL) {
+            if (L.kh != L.kw || L.kh < 1) return fail(CBINFER_EINVAL, "layer %d: pooling window must be square", l);
+            if (L.stride != L.kh || L.pad != 0) return fail(CBINFER_EUNSUPPORTED, "layer %d: pooling needs stride == window and no padding", l);
+            if (l == 0 || P.ops.back().kind != CBINFER_OP_CONV)
+                return fail(CBINFER_EUNSUPPORTED, "layer %d: pooling must directly follow a convolution layer", l);
+            if (h % L.kh || w % L.kh) return fail(CBINFER_EINVAL, "layer %d: map %d x %d is not a multiple of the pooling window", l, h, w);
+            op.kh = op.kw = op.stride = L.kh;
+            op.M = c;
+            op.Ms = round_up(c, 4);
+            op.Ho = h / L.kh;
+            op.Wo = w / L.kh;
+            op.conv_before = l - 1;
+            P.ops.back().pool_after = l;
+        } else {
+            return fail(CBINFER_EINVAL, "layer %d: unknown kind %d", l, L.kind);
+        }
+        h = op.Ho;
+        w = op.Wo;
+        const long long in_elems = (long long)P.S * op.H * op.W * op.Cs;
+        const long long out_elems = (long long)P.S * op.Ho * op.Wo * (L.kind == CBINFER_OP_CONV ? op.Ms : op.Ms);
+        if (in_elems > lim || out_elems > lim || (long long)op.Mpad * op.Kpad > lim)
+            return fail(CBINFER_EUNSUPPORTED, "layer %d: a map or the filter matrix exceeds 2^31-1 elements", l);
+        max_px = std::max(max_px, std::max((long long)P.S * op.H * op.W, (long long)P.S * op.Ho * op.Wo));
+        P.ops.push_back(op);
+    }
+    // workspace layout
+    Carver cv;
+    for (size_t l = 0; l < P.ops.size(); ++l) {
+        Op &op = P.ops[l];
+        const size_t in_px = (size_t)P.S * op.H * op.W, out_px = (size_t)P.S * op.Ho * op.Wo;
+        op.o_out = cv.take(out_px * op.Ms * 4);
+        op.o_ulist = cv.take(out_px * 4);
+        op.o_counts = cv.take(4 * 4);
+        if (op.kind == CBINFER_OP_CONV) {
+            op.o_ref = cv.take(in_px * op.Cs * 4);
+            if (l == 0 && P.hold) op.o_cur = cv.take(in_px * op.Cs * 4);
+            op.o_wt = cv.take((size_t)op.Mpad * op.Kpad * 4);
+            op.o_bias = cv.take((size_t)op.Mpad * 4);
+            op.o_taps = cv.take((size_t)op.Kpad / 4 * sizeof(int2));
+            op.o_chg = cv.take(((size_t)words_for((long long)in_px) + 1) * 8);
+            op.o_upd = cv.take(((size_t)words_for((long long)out_px) + 1) * 8);
+            if (op.pool_after >= 0) {
+                const Op &pp = P.ops[op.pool_after];
+                op.o_pool = cv.take(((size_t)words_for((long long)P.S * pp.Ho * pp.Wo) + 1) * 8);
+            }
+            op.o_clist = cv.take(in_px * 4);
+        }
+    }
+    P.iota_len = (int)max_px;
+    P.o_iota = cv.take((size_t)P.iota_len * 4);
+    P.o_const = cv.take(P.ops.size() * 2 * 4);
+    P.bytes = cv.off;
+    return CBINFER_OK;
+}
+
+struct EventPair {
+    hipEvent_t a = nullptr, b = nullptr;
+    int layer = 0, step = 0;
+};
+
+} // namespace
+
+struct cbinfer_state {
+    Plan plan;
+    hipStream_t stream = nullptr;
+    char *ws = nullptr;
+    bool owns_ws = false;
+    bool initialised = false; // a frame has been processed since create/reset
+    bool force_dense = false;
+    bool broken = false;
+    bool have_frame = false;
+    bool profiling = false;
+    std::vector<EventPair> events;
+    size_t events_used = 0;
+    std::vector<double> prof_ms;
+    std::vector<long long> prof_n;
+
+    template <class T>
+    T *at(size_t off) const
+    {
+        return off == SIZE_MAX ? nullptr : reinterpret_cast<T *>(ws + off);
+    }
+};
+
+namespace {
+
+#define HIP_TRY(expr)                                                                              \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) {                                                                    \
+            s->broken = true;                                                                      \
+            return fail(CBINFER_EDEVICE, "%s failed: %s", #expr, hipGetErrorString(e_));           \
+        }                                                                                          \
+    } while (0)
+
+struct StepTimer {
+    cbinfer_state *s;
+    EventPair *ep = nullptr;
+    StepTimer(cbinfer_state *s_, int layer, int step) : s(s_)
+    {
+        if (!s->profiling) return;
+        if (s->events_used == s->events.size()) {
+            EventPair p;
+            if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) return;
+            s->events.push_back(p);
+        }
+        ep = &s->events[s->events_used++];
+        ep->layer = layer;
+        ep->step = step;
+        (void)hipEventRecord(ep->a, s->stream);
+    }
+    ~StepTimer()
+    {
+        if (ep) (void)hipEventRecord(ep->b, s->stream);
+    }
+};
+
+int collect_profile(cbinfer_state *s)
+{
+    if (!s->profiling || s->events_used == 0) return CBINFER_OK;
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    for (size_t i = 0; i < s->events_used; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, s->events[i].a, s->events[i].b) == hipSuccess) {
+            const size_t k = (size_t)s->events[i].layer * CBINFER_STEP_COUNT + s->events[i].step;
+            s->prof_ms[k] += ms;
+            s->prof_n[k] += 1;
+        }
+    }
+    s->events_used = 0;
+    return CBINFER_OK;
+}
+
+// Filter matrix K (Section 3) re-laid-out for the gather: row o, column k = (j*kw + i)*Cs + c.
+void build_filter_matrix(const Op &op, const float *w, std::vector<float> &wt)
+{
+    wt.assign((size_t)op.Mpad * op.Kpad, 0.0f);
+    for (int o = 0; o < op.M; ++o)
+        for (int c = 0; c < op.C; ++c)
+            for (int j = 0; j < op.kh; ++j)
+                for (int i = 0; i < op.kw; ++i)
+                    wt[(size_t)o * op.Kpad + (size_t)(j * op.kw + i) * op.Cs + c] =
+                        w[(((size_t)o * op.C + c) * op.kh + j) * op.kw + i];
+}
+
+void build_taps(const Op &op, std::vector<int2> &taps)
+{
+    taps.resize(op.Kpad / 4);
+    for (int v = 0; v < op.Kpad / 4; ++v) {
+        const int k = v * 4;
+        int2 t;
+        if (k < op.K) {
+            const int tap = k / op.Cs, c = k - tap * op.Cs;
+            const int j = tap / op.kw, i = tap - j * op.kw;
+            t.x = (j * op.W + i) * op.Cs + c;
+            t.y = j | (i << 8) | (1 << 16);
+        } else {
+            t.x = 0;
+            t.y = 0;
+        }
+        taps[v] = t;
+    }
+}
+
+int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
+{
+    const Plan &P = s->plan;
+    hipStream_t st = s->stream;
+    const bool first = !s->initialised;
+    const int S = P.S;
+    int *iota = s->at<int>(P.o_iota);
+    int *consts = s->at<int>(P.o_const);
+    const int nops = (int)P.ops.size();
+
+    for (int l = 0; l < nops; ++l) {
+        const Op &op = P.ops[l];
+        if (op.kind == CBINFER_OP_CONV) {
+            const int N = op.H * op.W, No = op.Ho * op.Wo;
+            const float *x = nullptr;
+            float *ref = s->at<float>(op.o_ref);
+            int *counts = s->at<int>(op.o_counts);
+            const bool all = first || op.dense || s->force_dense;
+            // --- change detection (also turns the planar frame into a map for layer 0)
+            if (l == 0) {
+                StepTimer t(s, l, CBINFER_STEP_DETECT);
+                const int hold = (P.hold && !s->force_dense) ? 1 : 0;
+                HIP_TRY(cbk::detect_frame(st, frame, ref, s->at<float>(op.o_cur), s->at<uint64_t>(op.o_chg), op.C,
+                                          op.Cs, N, S, op.tau, hold, all ? 1 : 0));
+                x = hold ? s->at<float>(op.o_cur) : ref;
+            } else {
+                x = s->at<float>(P.ops[l - 1].o_out);
+                if (!s->force_dense) {
+                    StepTimer t(s, l, CBINFER_STEP_DETECT);
+                    HIP_TRY(cbk::detect_map(st, x, ref, s->at<uint64_t>(op.o_chg), op.Cs, S * N, op.tau,
+                                            P.hold ? 1 : 0, all ? 1 : 0));
+                }
+            }
+            const int *ulist = iota;
+            const int *ucount = consts + 2 * l;
+            if (!s->force_dense) {
+                cbk::DilateGeom g;
+                g.S = S; g.H = op.H; g.W = op.W; g.Ho = op.Ho; g.Wo = op.Wo;
+                g.kh = op.kh; g.kw = op.kw; g.stride = op.stride; g.pad = op.pad;
+                g.pool_k = 0; g.Hp = 0; g.Wp = 0;
+                uint64_t *pool_bits = nullptr;
+                if (op.pool_after >= 0) {
+                    const Op &pp = P.ops[op.pool_after];
+                    g.pool_k = pp.kh; g.Hp = pp.Ho; g.Wp = pp.Wo;
+                    pool_bits = s->at<uint64_t>(op.o_pool);
+                }
+                {
+                    StepTimer t(s, l, CBINFER_STEP_DILATE);
+                    HIP_TRY(cbk::dilate(st, s->at<uint64_t>(op.o_chg), s->at<uint64_t>(op.o_upd), pool_bits, g));
+                }
+                cbk::CompactJob jobs[3];
+                int nj = 0;
+                jobs[nj++] = {s->at<uint64_t>(op.o_upd), words_for((long long)S * No), s->at<int>(op.o_ulist), counts + 1};
+                jobs[nj++] = {s->at<uint64_t>(op.o_chg), words_for((long long)S * N), s->at<int>(op.o_clist), counts + 0};
+                if (op.pool_after >= 0) {
+                    const Op &pp = P.ops[op.pool_after];
+                    jobs[nj++] = {pool_bits, words_for((long long)S * pp.Ho * pp.Wo), s->at<int>(pp.o_ulist),
+                                  s->at<int>(pp.o_counts) + 1};
+                }
+                {
+                    StepTimer t(s, l, CBINFER_STEP_COMPACT);
+                    HIP_TRY(cbk::compact(st, jobs, nj));
+                }
+                ulist = s->at<int>(op.o_ulist);
+                ucount = counts + 1;
+            }
+            // --- gathered matrix generation + multiplication + output update
+            cbk::GemmArgs a;
+            a.x = x;
+            a.wt = s->at<float>(op.o_wt);
+            a.bias = s->at<float>(op.o_bias);
+            a.taps = s->at<int2>(op.o_taps);
+            a.list = ulist;
+            a.count = ucount;
+            a.out = s->at<float>(op.o_out);
+            a.N = N; a.H = op.H; a.W = op.W; a.No = No; a.Wo = op.Wo;
+            a.stride = op.stride; a.pad = op.pad; a.Cs = op.Cs; a.Kpad = op.Kpad;
+            a.M = op.M; a.Mpad = op.Mpad; a.Ms = op.Ms; a.relu = op.relu;
+            a.max_pixels = S * No;
+            {
+                StepTimer t(s, l, CBINFER_STEP_GEMM);
+                HIP_TRY(cbk::gemm_gather(st, a));
+            }
+        } else {
+            const Op &cv = P.ops[op.conv_before];
+            const int Np = op.Ho * op.Wo;
+            const int *plist = s->force_dense ? iota : s->at<int>(op.o_ulist);
+            const int *pcount = s->force_dense ? consts + 2 * l : s->at<int>(op.o_counts) + 1;
+            StepTimer t(s, l, CBINFER_STEP_POOL);
+            HIP_TRY(cbk::pool_sparse(st, plist, pcount, S * Np, s->at<float>(cv.o_out), s->at<float>(op.o_out), op.Ms,
+                                     op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np));
+        }
+    }
+    const Op &last = P.ops.back();
+    {
+        StepTimer t(s, nops - 1, CBINFER_STEP_OUTPUT);
+        HIP_TRY(cbk::map_to_planar(st, s->at<float>(last.o_out), out, last.M, last.Ms, last.Ho * last.Wo, S));
+    }
+    s->initialised = true;
+    s->have_frame = true;
+    return collect_profile(s);
+}
+
+} // namespace
+
+extern "C" {
+
+const char *cbinfer_last_error(void) { return g_err.c_str(); }
+
+size_t cbinfer_workspace_bytes(const cbinfer_network *net)
+{
+    Plan P;
+    if (make_plan(net, 0.0f, false, P) != CBINFER_OK) return 0;
+    return P.bytes;
+}
+
+cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold)
+{
+    Plan P;
+    if (make_plan(net, threshold, true, P) != CBINFER_OK) return nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
+        fail(CBINFER_EDEVICE, "no HIP device available (this library has no CPU path)");
+        return nullptr;
+    }
+    cbinfer_state *s = new cbinfer_state();
+    s->plan = P;
+    s->stream = reinterpret_cast<hipStream_t>(net->stream);
+    if (net->workspace) {
+        if (reinterpret_cast<uintptr_t>(net->workspace) % kAlign) {
+            fail(CBINFER_EINVAL, "workspace must be %zu-byte aligned", kAlign);
+            delete s;
+            return nullptr;
+        }
+        if (net->workspace_bytes < P.bytes) {
+            fail(CBINFER_ENOMEM, "workspace has %zu bytes, %zu needed", net->workspace_bytes, P.bytes);
+            delete s;
+            return nullptr;
+        }
+        s->ws = static_cast<char *>(net->workspace);
+    } else {
+        void *p = nullptr;
+        hipError_t e = hipMalloc(&p, P.bytes);
+        if (e != hipSuccess) {
+            fail(CBINFER_ENOMEM, "hipMalloc of %zu bytes failed: %s", P.bytes, hipGetErrorString(e));
+            delete s;
+            return nullptr;
+        }
+        s->ws = static_cast<char *>(p);
+        s->owns_ws = true;
+    }
+    s->prof_ms.assign(P.ops.size() * CBINFER_STEP_COUNT, 0.0);
+    s->prof_n.assign(P.ops.size() * CBINFER_STEP_COUNT, 0);
+
+    auto setup = [&]() -> int {
+        HIP_TRY(cbk::gemm_prepare());
+        HIP_TRY(hipMemsetAsync(s->ws, 0, P.bytes, s->stream));
+        std::vector<float> wt, bias;
+        std::vector<int2> taps;
+        std::vector<int> consts(P.ops.size() * 2, 0);
+        for (size_t l = 0; l < P.ops.size(); ++l) {
+            const Op &op = P.ops[l];
+            consts[2 * l] = P.S * op.Ho * op.Wo;
+            if (op.kind != CBINFER_OP_CONV) continue;
+            const cbinfer_layer &L = net->layers[l];
+            build_filter_matrix(op, static_cast<const float *>(L.weight), wt);
+            bias.assign(op.Mpad, 0.0f);
+            if (L.bias)
+                for (int o = 0; o < op.M; ++o) bias[o] = L.bias[o];
+            build_taps(op, taps);
+            // the staging vectors are reused for the next layer: wait for the copies first
+            HIP_TRY(hipMemcpyAsync(s->at<float>(op.o_wt), wt.data(), wt.size() * 4, hipMemcpyHostToDevice, s->stream));
+            HIP_TRY(hipMemcpyAsync(s->at<float>(op.o_bias), bias.data(), bias.size() * 4, hipMemcpyHostToDevice, s->stream));
+            HIP_TRY(hipMemcpyAsync(s->at<int2>(op.o_taps), taps.data(), taps.size() * sizeof(int2), hipMemcpyHostToDevice, s->stream));
+            HIP_TRY(hipStreamSynchronize(s->stream));
+        }
+        HIP_TRY(hipMemcpyAsync(s->at<int>(P.o_const), consts.data(), consts.size() * 4, hipMemcpyHostToDevice, s->stream));
+        HIP_TRY(cbk::fill_iota(s->stream, s->at<int>(P.o_iota), P.iota_len));
+        HIP_TRY(hipStreamSynchronize(s->stream));
+        return CBINFER_OK;
+    };
+    if (setup() != CBINFER_OK) {
+        if (s->owns_ws) (void)hipFree(s->ws);
+        delete s;
+        return nullptr;
+    }
+    return s;
+}
+
+int cbinfer_process_frame(cbinfer_state *s, const void *frame_dev, void *out_dev)
+{
+    if (!s) return fail(CBINFER_EINVAL, "state is NULL");
+    if (!frame_dev || !out_dev) return fail(CBINFER_EINVAL, "frame and output pointers must not be NULL");
+    if (s->broken) return fail(CBINFER_EDEVICE, "a previous HIP call failed; destroy this state");
+    return enqueue_frame(s, static_cast<const float *>(frame_dev), static_cast<float *>(out_dev));
+}
+
+int cbinfer_reset(cbinfer_state *s)
+{
+    if (!s) return fail(CBINFER_EINVAL, "state is NULL");
+    s->initialised = false;
+    return CBINFER_OK;
+}
+
+void cbinfer_destroy(cbinfer_state *s)
+{
+    if (!s) return;
+    (void)hipStreamSynchronize(s->stream);
+    for (auto &e : s->events) {
+        if (e.a) (void)hipEventDestroy(e.a);
+        if (e.b) (void)hipEventDestroy(e.b);
+    }
+    if (s->owns_ws && s->ws) (void)hipFree(s->ws);
+    delete s;
+}
+
+int cbinfer_set_mode(cbinfer_state *s, int force_dense)
+{
+    if (!s) return fail(CBINFER_EINVAL, "state is NULL");
+    s->force_dense = force_dense != 0;
+    s->initialised = false;
+    return CBINFER_OK;
+}
+
+int cbinfer_layer_shape(cbinfer_state *s, int layer, int32_t *c, int32_t *h, int32_t *w)
+{
+    if (!s) return fail(CBINFER_EINVAL, "state is NULL");
+    if (layer < 0 || layer >= (int)s->plan.ops.size()) return fail(CBINFER_EINVAL, "layer %d out of range", layer);
+    const Op &op = s->plan.ops[layer];
+    if (c) *c = op.M;
+    if (h) *h = op.Ho;
+    if (w) *w = op.Wo;
+    return CBINFER_OK;
+}
+
+static int check_query(cbinfer_state *s, int layer)
+{
+    if (!s) return fail(CBINFER_EINVAL, "state is NULL");
+    if (layer < 0 || layer >= (int)s->plan.ops.size()) return fail(CBINFER_EINVAL, "layer %d out of range", layer);
+    if (s->broken) return fail(CBINFER_EDEVICE, "a previous HIP call failed; destroy this state");
+    if (!s->have_frame) return fail(CBINFER_ESTATE, "no frame has been processed yet");
+    return CBINFER_OK;
+}
+
+int cbinfer_layer_counts(cbinfer_state *s, int layer, int64_t *n_changed, int64_t *n_update)
+{
+    int rc = check_query(s, layer);
+    if (rc) return rc;
+    const Op &op = s->plan.ops[layer];
+    int c[2] = {0, 0};
+    if (s->force_dense) {
+        c[0] = op.kind == CBINFER_OP_CONV ? s->plan.S * op.H * op.W : -1;
+        c[1] = s->plan.S * op.Ho * op.Wo;
+    } else {
+        HIP_TRY(hipStreamSynchronize(s->stream));
+        HIP_TRY(hipMemcpy(c, s->at<int>(op.o_counts), 8, hipMemcpyDeviceToHost));
+        if (op.kind != CBINFER_OP_CONV) c[0] = -1;
+    }
+    if (n_changed) *n_changed = c[0];
+    if (n_update) *n_update = c[1];
+    return CBINFER_OK;
+}
+
+int cbinfer_read_list(cbinfer_state *s, int layer, int which, int32_t *host, int64_t cap, int64_t *n)
+{
+    int rc = check_query(s, layer);
+    if (rc) return rc;
+    const Op &op = s->plan.ops[layer];
+    if (which != CBINFER_LIST_CHANGED && which != CBINFER_LIST_UPDATE) return fail(CBINFER_EINVAL, "unknown list %d", which);
+    if (which == CBINFER_LIST_CHANGED && op.kind != CBINFER_OP_CONV)
+        return fail(CBINFER_EINVAL, "layer %d is a pooling layer and has no changed-input list", layer);
+    if (cap < 0 || (cap > 0 && !host)) return fail(CBINFER_EINVAL, "bad host buffer");
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    int count = 0;
+    const int *src = nullptr;
+    if (s->force_dense) {
+        count = which == CBINFER_LIST_CHANGED ? s->plan.S * op.H * op.W : s->plan.S * op.Ho * op.Wo;
+        src = s->at<int>(s->plan.o_iota);
+    } else {
+        HIP_TRY(hipMemcpy(&count, s->at<int>(op.o_counts) + (which == CBINFER_LIST_CHANGED ? 0 : 1), 4,
+                          hipMemcpyDeviceToHost));
+        src = which == CBINFER_LIST_CHANGED ? s->at<int>(op.o_clist) : s->at<int>(op.o_ulist);
+    }
+    if (n) *n = count;
+    const int64_t m = count < cap ? count : cap;
+    if (m > 0) HIP_TRY(hipMemcpy(host, src, (size_t)m * 4, hipMemcpyDeviceToHost));
+    return CBINFER_OK;
+}
+
+int cbinfer_read_map(cbinfer_state *s, int layer, int which, float *host, size_t count)
+{
+    int rc = check_query(s, layer);
+    if (rc) return rc;
+    if (!host) return fail(CBINFER_EINVAL, "host buffer is NULL");
+    const Op &op = s->plan.ops[layer];
+    int C, Cs, HW;
+    const float *src;
+    if (which == CBINFER_MAP_REFERENCE) {
+        if (op.kind != CBINFER_OP_CONV) return fail(CBINFER_EINVAL, "layer %d has no stored previous input", layer);
+        if (s->force_dense && layer > 0) return fail(CBINFER_ESTATE, "dense mode keeps no previous input for layer %d", layer);
+        C = op.C; Cs = op.Cs; HW = op.H * op.W;
+        src = s->at<float>(op.o_ref);
+    } else if (which == CBINFER_MAP_OUTPUT) {
+        C = op.M; Cs = op.Ms; HW = op.Ho * op.Wo;
+        src = s->at<float>(op.o_out);
+    } else {
+        return fail(CBINFER_EINVAL, "unknown map %d", which);
+    }
+    const size_t need = (size_t)s->plan.S * C * HW;
+    if (count != need) return fail(CBINFER_EINVAL, "map has %zu values, buffer holds %zu", need, count);
+    std::vector<float> tmp((size_t)s->plan.S * HW * Cs);
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    HIP_TRY(hipMemcpy(tmp.data(), src, tmp.size() * 4, hipMemcpyDeviceToHost));
+    for (int st = 0; st < s->plan.S; ++st)
+        for (int c = 0; c < C; ++c)
+            for (int p = 0; p < HW; ++p)
+                host[((size_t)st * C + c) * HW + p] = tmp[((size_t)st * HW + p) * Cs + c];
+    return CBINFER_OK;
+}
+
+int cbinfer_set_profiling(cbinfer_state *s, int enable)
+{
+    if (!s) return fail(CBINFER_EINVAL, "state is NULL");
+    if (s->broken) return fail(CBINFER_EDEVICE, "a previous HIP call failed; destroy this state");
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    s->profiling = enable != 0;
+    s->events_used = 0;
+    std::fill(s->prof_ms.begin(), s->prof_ms.end(), 0.0);
+    std::fill(s->prof_n.begin(), s->prof_n.end(), 0);
+    return CBINFER_OK;
+}
+
+int cbinfer_read_profile(cbinfer_state *s, int layer, int step, double *ms_total, int64_t *launches)
+{
+    if (!s) return fail(CBINFER_EINVAL, "state is NULL");
+    if (layer < 0 || layer >= (int)s->plan.ops.size()) return fail(CBINFER_EINVAL, "layer %d out of range", layer);
+    if (step < 0 || step >= CBINFER_STEP_COUNT) return fail(CBINFER_EINVAL, "step %d out of range", step);
+    const size_t k = (size_t)layer * CBINFER_STEP_COUNT + step;
+    if (ms_total) *ms_total = s->prof_ms[k];
+    if (launches) *launches = s->prof_n[k];
+    return CBINFER_OK;
+}
+
+} // extern "C"

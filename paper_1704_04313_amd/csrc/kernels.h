@@ -1,0 +1,78 @@
+// Host-side launch interface of the gfx950 kernels.  Everything here enqueues work on the
+// given stream and returns the hipError_t of the launch; nothing synchronises or allocates.
+//
+// Internal data layout (all device memory):
+//   maps      [stream][y][x][Cs]  float32, channel-contiguous, Cs = channels rounded up to 4;
+//             the padding channels are zero.  "pixel g" = stream*H*W + y*W + x.
+//   bitmaps   one bit per pixel g, packed in uint64 words (bit g%64 of word g/64);
+//             bits at or beyond the pixel count are zero.
+//   lists     int32 pixel indices g, ascending, with their length in an int32 counter.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cbk {
+
+// ---- change detection (Section 3.1, first formula) ---------------------------------------
+// Planar float32 frame [S][C][N] against the stored previous input kept as a map.
+// Writes the change bitmap; refreshes the stored input (hold == 0: everywhere;
+// hold == 1: `cur` receives the frame as a map and `ref` is refreshed only where flagged).
+// force != 0: every pixel is flagged and ref is not read (first frame / dense mode).
+hipError_t detect_frame(hipStream_t st, const float *frame, float *ref, float *cur, uint64_t *bits,
+                        int C, int Cs, int N, int S, float tau, int hold, int force);
+
+// Map against map (layers fed by a stored output map).  x and ref are [S*N][Cs].
+hipError_t detect_map(hipStream_t st, const float *x, float *ref, uint64_t *bits, int Cs, int total,
+                      float tau, int hold, int force);
+
+// ---- dilation by the filter support (Section 3.1, second formula) -------------------------
+// upd bit (stream, qy, qx) = OR of the change bits inside that output's receptive field.
+// If pool_bits != nullptr also writes, for a k x k / stride k pooling that follows, the
+// bitmap of pooled positions whose window contains an updated output.
+struct DilateGeom {
+    int S, H, W, Ho, Wo, kh, kw, stride, pad; // convolution geometry
+    int pool_k, Hp, Wp;                       // pooling that follows (pool_k == 0: none)
+};
+hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, uint64_t *pool_bits,
+                  const DilateGeom &g);
+
+// ---- change-index extraction (Section 3.1) -------------------------------------------------
+// Up to three bitmaps -> ascending index lists and counts in one launch.
+struct CompactJob {
+    const uint64_t *bits;
+    int nwords;
+    int *list;
+    int *count;
+};
+hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs);
+
+// ---- gathered matrix generation + multiplication + output update (Section 3.1) -------------
+struct GemmArgs {
+    const float *x;     // input map [S*N][Cs]
+    const float *wt;    // filter matrix, [Mpad][Kpad], k = (j*kw + i)*Cs + c, zero padded
+    const float *bias;  // [Mpad]
+    const int2 *taps;   // [Kpad/4]: .x = element offset of the tap from the window origin,
+                        //           .y = j | i << 8 | valid << 16
+    const int *list;    // output pixels to recompute
+    const int *count;   // their number (device)
+    float *out;         // stored output map [S*No][Ms]
+    int N, H, W, No, Wo, stride, pad, Cs, Kpad, M, Mpad, Ms, relu;
+    int max_pixels;     // upper bound of *count (sizes the grid)
+};
+// Tile variant chosen from M; returns the channel tile BM through *bm when args == nullptr.
+int gemm_channel_tile(int M);
+int gemm_k_multiple(void);
+hipError_t gemm_prepare(void); // one-time function attributes (dynamic LDS size)
+hipError_t gemm_gather(hipStream_t st, const GemmArgs &a);
+
+// ---- max-pooling at listed pooled positions -----------------------------------------------
+hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const float *in,
+                       float *pooled, int Ms, int k, int Wo, int No, int Wp, int Np);
+
+// ---- stored map -> caller's planar output --------------------------------------------------
+hipError_t map_to_planar(hipStream_t st, const float *map, float *planar, int M, int Ms, int No, int S);
+
+// helpers
+hipError_t fill_iota(hipStream_t st, int *list, int n);
+
+} // namespace cbk

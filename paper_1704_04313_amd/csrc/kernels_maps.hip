@@ -1,0 +1,390 @@
+// Memory-bound kernels of the change-based convolution layer for gfx950 (wave64):
+// change detection, dilation by the filter support, change-index extraction, sparse
+// max-pooling and the final layout change.  See kernels.h for the data layout.
+#include "kernels.h"
+
+namespace cbk {
+
+static constexpr int kBlock = 256;
+
+__device__ __forceinline__ bool exceeds(const float4 a, const float4 r, const float tau)
+{
+    // one subtraction, one absolute value, one strict comparison per channel (Section 3.1);
+    // a NaN difference compares false and does not flag.
+    return (fabsf(a.x - r.x) > tau) || (fabsf(a.y - r.y) > tau) || (fabsf(a.z - r.z) > tau) ||
+           (fabsf(a.w - r.w) > tau);
+}
+
+// ------------------------------------------------------------------------------------------
+// Change detection on a planar frame: one thread per pixel, channels in groups of four.
+// Frame reads are coalesced per channel plane; the stored map is read and written as one
+// float4 per lane and group.  Each wave emits one 64-bit word of the change bitmap.
+// ------------------------------------------------------------------------------------------
+template <int HOLD>
+__global__ __launch_bounds__(kBlock) void detect_frame_kernel(const float *__restrict__ frame,
+                                                              float *__restrict__ ref,
+                                                              float *__restrict__ cur,
+                                                              uint64_t *__restrict__ bits, int C, int Cs,
+                                                              int N, int total, float tau, int force)
+{
+    const int g = blockIdx.x * kBlock + threadIdx.x;
+    bool flag = false;
+    if (g < total) {
+        const int st = g / N;
+        const int p = g - st * N;
+        const float *fp = frame + (size_t)st * C * N + p;
+        float4 *rp = reinterpret_cast<float4 *>(ref + (size_t)g * Cs);
+        float4 *cp = HOLD ? reinterpret_cast<float4 *>(cur + (size_t)g * Cs) : nullptr;
+        for (int c0 = 0; c0 < Cs; c0 += 4) {
+            float4 xv;
+            xv.x = fp[(size_t)c0 * N];
+            xv.y = (c0 + 1 < C) ? fp[(size_t)(c0 + 1) * N] : 0.0f;
+            xv.z = (c0 + 2 < C) ? fp[(size_t)(c0 + 2) * N] : 0.0f;
+            xv.w = (c0 + 3 < C) ? fp[(size_t)(c0 + 3) * N] : 0.0f;
+            if (!force) flag |= exceeds(xv, rp[c0 >> 2], tau);
+            if (HOLD)
+                cp[c0 >> 2] = xv;
+            else
+                rp[c0 >> 2] = xv;
+        }
+        if (force) flag = true;
+        if (HOLD && flag)
+            for (int c4 = 0; c4 < (Cs >> 2); ++c4) rp[c4] = cp[c4];
+    }
+    const uint64_t word = __ballot(flag);
+    const int g0 = g & ~63;
+    if ((threadIdx.x & 63) == 0 && g0 < total) bits[g0 >> 6] = word;
+}
+
+hipError_t detect_frame(hipStream_t st, const float *frame, float *ref, float *cur, uint64_t *bits, int C,
+                        int Cs, int N, int S, float tau, int hold, int force)
+{
+    const int total = S * N;
+    const int grid = (total + kBlock - 1) / kBlock;
+    if (hold)
+        hipLaunchKernelGGL(detect_frame_kernel<1>, dim3(grid), dim3(kBlock), 0, st, frame, ref, cur, bits, C,
+                           Cs, N, total, tau, force);
+    else
+        hipLaunchKernelGGL(detect_frame_kernel<0>, dim3(grid), dim3(kBlock), 0, st, frame, ref, cur, bits, C,
+                           Cs, N, total, tau, force);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Change detection map against map.  One workgroup per 64 pixels (one bitmap word); its
+// waves take turns over the 64*V float4 of those pixels, so every access is a fully
+// coalesced 1 KiB wave transaction.  A wave-wide ballot of "this float4 exceeded" is folded
+// into per-pixel flags by masking the ballot with each pixel's float4 range.
+// ------------------------------------------------------------------------------------------
+template <int HOLD>
+__global__ __launch_bounds__(1024) void detect_map_kernel(const float4 *__restrict__ x,
+                                                          float4 *__restrict__ ref,
+                                                          uint64_t *__restrict__ bits, int V, int total,
+                                                          float tau, int force)
+{
+    __shared__ uint64_t swords[16];
+    const int word = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int nw = blockDim.x >> 6;
+    const int px0 = word * 64;
+    const int npx = min(64, total - px0);
+    const size_t base = (size_t)px0 * V;
+    const int nf = npx * V;
+    const int lo0 = lane * V;
+    bool mine = false;
+    for (int t = wave; t * 64 < nf; t += nw) {
+        const int f = t * 64 + lane;
+        bool e = false;
+        if (f < nf) {
+            const float4 a = x[base + f];
+            if (!force) e = exceeds(a, ref[base + f], tau);
+            if (!HOLD) ref[base + f] = a;
+        }
+        const uint64_t B = __ballot(e);
+        int lo = lo0 - t * 64, hi = lo + V;
+        lo = max(lo, 0);
+        hi = min(hi, 64);
+        if (lo < hi) {
+            const int len = hi - lo;
+            const uint64_t mask = (len >= 64) ? ~0ull : (((1ull << len) - 1ull) << lo);
+            mine |= (B & mask) != 0ull;
+        }
+    }
+    if (force) mine = lane < npx;
+    uint64_t w = __ballot(mine);
+    if (nw > 1) {
+        if (lane == 0) swords[wave] = w;
+        __syncthreads();
+        w = 0;
+        for (int i = 0; i < nw; ++i) w |= swords[i];
+    }
+    if (threadIdx.x == 0) bits[word] = w;
+    if (HOLD) {
+        // refresh the stored input only at flagged pixels (all channels)
+        for (int f = threadIdx.x; f < nf; f += blockDim.x) {
+            const int px = f / V;
+            if ((w >> px) & 1ull) ref[base + f] = x[base + f];
+        }
+    }
+}
+
+hipError_t detect_map(hipStream_t st, const float *x, float *ref, uint64_t *bits, int Cs, int total, float tau,
+                      int hold, int force)
+{
+    const int V = Cs / 4;
+    const int words = (total + 63) / 64;
+    int nw = V < 16 ? V : 16;
+    if (nw < 1) nw = 1;
+    const float4 *x4 = reinterpret_cast<const float4 *>(x);
+    float4 *r4 = reinterpret_cast<float4 *>(ref);
+    if (hold)
+        hipLaunchKernelGGL(detect_map_kernel<1>, dim3(words), dim3(nw * 64), 0, st, x4, r4, bits, V, total, tau,
+                           force);
+    else
+        hipLaunchKernelGGL(detect_map_kernel<0>, dim3(words), dim3(nw * 64), 0, st, x4, r4, bits, V, total, tau,
+                           force);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Dilation.  An output position must be recomputed iff its receptive field contains a
+// changed input position.  One thread per output position tests, for each of the kh rows
+// of its field, the (clipped) run of kw bits of the change bitmap with two word reads.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t bit_run(const uint64_t *__restrict__ m, long long a, int len)
+{
+    const long long w = a >> 6;
+    const int o = (int)(a & 63);
+    uint64_t v = m[w] >> o;
+    if (o + len > 64) v |= m[w + 1] << (64 - o);
+    if (len < 64) v &= (1ull << len) - 1ull;
+    return v;
+}
+
+__device__ __forceinline__ bool field_changed(const uint64_t *__restrict__ m, const DilateGeom &g, int st,
+                                              int qy, int qx)
+{
+    const int x0 = max(qx * g.stride - g.pad, 0);
+    const int x1 = min(qx * g.stride - g.pad + g.kw - 1, g.W - 1);
+    if (x0 > x1) return false;
+    const int len = x1 - x0 + 1;
+    bool any = false;
+    for (int j = 0; j < g.kh; ++j) {
+        const int iy = qy * g.stride - g.pad + j;
+        if ((unsigned)iy < (unsigned)g.H) {
+            const long long a = ((long long)st * g.H + iy) * g.W + x0;
+            any |= bit_run(m, a, len) != 0ull;
+        }
+    }
+    return any;
+}
+
+__global__ __launch_bounds__(kBlock) void dilate_kernel(const uint64_t *__restrict__ chg,
+                                                        uint64_t *__restrict__ upd,
+                                                        uint64_t *__restrict__ pool, DilateGeom g,
+                                                        int upd_blocks)
+{
+    if ((int)blockIdx.x < upd_blocks) {
+        const int No = g.Ho * g.Wo;
+        const int total = g.S * No;
+        const int t = blockIdx.x * kBlock + threadIdx.x;
+        bool f = false;
+        if (t < total) {
+            const int st = t / No, q = t - st * No;
+            const int qy = q / g.Wo, qx = q - qy * g.Wo;
+            f = field_changed(chg, g, st, qy, qx);
+        }
+        const uint64_t word = __ballot(f);
+        const int t0 = t & ~63;
+        if ((threadIdx.x & 63) == 0 && t0 < total) upd[t0 >> 6] = word;
+    } else {
+        const int Np = g.Hp * g.Wp;
+        const int total = g.S * Np;
+        const int t = (blockIdx.x - upd_blocks) * kBlock + threadIdx.x;
+        bool f = false;
+        if (t < total) {
+            const int st = t / Np, q = t - st * Np;
+            const int py = q / g.Wp, px = q - py * g.Wp;
+            for (int a = 0; a < g.pool_k; ++a)
+                for (int b = 0; b < g.pool_k; ++b)
+                    f |= field_changed(chg, g, st, py * g.pool_k + a, px * g.pool_k + b);
+        }
+        const uint64_t word = __ballot(f);
+        const int t0 = t & ~63;
+        if ((threadIdx.x & 63) == 0 && t0 < total) pool[t0 >> 6] = word;
+    }
+}
+
+hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, uint64_t *pool_bits,
+                  const DilateGeom &g)
+{
+    const int ub = (g.S * g.Ho * g.Wo + kBlock - 1) / kBlock;
+    const int pb = (pool_bits && g.pool_k > 0) ? (g.S * g.Hp * g.Wp + kBlock - 1) / kBlock : 0;
+    hipLaunchKernelGGL(dilate_kernel, dim3(ub + pb), dim3(kBlock), 0, st, chg_bits, upd_bits, pool_bits, g, ub);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Change-index extraction.  Each workgroup owns kCompactWords bitmap words.  It obtains its
+// output offset by counting the set bits of all preceding words itself (the bitmaps are a
+// few KiB to a few hundred KiB and L2 resident, so this is cheaper and simpler than a second
+// launch or a cross-workgroup handshake, and it is deterministic), scans its own words'
+// popcounts, expands the bits into an LDS staging buffer and copies that out coalesced.
+// ------------------------------------------------------------------------------------------
+static constexpr int kCompactWords = 128;
+
+struct CompactJobs {
+    CompactJob j[3];
+};
+
+__device__ __forceinline__ int wave_incl_scan(int v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(v, d, 64);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+__global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
+{
+    __shared__ int stage[kCompactWords * 64];
+    __shared__ int swave[4];
+    __shared__ int swave2[4];
+    const CompactJob job = jobs.j[blockIdx.y];
+    const int w0 = blockIdx.x * kCompactWords;
+    if (w0 >= job.nwords) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // set bits in all words before this workgroup's
+    int before = 0;
+    for (int i = tid; i < w0; i += kBlock) before += __popcll(job.bits[i]);
+    before = wave_incl_scan(before, lane);
+    if (lane == 63) swave[wave] = before;
+
+    // this workgroup's words, one per thread of the first two waves
+    uint64_t mine = 0;
+    if (tid < kCompactWords && w0 + tid < job.nwords) mine = job.bits[w0 + tid];
+    const int cnt = __popcll(mine);
+    const int incl = wave_incl_scan(cnt, lane);
+    if (lane == 63) swave2[wave] = incl;
+    __syncthreads();
+    const int prefix = swave[0] + swave[1] + swave[2] + swave[3];
+    int off = incl - cnt;
+    for (int i = 0; i < wave; ++i) off += swave2[i];
+    const int total = swave2[0] + swave2[1] + swave2[2] + swave2[3];
+
+    const int pos0 = (w0 + tid) * 64;
+    while (mine) {
+        const int b = __ffsll((unsigned long long)mine) - 1;
+        stage[off++] = pos0 + b;
+        mine &= mine - 1ull;
+    }
+    __syncthreads();
+    for (int i = tid; i < total; i += kBlock) job.list[prefix + i] = stage[i];
+    if (tid == 0 && w0 + kCompactWords >= job.nwords) *job.count = prefix + total;
+}
+
+hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs)
+{
+    if (njobs < 1 || njobs > 3) return hipErrorInvalidValue;
+    CompactJobs js;
+    int maxw = 1;
+    for (int i = 0; i < 3; ++i) {
+        js.j[i] = jobs[i < njobs ? i : 0];
+        if (i < njobs && jobs[i].nwords > maxw) maxw = jobs[i].nwords;
+    }
+    const int gx = (maxw + kCompactWords - 1) / kCompactWords;
+    hipLaunchKernelGGL(compact_kernel, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Max-pooling at the listed pooled positions only: each is the maximum over its k x k window
+// of the stored (already updated, post-activation) map.  One thread per (position, 4 channels).
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restrict__ list,
+                                                             const int *__restrict__ count,
+                                                             const float4 *__restrict__ in,
+                                                             float4 *__restrict__ pooled, int V, int k, int Wo,
+                                                             int No, int Wp, int Np)
+{
+    const long long total = (long long)(*count) * V;
+    for (long long idx = (long long)blockIdx.x * kBlock + threadIdx.x; idx < total;
+         idx += (long long)gridDim.x * kBlock) {
+        const int u = (int)(idx / V), v = (int)(idx - (long long)u * V);
+        const int g = list[u];
+        const int st = g / Np, pp = g - st * Np;
+        const int py = pp / Wp, px = pp - py * Wp;
+        const long long base = (long long)st * No + (long long)(py * k) * Wo + px * k;
+        float4 m = in[base * V + v];
+        for (int j = 0; j < k; ++j)
+            for (int i = 0; i < k; ++i) {
+                const float4 a = in[(base + (long long)j * Wo + i) * V + v];
+                m.x = fmaxf(m.x, a.x);
+                m.y = fmaxf(m.y, a.y);
+                m.z = fmaxf(m.z, a.z);
+                m.w = fmaxf(m.w, a.w);
+            }
+        pooled[(long long)g * V + v] = m;
+    }
+}
+
+hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const float *in,
+                       float *pooled, int Ms, int k, int Wo, int No, int Wp, int Np)
+{
+    const int V = Ms / 4;
+    long long work = (long long)max_count * V;
+    long long grid = (work + kBlock - 1) / kBlock;
+    if (grid > 2048) grid = 2048;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(pool_sparse_kernel, dim3((int)grid), dim3(kBlock), 0, st, list, count,
+                       reinterpret_cast<const float4 *>(in), reinterpret_cast<float4 *>(pooled), V, k, Wo, No, Wp,
+                       Np);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Stored map [S*No][Ms] -> planar [S][M][No].  Consecutive lanes take consecutive pixels of
+// one channel plane so the planar writes are coalesced.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void map_to_planar_kernel(const float *__restrict__ map,
+                                                               float *__restrict__ planar, int M, int Ms,
+                                                               int No, long long total)
+{
+    for (long long idx = (long long)blockIdx.x * kBlock + threadIdx.x; idx < total;
+         idx += (long long)gridDim.x * kBlock) {
+        const int q = (int)(idx % No);
+        const long long sc = idx / No;
+        const int c = (int)(sc % M);
+        const long long st = sc / M;
+        planar[idx] = map[(st * No + q) * Ms + c];
+    }
+}
+
+hipError_t map_to_planar(hipStream_t st, const float *map, float *planar, int M, int Ms, int No, int S)
+{
+    const long long total = (long long)S * M * No;
+    long long grid = (total + kBlock - 1) / kBlock;
+    if (grid > 4096) grid = 4096;
+    hipLaunchKernelGGL(map_to_planar_kernel, dim3((int)grid), dim3(kBlock), 0, st, map, planar, M, Ms, No, total);
+    return hipGetLastError();
+}
+
+__global__ void iota_kernel(int *list, int n)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) list[i] = i;
+}
+
+hipError_t fill_iota(hipStream_t st, int *list, int n)
+{
+    int grid = (n + 255) / 256;
+    if (grid > 1024) grid = 1024;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(iota_kernel, dim3(grid), dim3(256), 0, st, list, n);
+    return hipGetLastError();
+}
+
+} // namespace cbk
