@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -41,6 +42,7 @@ struct Op {
     int kh = 1, kw = 1, stride = 1, pad = 0, relu = 0, dense = 0;
     float tau = 0.f;
     int K = 0, Kpad = 0, Mpad = 0;
+    int gemm_grid = 0;
     int pool_after = -1; // CONV: index of the pooling op that directly follows, or -1
     int conv_before = -1; // MAXPOOL: index of the conv it follows
     // workspace offsets (bytes); SIZE_MAX = absent
@@ -53,7 +55,8 @@ struct Plan {
     std::vector<Op> ops;
     int S = 1, in_c = 0, in_h = 0, in_w = 0;
     bool hold = false;
-    size_t o_iota = 0, o_const = 0;
+    size_t o_iota = 0, o_const = 0, o_partial = 0;
+    int gemm_split = 0; // forced K split (tuning), 0 = automatic
     int iota_len = 0;
     size_t bytes = 0;
 };
@@ -179,6 +182,12 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
     P.iota_len = (int)max_px;
     P.o_iota = cv.take((size_t)P.iota_len * 4);
     P.o_const = cv.take(P.ops.size() * 2 * 4);
+    {
+        size_t pb = 0;
+        for (const Op &op : P.ops)
+            if (op.kind == CBINFER_OP_CONV) pb = std::max(pb, cbk::gemm_partial_bytes(op.M));
+        P.o_partial = cv.take(pb);
+    }
     P.bytes = cv.off;
     return CBINFER_OK;
 }
@@ -371,9 +380,16 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             a.stride = op.stride; a.pad = op.pad; a.Cs = op.Cs; a.Kpad = op.Kpad;
             a.M = op.M; a.Mpad = op.Mpad; a.Ms = op.Ms; a.relu = op.relu;
             a.max_pixels = S * No;
+            a.partial = s->at<float>(P.o_partial);
+            a.split_override = P.gemm_split;
+            a.grid = op.gemm_grid;
             {
                 StepTimer t(s, l, CBINFER_STEP_GEMM);
                 HIP_TRY(cbk::gemm_gather(st, a));
+            }
+            if (cbk::gemm_can_split(a)) {
+                StepTimer t(s, l, CBINFER_STEP_UPDATE);
+                HIP_TRY(cbk::output_update(st, a));
             }
         } else {
             const Op &cv = P.ops[op.conv_before];
@@ -442,6 +458,15 @@ cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold)
         }
         s->ws = static_cast<char *>(p);
         s->owns_ws = true;
+    }
+    if (const char *e = getenv("CBINFER_GEMM_SPLIT")) s->plan.gemm_split = atoi(e) > 0 ? atoi(e) : 0;
+    for (Op &op : s->plan.ops) {
+        if (op.kind != CBINFER_OP_CONV) continue;
+        cbk::GemmArgs a{};
+        a.M = op.M; a.Mpad = op.Mpad; a.Kpad = op.Kpad;
+        a.max_pixels = P.S * op.Ho * op.Wo;
+        a.split_override = s->plan.gemm_split;
+        op.gemm_grid = cbk::gemm_grid(a);
     }
     s->prof_ms.assign(P.ops.size() * CBINFER_STEP_COUNT, 0.0);
     s->prof_n.assign(P.ops.size() * CBINFER_STEP_COUNT, 0);

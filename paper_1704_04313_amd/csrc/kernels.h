@@ -57,13 +57,22 @@ struct GemmArgs {
     const int *count;   // their number (device)
     float *out;         // stored output map [S*No][Ms]
     int N, H, W, No, Wo, stride, pad, Cs, Kpad, M, Mpad, Ms, relu;
-    int max_pixels;     // upper bound of *count (sizes the grid)
+    int max_pixels;     // upper bound of *count
+    float *partial;     // scratch for K-split partial sums, gemm_partial_bytes(M) bytes
+    int split_override; // 0: automatic K split; > 0: forced split factor (tuning)
+    int grid;           // workgroups to launch, from gemm_grid()
 };
-// Tile variant chosen from M; returns the channel tile BM through *bm when args == nullptr.
-int gemm_channel_tile(int M);
-int gemm_k_multiple(void);
-hipError_t gemm_prepare(void); // one-time function attributes (dynamic LDS size)
+int gemm_channel_tile(int M);   // channel tile BM used for M output channels (Mpad = M rounded up to it)
+int gemm_k_multiple(void);      // Kpad must be a multiple of this
+size_t gemm_partial_bytes(int M);
+int gemm_grid(const GemmArgs &a);
+bool gemm_can_split(const GemmArgs &a);
+hipError_t gemm_prepare(void);  // one-time function attributes (dynamic LDS size)
+// The multiplication.  With enough listed pixels it also performs the output update (bias,
+// activation, scatter); with few it splits K over more workgroups, writes partial sums to
+// a.partial, and output_update() -- which must then be enqueued right after it -- finishes.
 hipError_t gemm_gather(hipStream_t st, const GemmArgs &a);
+hipError_t output_update(hipStream_t st, const GemmArgs &a);
 
 // ---- max-pooling at listed pooled positions -----------------------------------------------
 hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const float *in,
