@@ -48,7 +48,9 @@ _lib = None
 
 
 def library_path() -> str:
-    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcbinfer_hip.so")
+    """The in-tree build, or another build of the same library named by CBINFER_LIBRARY."""
+    return os.environ.get("CBINFER_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                                                             "libcbinfer_hip.so")
 
 
 def load_library():
