@@ -144,13 +144,10 @@ enum {
     CBINFER_STEP_DETECT = 0,  /* change detection + update of the stored previous input */
     CBINFER_STEP_DILATE = 1,  /* change map -> map of outputs to update (and of pooled outputs) */
     CBINFER_STEP_COMPACT = 2, /* maps -> ascending index lists and counts */
-    CBINFER_STEP_GEMM = 3,    /* gathered matrix generation + multiplication (+ output update when
-                                 the multiplication is not split along K) */
+    CBINFER_STEP_GEMM = 3,    /* gathered matrix generation + multiplication + output update */
     CBINFER_STEP_POOL = 4,    /* max-pooling at the listed pooled positions */
     CBINFER_STEP_OUTPUT = 5,  /* copy of the last stored map to the caller's buffer (layer = last) */
-    CBINFER_STEP_UPDATE = 6,  /* output update after a K-split multiplication: sum of partial
-                                 results, bias, ReLU, scatter into the stored map */
-    CBINFER_STEP_COUNT = 7
+    CBINFER_STEP_COUNT = 6
 };
 
 /* enable != 0: bracket every kernel launch of later frames with HIP events on the state's

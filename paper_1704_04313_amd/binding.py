@@ -14,7 +14,7 @@ F32, BF16 = 0, 1
 FLAG_HOLD_REFERENCE = 1
 LIST_CHANGED, LIST_UPDATE = 0, 1
 MAP_REFERENCE, MAP_OUTPUT = 0, 1
-STEP_NAMES = ["detect", "dilate", "compact", "gemm", "pool", "output", "update"]
+STEP_NAMES = ["detect", "dilate", "compact", "gemm", "pool", "output"]
 
 EXPORTS = [
     "cbinfer_workspace_bytes", "cbinfer_create", "cbinfer_process_frame", "cbinfer_reset",

@@ -13,6 +13,24 @@
 #include <string>
 #include <vector>
 
+#ifdef CBK_TRACE
+// timing study builds only
+static unsigned long long *g_trace = nullptr;
+static unsigned long long *cbk_trace_buffer()
+{
+    if (!g_trace) {
+        (void)hipMalloc(&g_trace, 1024 * 2 * 16 * 8);
+        (void)hipMemset(g_trace, 0, 1024 * 2 * 16 * 8);
+    }
+    return g_trace;
+}
+extern "C" int cbinfer_debug_read_trace(unsigned long long *host)
+{
+    (void)hipDeviceSynchronize();
+    return (int)hipMemcpy(host, cbk_trace_buffer(), 1024 * 2 * 16 * 8, hipMemcpyDeviceToHost);
+}
+#endif
+
 namespace {
 
 thread_local std::string g_err = "";
@@ -29,6 +47,7 @@ int fail(int code, const char *fmt, ...)
 }
 
 constexpr size_t kAlign = 256;
+constexpr int kMaxGemmGrid = 256; // workgroups of one GEMM launch (one per compute unit of an MI355X)
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline int words_for(long long bits) { return (int)((bits + 63) / 64); }
@@ -55,8 +74,8 @@ struct Plan {
     std::vector<Op> ops;
     int S = 1, in_c = 0, in_h = 0, in_w = 0;
     bool hold = false;
-    size_t o_iota = 0, o_const = 0, o_partial = 0;
-    int gemm_split = 0; // forced K split (tuning), 0 = automatic
+    size_t o_iota = 0, o_const = 0, o_partial = 0, o_tickets = 0;
+    int compute_units = 256; // sizes the GEMM grids; the device's count replaces it in cbinfer_create
     int iota_len = 0;
     size_t bytes = 0;
 };
@@ -183,10 +202,12 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
     P.o_iota = cv.take((size_t)P.iota_len * 4);
     P.o_const = cv.take(P.ops.size() * 2 * 4);
     {
+        // sized for the largest grid the GEMM may use (its cap), whatever the device turns out to be
         size_t pb = 0;
         for (const Op &op : P.ops)
-            if (op.kind == CBINFER_OP_CONV) pb = std::max(pb, cbk::gemm_partial_bytes(op.M));
+            if (op.kind == CBINFER_OP_CONV) pb = std::max(pb, cbk::gemm_partial_bytes(op.M, kMaxGemmGrid));
         P.o_partial = cv.take(pb);
+        P.o_tickets = cv.take(cbk::gemm_ticket_bytes(kMaxGemmGrid));
     }
     P.bytes = cv.off;
     return CBINFER_OK;
@@ -381,15 +402,14 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             a.M = op.M; a.Mpad = op.Mpad; a.Ms = op.Ms; a.relu = op.relu;
             a.max_pixels = S * No;
             a.partial = s->at<float>(P.o_partial);
-            a.split_override = P.gemm_split;
+            a.tickets = s->at<int>(P.o_tickets);
             a.grid = op.gemm_grid;
+#ifdef CBK_TRACE
+            a.trace = cbk_trace_buffer();
+#endif
             {
                 StepTimer t(s, l, CBINFER_STEP_GEMM);
                 HIP_TRY(cbk::gemm_gather(st, a));
-            }
-            if (cbk::gemm_can_split(a)) {
-                StepTimer t(s, l, CBINFER_STEP_UPDATE);
-                HIP_TRY(cbk::output_update(st, a));
             }
         } else {
             const Op &cv = P.ops[op.conv_before];
@@ -459,14 +479,18 @@ cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold)
         s->ws = static_cast<char *>(p);
         s->owns_ws = true;
     }
-    if (const char *e = getenv("CBINFER_GEMM_SPLIT")) s->plan.gemm_split = atoi(e) > 0 ? atoi(e) : 0;
+    {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            s->plan.compute_units = cus < kMaxGemmGrid ? cus : kMaxGemmGrid;
+    }
     for (Op &op : s->plan.ops) {
         if (op.kind != CBINFER_OP_CONV) continue;
         cbk::GemmArgs a{};
         a.M = op.M; a.Mpad = op.Mpad; a.Kpad = op.Kpad;
         a.max_pixels = P.S * op.Ho * op.Wo;
-        a.split_override = s->plan.gemm_split;
-        op.gemm_grid = cbk::gemm_grid(a);
+        op.gemm_grid = cbk::gemm_grid(a, s->plan.compute_units);
     }
     s->prof_ms.assign(P.ops.size() * CBINFER_STEP_COUNT, 0.0);
     s->prof_n.assign(P.ops.size() * CBINFER_STEP_COUNT, 0);

@@ -58,21 +58,22 @@ struct GemmArgs {
     float *out;         // stored output map [S*No][Ms]
     int N, H, W, No, Wo, stride, pad, Cs, Kpad, M, Mpad, Ms, relu;
     int max_pixels;     // upper bound of *count
-    float *partial;     // scratch for K-split partial sums, gemm_partial_bytes(M) bytes
-    int split_override; // 0: automatic K split; > 0: forced split factor (tuning)
+    float *partial;     // scratch for partial accumulators, gemm_partial_bytes(M, grid) bytes
+    int *tickets;       // gemm_ticket_bytes(grid) bytes, zero before the first launch (each launch
+                        // leaves them zero again)
     int grid;           // workgroups to launch, from gemm_grid()
+#ifdef CBK_TRACE
+    unsigned long long *trace; // timing study builds only: [grid][2 roles][16] timestamps
+#endif
 };
 int gemm_channel_tile(int M);   // channel tile BM used for M output channels (Mpad = M rounded up to it)
 int gemm_k_multiple(void);      // Kpad must be a multiple of this
-size_t gemm_partial_bytes(int M);
-int gemm_grid(const GemmArgs &a);
-bool gemm_can_split(const GemmArgs &a);
+int gemm_grid(const GemmArgs &a, int compute_units); // needs M, Mpad, Kpad, max_pixels
+size_t gemm_partial_bytes(int M, int grid);
+size_t gemm_ticket_bytes(int grid);
 hipError_t gemm_prepare(void);  // one-time function attributes (dynamic LDS size)
-// The multiplication.  With enough listed pixels it also performs the output update (bias,
-// activation, scatter); with few it splits K over more workgroups, writes partial sums to
-// a.partial, and output_update() -- which must then be enqueued right after it -- finishes.
+// Matrix generation, multiplication and output update (bias, activation, scatter) in one launch.
 hipError_t gemm_gather(hipStream_t st, const GemmArgs &a);
-hipError_t output_update(hipStream_t st, const GemmArgs &a);
 
 // ---- max-pooling at listed pooled positions -----------------------------------------------
 hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const float *in,

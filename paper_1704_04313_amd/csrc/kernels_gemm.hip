@@ -2,10 +2,11 @@
 //
 // Section 3.1 of the paper assembles only the columns of the image matrix X that belong to
 // output positions needing an update, multiplies them with the unchanged filter matrix K and
-// writes the result (with the activation) over the stored output.  Here matrix generation and
-// multiplication are one kernel: a workgroup owns BN listed output positions x BM output
-// channels and builds the BN x 32 slices of the reduced X directly in LDS by gathering 16-byte
-// channel groups from the channel-contiguous input map; the reduced X never exists in HBM.
+// writes the result (with the activation) over the stored output.  Here the three steps are one
+// kernel: a workgroup owns BN listed output positions x BM output channels, builds the BN x 32
+// slices of the reduced X directly in LDS by gathering 16-byte channel groups from the
+// channel-contiguous input map, multiplies on the matrix cores and scatters bias + ReLU results
+// straight into the stored map.  The reduced X never exists in HBM.
 //
 // The workgroup has eight waves with two roles.  Waves 4-7 ("producers") compute gather
 // addresses, load the next K slice of both operands from global memory and store it to LDS;
@@ -13,6 +14,14 @@
 // fp32 accumulate).  One producer and one consumer wave share each SIMD, so address
 // arithmetic, global-load latency and LDS stores overlap the matrix pipeline instead of
 // draining it once per slice.
+//
+// Work distribution: one workgroup per compute unit.  Output tiles are dealt out whole as long
+// as every workgroup gets one; the (tiles mod workgroups) left over are cut along K into
+// equal iteration ranges, one per workgroup, so that all compute units finish together whatever
+// the list length is.  A workgroup that computed only part of a tile's K range stores its
+// partial accumulators; the last workgroup to finish a tile (an atomic ticket, nobody waits)
+// adds all parts in ascending K order, which keeps results deterministic, and performs the
+// output update.
 #include "kernels.h"
 
 #include <cstdio>
@@ -22,53 +31,77 @@ namespace cbk {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+#ifdef CBK_TRACE
+// timing study builds only: lane 0 of wave 0 (consumer) and of wave 4 (producer) stamp events
+#define CBK_STAMP(slot)                                                                         \
+    do {                                                                                        \
+        if (lane == 0 && (wave == 0 || wave == 4) && (slot) < 16)                               \
+            a.trace[((size_t)blockIdx.x * 2 + (wave >> 2)) * 16 + (slot)] = wall_clock64();      \
+    } while (0)
+#else
+#define CBK_STAMP(slot) do { } while (0)
+#endif
+
 static constexpr int BK = 32;       // K slice per pipeline stage (floats)
 static constexpr int LDK = BK + 4;  // LDS row pitch: 36 floats keeps 16-byte alignment and makes
                                     // the rows read by one ds_read_b128 phase hit distinct banks
 static constexpr int NT = 512;      // threads per workgroup: 4 consumer + 4 producer waves
 static constexpr int NPROD = 256;   // producer threads
-static constexpr int kMaxSplit = 16;   // deepest K split
-static constexpr int kMaxItems = 1024; // most work items a split multiplication may create
-static constexpr int kCUs = 256;       // compute units of an MI355X; one workgroup each
-static constexpr int kStages = 3;      // K slices resident in LDS
+static constexpr int NCONS = 256;   // consumer threads
+static constexpr int kStages = 3;   // K slices resident in LDS
+static constexpr int kMinIters = 4; // shortest K range worth giving to a workgroup
+static constexpr int kMaxGrid = 1024;
 
 template <int BM, int BN>
 struct TileSmem {
     static constexpr int a_floats = BN * LDK;
     static constexpr int b_floats = BM * LDK;
-    static constexpr int bytes = kStages * (a_floats + b_floats) * 4 + BN * 4;
+    static constexpr int bytes = kStages * (a_floats + b_floats) * 4 + BN * 4 + 16;
 };
 
-// How many K ranges a tile's contraction is split into.  A function of the tile count and
-// the K length only, so that the multiplication kernel and the output-update kernel (and two
-// runs on the same input) always agree.  With few listed pixels there are too few tiles to
-// occupy 256 compute units; splitting K restores the parallelism at the price of writing
-// partial sums that the output update adds up in a fixed order (deterministic results).
-// Picks the split with the least (rounds over the compute units) x (slices per item + fixed
-// cost of starting and finishing an item).
-__host__ __device__ inline int choose_split(int tiles, int nk, int split_override)
+// The split of one launch's work over W workgroups; a pure function of its arguments.
+struct Schedule {
+    int tiles;       // output tiles: pixel tiles x channel tiles (channel tile fastest)
+    int whole;       // rounds in which every workgroup takes one whole tile
+    int rem;         // tiles left over, shared along K
+    int wr;          // workgroups sharing the left-over tiles
+    long long iters; // rem * nk: K-slice iterations of the left-over tiles
+};
+
+__device__ __forceinline__ Schedule make_schedule(int n, int bn, int mtiles, int nk, int W)
 {
-    int smax = nk / 4;
-    if (smax > kMaxSplit) smax = kMaxSplit;
-    if (smax < 1) smax = 1;
-    if (tiles < 1) return 1;
-    int best = 1;
-    if (split_override > 0) {
-        best = split_override < smax ? split_override : smax;
-    } else {
-        if (tiles >= 4 * kCUs) return 1;
-        long long best_cost = -1;
-        for (int s = 1; s <= smax; ++s) {
-            const long long rounds = ((long long)tiles * s + kCUs - 1) / kCUs;
-            const long long cost = rounds * ((nk + s - 1) / s + 2);
-            if (best_cost < 0 || cost < best_cost) {
-                best_cost = cost;
-                best = s;
-            }
-        }
+    Schedule s;
+    s.tiles = ((n + bn - 1) / bn) * mtiles;
+    s.whole = s.tiles / W;
+    s.rem = s.tiles - s.whole * W;
+    s.iters = (long long)s.rem * nk;
+    // Cut every left-over tile into the same number of parts if that occupies at least 7/8 of
+    // the workgroups (ranges then start on tile boundaries: one segment per workgroup); otherwise
+    // deal the iterations out evenly over all workgroups.  Never make parts shorter than
+    // kMinIters slices.
+    const int max_parts = nk / kMinIters > 1 ? nk / kMinIters : 1;
+    int wr = 1;
+    if (s.rem > 0) {
+        int p = W / s.rem;
+        if (p > max_parts) p = max_parts;
+        if (p < 1) p = 1;
+        wr = s.rem * p;
+        if (wr * 8 < W * 7 && (long long)s.rem * max_parts >= W) wr = W;
+        if (wr > W) wr = W;
     }
-    while (best > 1 && (long long)best * tiles > kMaxItems) --best;
-    return best;
+    s.wr = wr;
+    return s;
+}
+
+// First iteration of workgroup w's share, and the workgroup owning an iteration.
+__device__ __forceinline__ long long share_begin(const Schedule &s, int w) { return s.iters * w / s.wr; }
+
+__device__ __forceinline__ int share_owner(const Schedule &s, long long it)
+{
+    int w = (int)(it * s.wr / s.iters);
+    while (w + 1 < s.wr && share_begin(s, w + 1) <= it) ++w;
+    while (w > 0 && share_begin(s, w) > it) --w;
+    return w;
 }
 
 // Image-matrix rows gathered by one producer thread for one K slice: PA rows (32 apart), one
@@ -127,47 +160,88 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     constexpr int PA = BN / 32;      // image-matrix rows staged per producer thread and slice
     constexpr int PB = (BM + 31) / 32;
     constexpr int ASZ = BN * LDK, BSZ = BM * LDK;
+    constexpr int SLAB = BM * BN; // floats of one partial-accumulator slab
     static_assert(TP >= 1 && TC >= 1, "tile too small");
     static_assert(BK == 32, "two 16-wide fragment groups per slice");
+    static_assert(TC * TP * 4 * NCONS == SLAB, "a slab holds every consumer lane's accumulators");
 
     extern __shared__ __align__(16) float smem[];
-    float *As = smem;                                    // [3][BN][LDK]  gathered image-matrix slices
-    float *Bs = smem + kStages * ASZ;                    // [3][BM][LDK]  filter-matrix slices
+    float *As = smem;                                      // [3][BN][LDK]  gathered image-matrix slices
+    float *Bs = smem + kStages * ASZ;                      // [3][BM][LDK]  filter-matrix slices
     int *sU = reinterpret_cast<int *>(Bs + kStages * BSZ); // [BN] listed pixels of this tile (-1: none)
+    int *sFlag = sU + BN;                                  // ticket of the tile just finished
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const bool producer = wave >= 4;
 
+    CBK_STAMP(0);
     const int n = *a.count;
     const int mtiles = a.Mpad / BM;
-    const int ptiles = (n + BN - 1) / BN;
     const int nk = a.Kpad / BK;
-    const int S = choose_split(ptiles * mtiles, nk, a.split_override);
-    const int items = ptiles * mtiles * S;
-    // Consecutive work items share their gathered pixels (channel tiles of one pixel tile) or
-    // their filter slice; give each XCD (workgroups are dealt round-robin over the 8 XCDs) one
-    // contiguous range of items so that this sharing happens inside one L2.
-    const int per_xcd = (items + 7) / 8;
+    const int W = gridDim.x;
+    const Schedule sch = make_schedule(n, BN, mtiles, nk, W);
+    if (sch.tiles == 0) return;
+    // Workgroups are dealt round-robin over the 8 XCDs.  Number them so that each XCD works on a
+    // contiguous range of tiles / iterations: neighbours share gathered pixels (channel tiles of
+    // one pixel tile) or filter slices, and that sharing then happens inside one L2.
+    const int w = (int)(blockIdx.x & 7) * (W >> 3) + (int)(blockIdx.x >> 3);
+    const bool xcd_ranges = (sch.wr & 7) == 0;
+    const int wsh = xcd_ranges ? (int)(blockIdx.x & 7) * (sch.wr >> 3) + (int)(blockIdx.x >> 3)
+                               : (int)blockIdx.x; // number inside the K-sharing group
+    const bool sharing =
+        sch.rem > 0 && (xcd_ranges ? (int)(blockIdx.x >> 3) < (sch.wr >> 3) : (int)blockIdx.x < sch.wr);
+    const long long it_begin = sharing ? share_begin(sch, wsh) : 0;
+    const long long it_end = sharing ? share_begin(sch, wsh + 1) : 0;
 
-    for (int b = blockIdx.x; b < per_xcd * 8; b += gridDim.x) {
-        const int item = (b & 7) * per_xcd + (b >> 3);
-        if (item >= items) continue;
-        const int mt = item % mtiles;
-        const int ks = (item / mtiles) % S;
-        const int pt = item / (mtiles * S);
-        const int kc0 = (int)((long long)ks * nk / S);
-        const int kc1 = (int)((long long)(ks + 1) * nk / S);
+    int round = 0;
+    long long it = it_begin;
+    int seg = 0;
+    CBK_STAMP(1);
+    while (true) {
+        // ---- next segment of this workgroup: a whole tile, or part of a shared tile's K range
+        int tile, kc0, kc1, shared_j = -1;
+        if (round < sch.whole) {
+            tile = round * W + w;
+            kc0 = 0;
+            kc1 = nk;
+            ++round;
+        } else if (it < it_end) {
+            shared_j = (int)(it / nk);
+            kc0 = (int)(it - (long long)shared_j * nk);
+            const long long left = it_end - it;
+            kc1 = (left < nk - kc0) ? kc0 + (int)left : nk;
+            tile = sch.whole * W + shared_j;
+            it += kc1 - kc0;
+        } else {
+            break;
+        }
+        const int pt = tile / mtiles;
+        const int mt = tile - pt * mtiles;
+        const bool partial = (kc1 - kc0) != nk;
 
-        __syncthreads(); // the previous item's LDS reads are done
+        CBK_STAMP(2 + 6 * seg);
+        __syncthreads(); // the previous segment's LDS reads are done
         for (int i = tid; i < BN; i += NT) {
             const int u = pt * BN + i;
             sU[i] = (u < n) ? a.list[u] : -1;
         }
         __syncthreads();
 
-        // Both roles execute the same number of barriers: one after the prologue and one per slice.
+        // consumer coordinates (used again after the role-specific loops)
+        const int cw = wave & 3;
+        const int wpx0 = (cw % WN) * (BN / WN);
+        const int wch0 = (cw / WN) * (BM / WM);
+        const int lrow = lane & 15; // row of the 16-row operand tiles this lane feeds
+        const int lk = lane >> 4;   // k slot this lane feeds
+        floatx4 acc[TC][TP];
+#pragma unroll
+        for (int j = 0; j < TC; ++j)
+#pragma unroll
+            for (int i = 0; i < TP; ++i) acc[j][i] = (floatx4){0.f, 0.f, 0.f, 0.f};
+
+        // Both roles execute the same number of barriers: one after the prologue, one per slice.
         if (producer) {
             const int ptid = tid & (NPROD - 1);
             const int v = ptid & 7;   // float4 column inside the K slice
@@ -191,7 +265,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             const float *wrow = a.wt + (size_t)(mt * BM + r0) * a.Kpad + v * 4;
             const int2 *taps = a.taps + v;
             floatx4 ra[PA], rb[PB], ra2[PA], rb2[PB];
-            // prologue: slices kc0 and kc0+1 into ring slots 0 and 1, slice kc0+2 into registers
+            // prologue: slices kc0 and kc0+1 into ring slots 0 and 1, slice kc0+2 into registers.
+            // The tap descriptor of a slice is loaded ahead of the operand loads that need it.
             const int2 t0 = taps[kc0 * (BK / 4)];
             const int2 t1 = taps[(kc0 + 1 < kc1 ? kc0 + 1 : kc0) * (BK / 4)];
             int2 tp = taps[(kc0 + 2 < kc1 ? kc0 + 2 : kc0) * (BK / 4)];
@@ -209,13 +284,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 if (kc0 + 3 < kc1) tp = taps[(kc0 + 3) * (BK / 4)];
             }
             __syncthreads();
+            CBK_STAMP(3 + 6 * seg);
             int slot = 2; // ring slot of slice kc+2
             for (int kc = kc0; kc < kc1; ++kc) {
-#ifdef CBK_EXP_NOPRODUCER
-                if (false) {
-#else
                 if (kc + 2 < kc1) {
-#endif
                     stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, v, ra, rb);
                     if (kc + 3 < kc1) {
                         gather_rows<PA>(a, tp, iy0, ix0, base, ra);
@@ -224,20 +296,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                     }
                 }
                 slot = slot == kStages - 1 ? 0 : slot + 1;
-#ifndef CBK_EXP_NOBARRIER
                 __syncthreads();
-#endif
             }
         } else {
-            const int wpx0 = (wave % WN) * (BN / WN);
-            const int wch0 = (wave / WN) * (BM / WM);
-            const int lrow = lane & 15; // row of the 16-row operand tiles this lane feeds
-            const int lk = lane >> 4;   // k slot this lane feeds
-            floatx4 acc[TC][TP];
-#pragma unroll
-            for (int j = 0; j < TC; ++j)
-#pragma unroll
-                for (int i = 0; i < TP; ++i) acc[j][i] = (floatx4){0.f, 0.f, 0.f, 0.f};
             const float *A0 = As + (wpx0 + lrow) * LDK + lk * 4;
             const float *B0 = Bs + (wch0 + lrow) * LDK + lk * 4;
             // Each lane reads four consecutive k of its row; MFMA step s then contracts
@@ -264,6 +325,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                                                                              0, 0, 0);
             };
             __syncthreads();
+            CBK_STAMP(3 + 6 * seg);
+            // the wave feeding the matrix pipeline wins instruction-issue arbitration on its SIMD
+            __builtin_amdgcn_s_setprio(3);
             read_frags(0, 0, 0);
             int slot = 0; // ring slot of slice kc
             for (int kc = kc0; kc < kc1; ++kc) {
@@ -271,108 +335,105 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 // The scheduling barriers pin the order "issue the LDS reads of the next fragment
                 // group, then the 64 MFMAs of the current one", so that LDS latency and bandwidth
                 // are spent while the matrix pipeline is busy.
-#ifndef CBK_EXP_NOLDSREAD
                 read_frags(1, slot, 1);
-#endif
                 __builtin_amdgcn_sched_barrier(0);
                 multiply(0);
                 __builtin_amdgcn_sched_barrier(0);
-#ifndef CBK_EXP_NOLDSREAD
                 if (kc + 1 < kc1) read_frags(0, nslot, 0);
-#endif
                 __builtin_amdgcn_sched_barrier(0);
                 multiply(1);
                 __builtin_amdgcn_sched_barrier(0);
                 slot = nslot;
-#ifndef CBK_EXP_NOBARRIER
                 __syncthreads();
-#endif
             }
+            __builtin_amdgcn_s_setprio(0);
+        }
 
-            if (S == 1) {
-                // Output update fused: bias, activation, scatter to the stored map.
-#pragma unroll
-                for (int j = 0; j < TC; ++j) {
-                    const int ch = mt * BM + wch0 + j * 16 + lk * 4;
-                    const float4 bv = *reinterpret_cast<const float4 *>(a.bias + ch);
-#pragma unroll
-                    for (int i = 0; i < TP; ++i) {
-                        const int g = sU[wpx0 + i * 16 + lrow];
-                        if (g >= 0 && ch < a.Ms) {
-                            float4 o;
-                            o.x = acc[j][i][0] + bv.x;
-                            o.y = acc[j][i][1] + bv.y;
-                            o.z = acc[j][i][2] + bv.z;
-                            o.w = acc[j][i][3] + bv.w;
-                            if (a.relu) {
-                                o.x = fmaxf(o.x, 0.f);
-                                o.y = fmaxf(o.y, 0.f);
-                                o.z = fmaxf(o.z, 0.f);
-                                o.w = fmaxf(o.w, 0.f);
-                            }
-                            *reinterpret_cast<float4 *>(a.out + (size_t)g * a.Ms + ch) = o;
-                        }
-                    }
-                }
-            } else {
-                // Partial sums of this K range, [pixel][channel] inside the item's slab.
-                float *slab = a.partial + (size_t)item * (BN * BM);
+        // ---- a shared tile: store this K range's accumulators, take a ticket; the workgroup
+        //      holding the last ticket adds up all ranges (ascending K) and does the output update.
+        //      Slab traffic uses device-scope atomic stores and loads (write-through / read at the
+        //      level all XCDs share), completed before the ticket is taken, so no cache-wide
+        //      write-back or invalidate is needed to make the parts visible across XCDs.
+        CBK_STAMP(4 + 6 * seg);
+        bool finish = true;
+        if (partial) {
+            const long long t0 = (long long)shared_j * nk;
+            const int w_first = share_owner(sch, t0);
+            const int w_last = share_owner(sch, t0 + nk - 1);
+            const int ctid = tid & (NCONS - 1);
+            if (!producer) {
+                // slab 2*wsh + (0: first tile this workgroup touches, 1: a later one), register layout
+                const int first_j = (int)(it_begin / nk);
+                float *slab = a.partial + (size_t)(2 * wsh + (shared_j == first_j ? 0 : 1)) * SLAB;
 #pragma unroll
                 for (int j = 0; j < TC; ++j)
 #pragma unroll
-                    for (int i = 0; i < TP; ++i) {
-                        float4 o;
-                        o.x = acc[j][i][0];
-                        o.y = acc[j][i][1];
-                        o.z = acc[j][i][2];
-                        o.w = acc[j][i][3];
-                        *reinterpret_cast<float4 *>(slab + (wpx0 + i * 16 + lrow) * BM + wch0 + j * 16 + lk * 4) = o;
+                    for (int i = 0; i < TP; ++i)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            __hip_atomic_store(slab + ((j * TP + i) * 4 + r) * NCONS + ctid, acc[j][i][r],
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // all of this lane's slab stores have reached the device-coherent level
+                __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
+            }
+            __syncthreads();
+            if (tid == 0)
+                *sFlag = __hip_atomic_fetch_add(a.tickets + shared_j, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            CBK_STAMP(5 + 6 * seg);
+            finish = (*sFlag == w_last - w_first);
+            if (finish) {
+                if (tid == 0) a.tickets[shared_j] = 0; // ready for the next launch
+                if (!producer) {
+#pragma unroll
+                    for (int j = 0; j < TC; ++j)
+#pragma unroll
+                        for (int i = 0; i < TP; ++i) acc[j][i] = (floatx4){0.f, 0.f, 0.f, 0.f};
+                    for (int ww = w_first; ww <= w_last; ++ww) {
+                        const int fj = (int)(share_begin(sch, ww) / nk);
+                        const float *slab = a.partial + (size_t)(2 * ww + (shared_j == fj ? 0 : 1)) * SLAB;
+#pragma unroll
+                        for (int j = 0; j < TC; ++j)
+#pragma unroll
+                            for (int i = 0; i < TP; ++i)
+#pragma unroll
+                                for (int r = 0; r < 4; ++r)
+                                    acc[j][i][r] += __hip_atomic_load(slab + ((j * TP + i) * 4 + r) * NCONS + ctid,
+                                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
+                }
             }
         }
-    }
-}
 
-// Output update after a split multiplication (Section 3.1, "Output Updating"): add the K-range
-// partial sums in ascending K order, add the bias, apply the activation and write the listed
-// positions of the stored map.  One thread per (listed pixel, 4 channels): reads and writes are
-// contiguous runs of 16*Ms/4 bytes per pixel.  Does nothing if the multiplication was not split.
-template <int BM, int BN>
-__global__ __launch_bounds__(256) void output_update_kernel(GemmArgs a)
-{
-    const int n = *a.count;
-    const int mtiles = a.Mpad / BM;
-    const int ptiles = (n + BN - 1) / BN;
-    const int S = choose_split(ptiles * mtiles, a.Kpad / BK, a.split_override);
-    if (S == 1) return;
-    const int V = a.Ms >> 2;
-    const long long total = (long long)n * V;
-    for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long long)gridDim.x * 256) {
-        const int u = (int)(idx / V);
-        const int ch = (int)(idx - (long long)u * V) * 4;
-        const int pt = u / BN, pl = u - pt * BN;
-        const int mt = ch / BM, cl = ch - mt * BM;
-        const float *p = a.partial + ((size_t)(pt * S) * mtiles + mt) * (BN * BM) + (size_t)pl * BM + cl;
-        float4 sum = *reinterpret_cast<const float4 *>(p);
-        for (int s = 1; s < S; ++s) {
-            const float4 t = *reinterpret_cast<const float4 *>(p + (size_t)s * mtiles * (BN * BM));
-            sum.x += t.x;
-            sum.y += t.y;
-            sum.z += t.z;
-            sum.w += t.w;
+        CBK_STAMP(6 + 6 * seg);
+        // ---- output update: bias, activation, scatter to the stored map
+        if (finish && !producer) {
+#pragma unroll
+            for (int j = 0; j < TC; ++j) {
+                const int ch = mt * BM + wch0 + j * 16 + lk * 4;
+                const float4 bv = *reinterpret_cast<const float4 *>(a.bias + ch);
+#pragma unroll
+                for (int i = 0; i < TP; ++i) {
+                    const int g = sU[wpx0 + i * 16 + lrow];
+                    if (g >= 0 && ch < a.Ms) {
+                        float4 o;
+                        o.x = acc[j][i][0] + bv.x;
+                        o.y = acc[j][i][1] + bv.y;
+                        o.z = acc[j][i][2] + bv.z;
+                        o.w = acc[j][i][3] + bv.w;
+                        if (a.relu) {
+                            o.x = fmaxf(o.x, 0.f);
+                            o.y = fmaxf(o.y, 0.f);
+                            o.z = fmaxf(o.z, 0.f);
+                            o.w = fmaxf(o.w, 0.f);
+                        }
+                        *reinterpret_cast<float4 *>(a.out + (size_t)g * a.Ms + ch) = o;
+                    }
+                }
+            }
         }
-        const float4 bv = *reinterpret_cast<const float4 *>(a.bias + ch);
-        sum.x += bv.x;
-        sum.y += bv.y;
-        sum.z += bv.z;
-        sum.w += bv.w;
-        if (a.relu) {
-            sum.x = fmaxf(sum.x, 0.f);
-            sum.y = fmaxf(sum.y, 0.f);
-            sum.z = fmaxf(sum.z, 0.f);
-            sum.w = fmaxf(sum.w, 0.f);
-        }
-        *reinterpret_cast<float4 *>(a.out + (size_t)a.list[u] * a.Ms + ch) = sum;
+        CBK_STAMP(7 + 6 * seg);
+        ++seg;
     }
 }
 
@@ -389,10 +450,29 @@ int gemm_channel_tile(int M)
 
 static int pixel_tile(int bm) { return bm == 128 ? 128 : 256; }
 
-size_t gemm_partial_bytes(int M)
+// Two partial-accumulator slabs per workgroup.
+size_t gemm_partial_bytes(int M, int grid)
 {
     const int bm = gemm_channel_tile(M);
-    return (size_t)kMaxItems * bm * pixel_tile(bm) * sizeof(float);
+    return (size_t)2 * grid * bm * pixel_tile(bm) * sizeof(float);
+}
+
+// One ticket counter per shared tile (fewer than the workgroup count); zero between launches.
+size_t gemm_ticket_bytes(int grid) { return (size_t)grid * sizeof(int); }
+
+// Workgroups to launch: one per compute unit, fewer if even the longest list gives less work.
+int gemm_grid(const GemmArgs &a, int compute_units)
+{
+    const int bm = gemm_channel_tile(a.M), bn = pixel_tile(bm);
+    int W = compute_units & ~7;
+    if (W < 8) W = 8;
+    if (W > kMaxGrid) W = kMaxGrid;
+    const long long tiles = (long long)((a.max_pixels + bn - 1) / bn) * (a.Mpad / bm);
+    const int nk = a.Kpad / BK;
+    const int parts = nk / kMinIters > 1 ? nk / kMinIters : 1;
+    long long need = tiles >= W ? W : (tiles * parts + 7) / 8 * 8;
+    if (need < 8) need = 8;
+    return (int)(need < W ? need : W);
 }
 
 #define CBK_VARIANTS(X) X(16, 256, 1, 4) X(32, 256, 1, 4) X(64, 256, 1, 4) X(128, 128, 2, 2)
@@ -406,19 +486,6 @@ hipError_t gemm_prepare(void)
                                 hipFuncAttributeMaxDynamicSharedMemorySize, TileSmem<BM_, BN_>::bytes);
     CBK_VARIANTS(X)
 #undef X
-    if (getenv("CBINFER_DEBUG")) {
-#define X(BM_, BN_, WM_, WN_)                                                                              \
-    {                                                                                                      \
-        int nb = -1;                                                                                       \
-        (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(                                                \
-            &nb, reinterpret_cast<const void *>(&gemm_gather_kernel<BM_, BN_, WM_, WN_>), NT,              \
-            TileSmem<BM_, BN_>::bytes);                                                                    \
-        fprintf(stderr, "gemm_gather<%d,%d>: %d B LDS, %d workgroups/CU\n", BM_, BN_,                       \
-                (int)TileSmem<BM_, BN_>::bytes, nb);                                                       \
-    }
-        CBK_VARIANTS(X)
-#undef X
-    }
     return e;
 }
 
@@ -430,60 +497,17 @@ static hipError_t launch(hipStream_t st, const GemmArgs &a)
     return hipGetLastError();
 }
 
-template <int BM, int BN>
-static hipError_t launch_update(hipStream_t st, const GemmArgs &a)
-{
-    // has work only while the tile count is below the splitting limit
-    long long work = (long long)4 * kCUs * BN * (a.Ms / 4);
-    const long long full = (long long)a.max_pixels * (a.Ms / 4);
-    if (full < work) work = full;
-    long long grid = (work + 255) / 256;
-    if (grid > 2048) grid = 2048;
-    if (grid < 1) grid = 1;
-    output_update_kernel<BM, BN><<<dim3((int)grid), dim3(256), 0, st>>>(a);
-    return hipGetLastError();
-}
-
-// Workgroups to launch: the largest work-item count any list length can produce, capped.
-int gemm_grid(const GemmArgs &a)
-{
-    const int bm = gemm_channel_tile(a.M), bn = pixel_tile(bm);
-    const int nk = a.Kpad / BK, mtiles = a.Mpad / bm;
-    const int maxpt = (a.max_pixels + bn - 1) / bn;
-    long long best = 1;
-    for (int pt = 1; pt <= maxpt; ++pt) {
-        const long long t = (long long)pt * mtiles;
-        const long long items = t * choose_split((int)(t > 0x7fffffff ? 0x7fffffff : t), nk, a.split_override);
-        if (items > best) best = items;
-        if (best >= 1024) break;
-    }
-    if (best > 1024) best = 1024;
-    return (int)((best + 7) / 8 * 8);
-}
-
-bool gemm_can_split(const GemmArgs &a) { return choose_split(1, a.Kpad / BK, a.split_override) > 1; }
-
 hipError_t gemm_gather(hipStream_t st, const GemmArgs &a)
 {
     const int bm = gemm_channel_tile(a.M);
-    if (a.Mpad % bm != 0 || a.Kpad % BK != 0 || a.Cs % 4 != 0 || !a.partial || a.grid < 1)
+    if (a.Mpad % bm != 0 || a.Kpad % BK != 0 || a.Cs % 4 != 0 || !a.partial || !a.tickets || a.grid < 8 ||
+        (a.grid & 7))
         return hipErrorInvalidValue;
     switch (bm) {
     case 16: return launch<16, 256, 1, 4>(st, a);
     case 32: return launch<32, 256, 1, 4>(st, a);
     case 64: return launch<64, 256, 1, 4>(st, a);
     default: return launch<128, 128, 2, 2>(st, a);
-    }
-}
-
-hipError_t output_update(hipStream_t st, const GemmArgs &a)
-{
-    const int bm = gemm_channel_tile(a.M);
-    switch (bm) {
-    case 16: return launch_update<16, 256>(st, a);
-    case 32: return launch_update<32, 256>(st, a);
-    case 64: return launch_update<64, 256>(st, a);
-    default: return launch_update<128, 128>(st, a);
     }
 }
 

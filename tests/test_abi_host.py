@@ -32,9 +32,9 @@ def test_library_exports_every_declared_function():
 def test_workspace_bytes_and_layout_constants():
     layers = scene_labeling_net()
     n = cb.cbinfer_workspace_bytes(layers, make_weights(layers, 0), (3, 240, 320))
-    assert 20e6 < n < 80e6
+    assert 30e6 < n < 120e6            # maps, lists and 32 MiB of GEMM scratch
     n64 = cb.cbinfer_workspace_bytes(layers, make_weights(layers, 0), (3, 240, 320), n_streams=64)
-    assert n64 > 50 * n
+    assert n64 > 20 * n
 
 
 def _net_for(layers, params, shape, **kw):
