@@ -184,7 +184,9 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
         op.o_ulist = cv.take(out_px * 4);
         op.o_counts = cv.take(4 * 4);
         if (op.kind == CBINFER_OP_CONV) {
-            op.o_ref = cv.take(in_px * op.Cs * 4);
+            // Layers behind the first keep no copy of their previous input unless asked to hold it
+            // or to run densely: their previous input is the stored output of the op before them.
+            if (l == 0 || P.hold || op.dense) op.o_ref = cv.take(in_px * op.Cs * 4);
             if (l == 0 && P.hold) op.o_cur = cv.take(in_px * op.Cs * 4);
             op.o_wt = cv.take((size_t)op.Mpad * op.Kpad * 4);
             op.o_bias = cv.take((size_t)op.Mpad * 4);
@@ -322,6 +324,12 @@ void build_taps(const Op &op, std::vector<int2> &taps)
     }
 }
 
+// Whether conv op l takes its change bitmap from the op that produces its input.
+bool fuses_detection(const Plan &P, int l, bool force_dense)
+{
+    return l > 0 && !P.hold && !P.ops[l].dense && !force_dense;
+}
+
 int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
 {
     const Plan &P = s->plan;
@@ -340,6 +348,10 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             float *ref = s->at<float>(op.o_ref);
             int *counts = s->at<int>(op.o_counts);
             const bool all = first || op.dense || s->force_dense;
+            // A layer fed by a stored map finds its changes while that map is updated (the op
+            // before it compares each new value with the one it replaces), unless it holds its
+            // reference or runs densely.
+            const bool fused_in = l > 0 && !P.hold && !op.dense && !s->force_dense;
             // --- change detection (also turns the planar frame into a map for layer 0)
             if (l == 0) {
                 StepTimer t(s, l, CBINFER_STEP_DETECT);
@@ -349,7 +361,7 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                 x = hold ? s->at<float>(op.o_cur) : ref;
             } else {
                 x = s->at<float>(P.ops[l - 1].o_out);
-                if (!s->force_dense) {
+                if (!s->force_dense && !fused_in) {
                     StepTimer t(s, l, CBINFER_STEP_DETECT);
                     HIP_TRY(cbk::detect_map(st, x, ref, s->at<uint64_t>(op.o_chg), op.Cs, S * N, op.tau,
                                             P.hold ? 1 : 0, all ? 1 : 0));
@@ -404,6 +416,15 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             a.partial = s->at<float>(P.o_partial);
             a.tickets = s->at<int>(P.o_tickets);
             a.grid = op.gemm_grid;
+            a.next_chg = nullptr;
+            a.next_tau = 0.f;
+            a.next_force = first ? 1 : 0;
+            if (l + 1 < nops && P.ops[l + 1].kind == CBINFER_OP_CONV && fuses_detection(P, l + 1, s->force_dense)) {
+                a.next_chg = s->at<uint64_t>(P.ops[l + 1].o_chg);
+                a.next_tau = P.ops[l + 1].tau;
+            }
+            a.clear_bits = fused_in ? s->at<uint64_t>(op.o_chg) : nullptr;
+            a.clear_words = words_for((long long)S * N);
 #ifdef CBK_TRACE
             a.trace = cbk_trace_buffer();
 #endif
@@ -416,9 +437,15 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             const int Np = op.Ho * op.Wo;
             const int *plist = s->force_dense ? iota : s->at<int>(op.o_ulist);
             const int *pcount = s->force_dense ? consts + 2 * l : s->at<int>(op.o_counts) + 1;
+            uint64_t *next_chg = nullptr;
+            float next_tau = 0.f;
+            if (l + 1 < nops && P.ops[l + 1].kind == CBINFER_OP_CONV && fuses_detection(P, l + 1, s->force_dense)) {
+                next_chg = s->at<uint64_t>(P.ops[l + 1].o_chg);
+                next_tau = P.ops[l + 1].tau;
+            }
             StepTimer t(s, l, CBINFER_STEP_POOL);
             HIP_TRY(cbk::pool_sparse(st, plist, pcount, S * Np, s->at<float>(cv.o_out), s->at<float>(op.o_out), op.Ms,
-                                     op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np));
+                                     op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np, next_chg, next_tau, first ? 1 : 0));
         }
     }
     const Op &last = P.ops.back();
@@ -642,7 +669,8 @@ int cbinfer_read_map(cbinfer_state *s, int layer, int which, float *host, size_t
         if (op.kind != CBINFER_OP_CONV) return fail(CBINFER_EINVAL, "layer %d has no stored previous input", layer);
         if (s->force_dense && layer > 0) return fail(CBINFER_ESTATE, "dense mode keeps no previous input for layer %d", layer);
         C = op.C; Cs = op.Cs; HW = op.H * op.W;
-        src = s->at<float>(op.o_ref);
+        // a layer that keeps no copy of its own: its previous input is the stored map that feeds it
+        src = op.o_ref != SIZE_MAX ? s->at<float>(op.o_ref) : s->at<float>(s->plan.ops[layer - 1].o_out);
     } else if (which == CBINFER_MAP_OUTPUT) {
         C = op.M; Cs = op.Ms; HW = op.Ho * op.Wo;
         src = s->at<float>(op.o_out);

@@ -13,6 +13,14 @@
 
 namespace cbk {
 
+// One subtraction, one absolute value and one strict comparison per channel (Section 3.1);
+// a NaN difference compares false and does not flag.
+__device__ __forceinline__ bool exceeds(const float4 a, const float4 r, const float tau)
+{
+    return (fabsf(a.x - r.x) > tau) || (fabsf(a.y - r.y) > tau) || (fabsf(a.z - r.z) > tau) ||
+           (fabsf(a.w - r.w) > tau);
+}
+
 // ---- change detection (Section 3.1, first formula) ---------------------------------------
 // Planar float32 frame [S][C][N] against the stored previous input kept as a map.
 // Writes the change bitmap; refreshes the stored input (hold == 0: everywhere;
@@ -62,6 +70,16 @@ struct GemmArgs {
     int *tickets;       // gemm_ticket_bytes(grid) bytes, zero before the first launch (each launch
                         // leaves them zero again)
     int grid;           // workgroups to launch, from gemm_grid()
+    // Change detection of the next layer fused into the output update (used when that layer's
+    // stored previous input is this layer's stored output): bits of positions whose new value
+    // differs from the replaced one by more than next_tau are set in next_chg (zero on entry).
+    uint64_t *next_chg; // nullptr: off
+    float next_tau;
+    int next_force;     // flag every recomputed position (first frame)
+    // Bitmap this launch clears for the next frame (this layer's own change bitmap, already
+    // condensed into lists when the multiplication runs); nullptr: none.
+    uint64_t *clear_bits;
+    int clear_words;
 #ifdef CBK_TRACE
     unsigned long long *trace; // timing study builds only: [grid][2 roles][16] timestamps
 #endif
@@ -76,8 +94,13 @@ hipError_t gemm_prepare(void);  // one-time function attributes (dynamic LDS siz
 hipError_t gemm_gather(hipStream_t st, const GemmArgs &a);
 
 // ---- max-pooling at listed pooled positions -----------------------------------------------
+// next_chg != nullptr: the pooled map feeds a convolution layer whose stored previous input is
+// this very map; compare each recomputed value with the one it replaces against next_tau and set
+// the position's bit in that layer's change bitmap (which must be zero on entry).
+// next_force != 0: flag every recomputed position (first frame).
 hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const float *in,
-                       float *pooled, int Ms, int k, int Wo, int No, int Wp, int Np);
+                       float *pooled, int Ms, int k, int Wo, int No, int Wp, int Np, uint64_t *next_chg,
+                       float next_tau, int next_force);
 
 // ---- stored map -> caller's planar output --------------------------------------------------
 hipError_t map_to_planar(hipStream_t st, const float *map, float *planar, int M, int Ms, int No, int S);

@@ -177,6 +177,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     const bool producer = wave >= 4;
 
     CBK_STAMP(0);
+    // this layer's change bitmap has been condensed into the lists already: clear it for the next frame
+    if (a.clear_bits)
+        for (int i = blockIdx.x * NT + tid; i < a.clear_words; i += gridDim.x * NT) a.clear_bits[i] = 0ull;
     const int n = *a.count;
     const int mtiles = a.Mpad / BM;
     const int nk = a.Kpad / BK;
@@ -406,8 +409,13 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         }
 
         CBK_STAMP(6 + 6 * seg);
-        // ---- output update: bias, activation, scatter to the stored map
+        // ---- output update: bias, activation, scatter to the stored map; optionally the change
+        //      detection of the layer this map feeds (new value against the one it replaces)
         if (finish && !producer) {
+            const bool detect = a.next_chg != nullptr && !a.next_force;
+            bool changed[TP];
+#pragma unroll
+            for (int i = 0; i < TP; ++i) changed[i] = false;
 #pragma unroll
             for (int j = 0; j < TC; ++j) {
                 const int ch = mt * BM + wch0 + j * 16 + lk * 4;
@@ -427,8 +435,22 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                             o.z = fmaxf(o.z, 0.f);
                             o.w = fmaxf(o.w, 0.f);
                         }
-                        *reinterpret_cast<float4 *>(a.out + (size_t)g * a.Ms + ch) = o;
+                        float4 *dst = reinterpret_cast<float4 *>(a.out + (size_t)g * a.Ms + ch);
+                        if (detect) changed[i] |= exceeds(o, *dst, a.next_tau);
+                        *dst = o;
                     }
+                }
+            }
+            if (a.next_chg) {
+                unsigned long long *bits = reinterpret_cast<unsigned long long *>(a.next_chg);
+#pragma unroll
+                for (int i = 0; i < TP; ++i) {
+                    const int g = sU[wpx0 + i * 16 + lrow];
+                    int f = a.next_force ? 1 : (int)changed[i];
+                    // the other channels of this pixel sit in the lanes 16, 32 and 48 further on
+                    f |= __shfl_xor(f, 16);
+                    f |= __shfl_xor(f, 32);
+                    if (lk == 0 && f && g >= 0) atomicOr(bits + (g >> 6), 1ull << (g & 63));
                 }
             }
         }

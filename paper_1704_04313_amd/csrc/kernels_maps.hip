@@ -7,14 +7,6 @@ namespace cbk {
 
 static constexpr int kBlock = 256;
 
-__device__ __forceinline__ bool exceeds(const float4 a, const float4 r, const float tau)
-{
-    // one subtraction, one absolute value, one strict comparison per channel (Section 3.1);
-    // a NaN difference compares false and does not flag.
-    return (fabsf(a.x - r.x) > tau) || (fabsf(a.y - r.y) > tau) || (fabsf(a.z - r.z) > tau) ||
-           (fabsf(a.w - r.w) > tau);
-}
-
 // ------------------------------------------------------------------------------------------
 // Change detection on a planar frame: one thread per pixel, channels in groups of four.
 // Frame reads are coalesced per channel plane; the stored map is read and written as one
@@ -206,9 +198,18 @@ __global__ __launch_bounds__(kBlock) void dilate_kernel(const uint64_t *__restri
         if (t < total) {
             const int st = t / Np, q = t - st * Np;
             const int py = q / g.Wp, px = q - py * g.Wp;
-            for (int a = 0; a < g.pool_k; ++a)
-                for (int b = 0; b < g.pool_k; ++b)
-                    f |= field_changed(chg, g, st, py * g.pool_k + a, px * g.pool_k + b);
+            DilateGeom e = g;
+            e.stride = g.stride * g.pool_k;
+            e.kh = g.kh + (g.pool_k - 1) * g.stride;
+            e.kw = g.kw + (g.pool_k - 1) * g.stride;
+            if (g.stride <= g.kh && g.stride <= g.kw && e.kw <= 64) {
+                // the k x k outputs' receptive fields tile one larger window without gaps
+                f = field_changed(chg, e, st, py, px);
+            } else {
+                for (int a = 0; a < g.pool_k; ++a)
+                    for (int b = 0; b < g.pool_k; ++b)
+                        f |= field_changed(chg, g, st, py * g.pool_k + a, px * g.pool_k + b);
+            }
         }
         const uint64_t word = __ballot(f);
         const int t0 = t & ~63;
@@ -309,9 +310,13 @@ __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restri
                                                              const int *__restrict__ count,
                                                              const float4 *__restrict__ in,
                                                              float4 *__restrict__ pooled, int V, int k, int Wo,
-                                                             int No, int Wp, int Np)
+                                                             int No, int Wp, int Np,
+                                                             unsigned long long *__restrict__ next_chg,
+                                                             float next_tau, int next_force)
 {
     const long long total = (long long)(*count) * V;
+    const int lane = threadIdx.x & 63;
+    const bool pow2 = (V & (V - 1)) == 0 && V <= 64;
     for (long long idx = (long long)blockIdx.x * kBlock + threadIdx.x; idx < total;
          idx += (long long)gridDim.x * kBlock) {
         const int u = (int)(idx / V), v = (int)(idx - (long long)u * V);
@@ -328,12 +333,27 @@ __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restri
                 m.z = fmaxf(m.z, a.z);
                 m.w = fmaxf(m.w, a.w);
             }
+        if (next_chg) {
+            // Change detection of the layer this map feeds (Section 3.1, first formula): the value
+            // being replaced is that layer's stored previous input, and positions that are not
+            // recomputed cannot differ from it.
+            bool f = next_force != 0;
+            if (!f) f = exceeds(m, pooled[(long long)g * V + v], next_tau);
+            if (pow2) {
+                const unsigned long long B = __ballot(f);
+                const unsigned long long grp = (V == 64) ? ~0ull : (((1ull << V) - 1ull) << (lane & ~(V - 1)));
+                if (v == 0 && (B & grp) != 0ull) atomicOr(next_chg + (g >> 6), 1ull << (g & 63));
+            } else if (f) {
+                atomicOr(next_chg + (g >> 6), 1ull << (g & 63));
+            }
+        }
         pooled[(long long)g * V + v] = m;
     }
 }
 
 hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const float *in,
-                       float *pooled, int Ms, int k, int Wo, int No, int Wp, int Np)
+                       float *pooled, int Ms, int k, int Wo, int No, int Wp, int Np, uint64_t *next_chg,
+                       float next_tau, int next_force)
 {
     const int V = Ms / 4;
     long long work = (long long)max_count * V;
@@ -342,7 +362,7 @@ hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int ma
     if (grid < 1) grid = 1;
     hipLaunchKernelGGL(pool_sparse_kernel, dim3((int)grid), dim3(kBlock), 0, st, list, count,
                        reinterpret_cast<const float4 *>(in), reinterpret_cast<float4 *>(pooled), V, k, Wo, No, Wp,
-                       Np);
+                       Np, reinterpret_cast<unsigned long long *>(next_chg), next_tau, next_force);
     return hipGetLastError();
 }
 

@@ -292,3 +292,93 @@ def test_determinism_two_runs_byte_identical():
     for a, b in zip(outs[0][0], outs[1][0]):
         np.testing.assert_array_equal(a, b)
     np.testing.assert_array_equal(outs[0][1], outs[1][1])
+
+
+# ------------------------------------------------------------------ exact arithmetic, whole network
+def _integer_video(H, W, C, n_frames, seed):
+    """Small-integer frames: static background, one moving block, a few +-1 flickers per frame.
+    With small-integer weights every sum is an exactly representable integer in float32 and in
+    double alike, so the HIP path and the oracle agree bit for bit at every layer and the lists
+    of all layers can be compared exactly (no threshold knife-edges)."""
+    r = np.random.default_rng(seed)
+    bg = r.integers(0, 4, size=(C, H, W)).astype(np.float32)
+    tex = r.integers(0, 4, size=(C, 5, 6)).astype(np.float32)
+    frames = []
+    for t in range(n_frames):
+        f = bg.copy()
+        y, x = 3 + t, 2 + 2 * t
+        f[:, y:y + 5, x:x + 6] = tex
+        for _ in range(6):
+            c, yy, xx = r.integers(0, C), r.integers(0, H), r.integers(0, W)
+            f[c, yy, xx] += float(r.integers(-1, 2))
+        frames.append(f)
+    return frames
+
+
+def _integer_params(layers, seed):
+    r = np.random.default_rng(seed)
+    params = []
+    for L in layers:
+        if L.kind != "conv":
+            params.append(None)
+            continue
+        w = r.integers(-1, 2, size=(L.cout, L.cin, L.kh, L.kw)).astype(np.float32)
+        b = r.integers(-2, 3, size=L.cout).astype(np.float32)
+        params.append((w, b))
+    return params
+
+
+@pytest.mark.parametrize("hold", [False, True])
+def test_integer_network_every_layer_bit_exact(hold):
+    layers = [conv(3, 8, 3), pool(), conv(8, 20, 3), conv(20, 12, 1), pool(), conv(12, 5, 3, relu=False)]
+    params = _integer_params(layers, 31)
+    H, W = 24, 36
+    frames = _integer_video(H, W, 3, 7, 77)
+    taus = [0.5, None, 1.5, 2.5, None, 3.5]
+    net = cb.CBInfer(layers, params, (3, H, W), taus, hold_reference=hold)
+    orc = oracle.OracleCBNet(layers, params, [0.0 if t is None else t for t in taus], ref_mode=1 if hold else 0)
+    sparse_seen = False
+    for t, f in enumerate(frames):
+        want = orc.process_frame(f)
+        got = net.process_frame(to_dev(f)).cpu().numpy()[0]
+        for l, L in enumerate(layers):
+            what = "layer %d frame %d" % (l, t)
+            if L.kind == "conv":
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_CHANGED), orc.trace[l]["C"], err_msg=what)
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), orc.trace[l]["U"], err_msg=what)
+                np.testing.assert_array_equal(net.read_map(l, cb.MAP_REFERENCE)[0], orc.ref[l], err_msg=what)
+                if t and l >= 2 and 0 < orc.trace[l]["C"].size < orc.trace[l]["x"][0].size:
+                    sparse_seen = True
+            else:
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), orc.trace[l]["P"], err_msg=what)
+            np.testing.assert_array_equal(net.read_map(l, cb.MAP_OUTPUT)[0], orc.out[l], err_msg=what)
+        np.testing.assert_array_equal(got, want)
+    assert sparse_seen, "the deeper layers never saw a sparse change list; the test is too easy"
+    net.destroy()
+
+
+def test_integer_network_reset_and_dense_switch_keep_lists_exact():
+    """Resetting and switching modes in mid-video must leave the fused change bitmaps clean."""
+    layers = [conv(3, 8, 3), pool(), conv(8, 16, 3), conv(16, 4, 1, relu=False)]
+    params = _integer_params(layers, 32)
+    frames = _integer_video(20, 28, 3, 8, 78)
+    taus = [0.5, None, 1.5, 2.5]
+    net = cb.CBInfer(layers, params, (3, 20, 28), taus)
+    orc = oracle.OracleCBNet(layers, params, [0.0 if t is None else t for t in taus])
+    for t, f in enumerate(frames):
+        if t == 3:
+            net.reset()
+            orc.reset()
+        if t == 5:
+            net.set_mode(True)
+            net.process_frame(to_dev(frames[0]))
+            net.set_mode(False)
+            orc.reset()
+        want = orc.process_frame(f)
+        got = net.process_frame(to_dev(f)).cpu().numpy()[0]
+        for l in (0, 2, 3):
+            np.testing.assert_array_equal(net.read_list(l, cb.LIST_CHANGED), orc.trace[l]["C"],
+                                          err_msg="layer %d frame %d" % (l, t))
+            np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), orc.trace[l]["U"])
+        np.testing.assert_array_equal(got, want)
+    net.destroy()
