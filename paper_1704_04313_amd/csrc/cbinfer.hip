@@ -191,7 +191,8 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
             op.o_wt = cv.take((size_t)op.Mpad * op.Kpad * 4);
             op.o_bias = cv.take((size_t)op.Mpad * 4);
             op.o_taps = cv.take((size_t)op.Kpad / 4 * sizeof(int2));
-            op.o_chg = cv.take(((size_t)words_for((long long)in_px) + 1) * 8);
+            // change map: one bit per pixel, or one byte per pixel when the op before fills it in
+            op.o_chg = cv.take(((size_t)words_for((long long)in_px) + 1) * 64);
             op.o_upd = cv.take(((size_t)words_for((long long)out_px) + 1) * 8);
             if (op.pool_after >= 0) {
                 const Op &pp = P.ops[op.pool_after];
@@ -374,6 +375,7 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                 g.S = S; g.H = op.H; g.W = op.W; g.Ho = op.Ho; g.Wo = op.Wo;
                 g.kh = op.kh; g.kw = op.kw; g.stride = op.stride; g.pad = op.pad;
                 g.pool_k = 0; g.Hp = 0; g.Wp = 0;
+                g.chg_bytes = fused_in ? 1 : 0;
                 uint64_t *pool_bits = nullptr;
                 if (op.pool_after >= 0) {
                     const Op &pp = P.ops[op.pool_after];
@@ -386,11 +388,11 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                 }
                 cbk::CompactJob jobs[3];
                 int nj = 0;
-                jobs[nj++] = {s->at<uint64_t>(op.o_upd), words_for((long long)S * No), s->at<int>(op.o_ulist), counts + 1};
-                jobs[nj++] = {s->at<uint64_t>(op.o_chg), words_for((long long)S * N), s->at<int>(op.o_clist), counts + 0};
+                jobs[nj++] = {s->at<uint64_t>(op.o_upd), 0, words_for((long long)S * No), s->at<int>(op.o_ulist), counts + 1};
+                jobs[nj++] = {s->at<uint64_t>(op.o_chg), fused_in ? 1 : 0, words_for((long long)S * N), s->at<int>(op.o_clist), counts + 0};
                 if (op.pool_after >= 0) {
                     const Op &pp = P.ops[op.pool_after];
-                    jobs[nj++] = {pool_bits, words_for((long long)S * pp.Ho * pp.Wo), s->at<int>(pp.o_ulist),
+                    jobs[nj++] = {pool_bits, 0, words_for((long long)S * pp.Ho * pp.Wo), s->at<int>(pp.o_ulist),
                                   s->at<int>(pp.o_counts) + 1};
                 }
                 {
@@ -416,15 +418,15 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             a.partial = s->at<float>(P.o_partial);
             a.tickets = s->at<int>(P.o_tickets);
             a.grid = op.gemm_grid;
-            a.next_chg = nullptr;
+            a.next_flags = nullptr;
             a.next_tau = 0.f;
             a.next_force = first ? 1 : 0;
             if (l + 1 < nops && P.ops[l + 1].kind == CBINFER_OP_CONV && fuses_detection(P, l + 1, s->force_dense)) {
-                a.next_chg = s->at<uint64_t>(P.ops[l + 1].o_chg);
+                a.next_flags = s->at<unsigned char>(P.ops[l + 1].o_chg);
                 a.next_tau = P.ops[l + 1].tau;
             }
             a.clear_bits = fused_in ? s->at<uint64_t>(op.o_chg) : nullptr;
-            a.clear_words = words_for((long long)S * N);
+            a.clear_words = words_for((long long)S * N) * 8; // 64 bytes per 64 pixels
 #ifdef CBK_TRACE
             a.trace = cbk_trace_buffer();
 #endif
@@ -437,15 +439,15 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             const int Np = op.Ho * op.Wo;
             const int *plist = s->force_dense ? iota : s->at<int>(op.o_ulist);
             const int *pcount = s->force_dense ? consts + 2 * l : s->at<int>(op.o_counts) + 1;
-            uint64_t *next_chg = nullptr;
+            unsigned char *next_flags = nullptr;
             float next_tau = 0.f;
             if (l + 1 < nops && P.ops[l + 1].kind == CBINFER_OP_CONV && fuses_detection(P, l + 1, s->force_dense)) {
-                next_chg = s->at<uint64_t>(P.ops[l + 1].o_chg);
+                next_flags = s->at<unsigned char>(P.ops[l + 1].o_chg);
                 next_tau = P.ops[l + 1].tau;
             }
             StepTimer t(s, l, CBINFER_STEP_POOL);
             HIP_TRY(cbk::pool_sparse(st, plist, pcount, S * Np, s->at<float>(cv.o_out), s->at<float>(op.o_out), op.Ms,
-                                     op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np, next_chg, next_tau, first ? 1 : 0));
+                                     op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np, next_flags, next_tau, first ? 1 : 0));
         }
     }
     const Op &last = P.ops.back();

@@ -40,6 +40,7 @@ hipError_t detect_map(hipStream_t st, const float *x, float *ref, uint64_t *bits
 struct DilateGeom {
     int S, H, W, Ho, Wo, kh, kw, stride, pad; // convolution geometry
     int pool_k, Hp, Wp;                       // pooling that follows (pool_k == 0: none)
+    int chg_bytes;                            // the change map has one byte per pixel instead of one bit
 };
 hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, uint64_t *pool_bits,
                   const DilateGeom &g);
@@ -47,8 +48,9 @@ hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, 
 // ---- change-index extraction (Section 3.1) -------------------------------------------------
 // Up to three bitmaps -> ascending index lists and counts in one launch.
 struct CompactJob {
-    const uint64_t *bits;
-    int nwords;
+    const uint64_t *bits; // bitmap, or (bytes != 0) a map with one byte per pixel, padded to 64 pixels
+    int bytes;
+    int nwords;           // 64-pixel words
     int *list;
     int *count;
 };
@@ -71,12 +73,13 @@ struct GemmArgs {
                         // leaves them zero again)
     int grid;           // workgroups to launch, from gemm_grid()
     // Change detection of the next layer fused into the output update (used when that layer's
-    // stored previous input is this layer's stored output): bits of positions whose new value
-    // differs from the replaced one by more than next_tau are set in next_chg (zero on entry).
-    uint64_t *next_chg; // nullptr: off
+    // stored previous input is this layer's stored output): positions whose new value differs
+    // from the replaced one by more than next_tau get their byte set in next_flags (one byte per
+    // pixel, zero on entry; several workgroups may store the same 1, no atomics needed).
+    unsigned char *next_flags; // nullptr: off
     float next_tau;
-    int next_force;     // flag every recomputed position (first frame)
-    // Bitmap this launch clears for the next frame (this layer's own change bitmap, already
+    int next_force;            // flag every recomputed position (first frame)
+    // Map this launch clears for the next frame (this layer's own change map, already
     // condensed into lists when the multiplication runs); nullptr: none.
     uint64_t *clear_bits;
     int clear_words;
@@ -94,12 +97,12 @@ hipError_t gemm_prepare(void);  // one-time function attributes (dynamic LDS siz
 hipError_t gemm_gather(hipStream_t st, const GemmArgs &a);
 
 // ---- max-pooling at listed pooled positions -----------------------------------------------
-// next_chg != nullptr: the pooled map feeds a convolution layer whose stored previous input is
+// next_flags != nullptr: the pooled map feeds a convolution layer whose stored previous input is
 // this very map; compare each recomputed value with the one it replaces against next_tau and set
-// the position's bit in that layer's change bitmap (which must be zero on entry).
+// the position's byte in that layer's change map (one byte per pixel, zero on entry).
 // next_force != 0: flag every recomputed position (first frame).
 hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const float *in,
-                       float *pooled, int Ms, int k, int Wo, int No, int Wp, int Np, uint64_t *next_chg,
+                       float *pooled, int Ms, int k, int Wo, int No, int Wp, int Np, unsigned char *next_flags,
                        float next_tau, int next_force);
 
 // ---- stored map -> caller's planar output --------------------------------------------------

@@ -291,10 +291,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             int slot = 2; // ring slot of slice kc+2
             for (int kc = kc0; kc < kc1; ++kc) {
                 if (kc + 2 < kc1) {
+#ifndef CBK_EXP_NOSTAGE
                     stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, v, ra, rb);
+#endif
                     if (kc + 3 < kc1) {
+#ifndef CBK_EXP_NOGATHER
                         gather_rows<PA>(a, tp, iy0, ix0, base, ra);
+#endif
+#ifndef CBK_EXP_NOFILTER
                         load_filter_rows<BM, PB>(wrow, a.Kpad, kc + 3, r0, rb);
+#endif
                         if (kc + 4 < kc1) tp = taps[(kc + 4) * (BK / 4)];
                     }
                 }
@@ -365,17 +371,23 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             const int w_last = share_owner(sch, t0 + nk - 1);
             const int ctid = tid & (NCONS - 1);
             if (!producer) {
-                // slab 2*wsh + (0: first tile this workgroup touches, 1: a later one), register layout
+                // slab 2*wsh + (0: first tile this workgroup touches, 1: a later one), register layout:
+                // accumulator halves as 64-bit words, consecutive lanes consecutive addresses
                 const int first_j = (int)(it_begin / nk);
-                float *slab = a.partial + (size_t)(2 * wsh + (shared_j == first_j ? 0 : 1)) * SLAB;
+                unsigned long long *slab = reinterpret_cast<unsigned long long *>(
+                    a.partial + (size_t)(2 * wsh + (shared_j == first_j ? 0 : 1)) * SLAB);
 #pragma unroll
                 for (int j = 0; j < TC; ++j)
 #pragma unroll
                     for (int i = 0; i < TP; ++i)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            __hip_atomic_store(slab + ((j * TP + i) * 4 + r) * NCONS + ctid, acc[j][i][r],
-                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        for (int h = 0; h < 2; ++h) {
+                            union { float f[2]; unsigned long long u; } pk;
+                            pk.f[0] = acc[j][i][2 * h];
+                            pk.f[1] = acc[j][i][2 * h + 1];
+                            __hip_atomic_store(slab + ((j * TP + i) * 2 + h) * NCONS + ctid, pk.u, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                        }
                 // all of this lane's slab stores have reached the device-coherent level
                 __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
             }
@@ -388,21 +400,28 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             if (finish) {
                 if (tid == 0) a.tickets[shared_j] = 0; // ready for the next launch
                 if (!producer) {
+                    // Sum the parts in ascending K order, whichever workgroup finishes (its own part
+                    // is read back like the others, which keeps the accumulators in one register set).
 #pragma unroll
                     for (int j = 0; j < TC; ++j)
 #pragma unroll
                         for (int i = 0; i < TP; ++i) acc[j][i] = (floatx4){0.f, 0.f, 0.f, 0.f};
                     for (int ww = w_first; ww <= w_last; ++ww) {
                         const int fj = (int)(share_begin(sch, ww) / nk);
-                        const float *slab = a.partial + (size_t)(2 * ww + (shared_j == fj ? 0 : 1)) * SLAB;
+                        const unsigned long long *slab = reinterpret_cast<const unsigned long long *>(
+                            a.partial + (size_t)(2 * ww + (shared_j == fj ? 0 : 1)) * SLAB);
 #pragma unroll
                         for (int j = 0; j < TC; ++j)
 #pragma unroll
                             for (int i = 0; i < TP; ++i)
 #pragma unroll
-                                for (int r = 0; r < 4; ++r)
-                                    acc[j][i][r] += __hip_atomic_load(slab + ((j * TP + i) * 4 + r) * NCONS + ctid,
-                                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                for (int h = 0; h < 2; ++h) {
+                                    union { float f[2]; unsigned long long u; } pk;
+                                    pk.u = __hip_atomic_load(slab + ((j * TP + i) * 2 + h) * NCONS + ctid,
+                                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                    acc[j][i][2 * h] += pk.f[0];
+                                    acc[j][i][2 * h + 1] += pk.f[1];
+                                }
                     }
                 }
             }
@@ -412,7 +431,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         // ---- output update: bias, activation, scatter to the stored map; optionally the change
         //      detection of the layer this map feeds (new value against the one it replaces)
         if (finish && !producer) {
-            const bool detect = a.next_chg != nullptr && !a.next_force;
+            const bool detect = a.next_flags != nullptr && !a.next_force;
             bool changed[TP];
 #pragma unroll
             for (int i = 0; i < TP; ++i) changed[i] = false;
@@ -441,8 +460,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                     }
                 }
             }
-            if (a.next_chg) {
-                unsigned long long *bits = reinterpret_cast<unsigned long long *>(a.next_chg);
+            if (a.next_flags) {
 #pragma unroll
                 for (int i = 0; i < TP; ++i) {
                     const int g = sU[wpx0 + i * 16 + lrow];
@@ -450,7 +468,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                     // the other channels of this pixel sit in the lanes 16, 32 and 48 further on
                     f |= __shfl_xor(f, 16);
                     f |= __shfl_xor(f, 32);
-                    if (lk == 0 && f && g >= 0) atomicOr(bits + (g >> 6), 1ull << (g & 63));
+                    if (lk == 0 && f && g >= 0) a.next_flags[g] = 1;
                 }
             }
         }

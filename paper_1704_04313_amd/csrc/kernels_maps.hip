@@ -154,6 +154,26 @@ __device__ __forceinline__ uint64_t bit_run(const uint64_t *__restrict__ m, long
     return v;
 }
 
+// Same question for a map with one byte per pixel (nonzero = changed): is any of the len bytes
+// starting at byte a set?  Eight bytes per step through two aligned 64-bit loads.
+__device__ __forceinline__ bool byte_run_any(const uint64_t *__restrict__ m, long long a, int len)
+{
+    bool any = false;
+    while (len > 0) {
+        const int n = len < 8 ? len : 8;
+        const long long w = a >> 3;
+        const int o = (int)(a & 7) * 8;
+        uint64_t v = m[w] >> o;
+        if (o + n * 8 > 64) v |= m[w + 1] << (64 - o);
+        if (n < 8) v &= (1ull << (n * 8)) - 1ull;
+        any |= v != 0ull;
+        a += n;
+        len -= n;
+    }
+    return any;
+}
+
+template <bool BYTES>
 __device__ __forceinline__ bool field_changed(const uint64_t *__restrict__ m, const DilateGeom &g, int st,
                                               int qy, int qx)
 {
@@ -166,12 +186,16 @@ __device__ __forceinline__ bool field_changed(const uint64_t *__restrict__ m, co
         const int iy = qy * g.stride - g.pad + j;
         if ((unsigned)iy < (unsigned)g.H) {
             const long long a = ((long long)st * g.H + iy) * g.W + x0;
-            any |= bit_run(m, a, len) != 0ull;
+            if (BYTES)
+                any |= byte_run_any(m, a, len);
+            else
+                any |= bit_run(m, a, len) != 0ull;
         }
     }
     return any;
 }
 
+template <bool BYTES>
 __global__ __launch_bounds__(kBlock) void dilate_kernel(const uint64_t *__restrict__ chg,
                                                         uint64_t *__restrict__ upd,
                                                         uint64_t *__restrict__ pool, DilateGeom g,
@@ -185,7 +209,7 @@ __global__ __launch_bounds__(kBlock) void dilate_kernel(const uint64_t *__restri
         if (t < total) {
             const int st = t / No, q = t - st * No;
             const int qy = q / g.Wo, qx = q - qy * g.Wo;
-            f = field_changed(chg, g, st, qy, qx);
+            f = field_changed<BYTES>(chg, g, st, qy, qx);
         }
         const uint64_t word = __ballot(f);
         const int t0 = t & ~63;
@@ -202,13 +226,13 @@ __global__ __launch_bounds__(kBlock) void dilate_kernel(const uint64_t *__restri
             e.stride = g.stride * g.pool_k;
             e.kh = g.kh + (g.pool_k - 1) * g.stride;
             e.kw = g.kw + (g.pool_k - 1) * g.stride;
-            if (g.stride <= g.kh && g.stride <= g.kw && e.kw <= 64) {
+            if (g.stride <= g.kh && g.stride <= g.kw && (BYTES || e.kw <= 64)) {
                 // the k x k outputs' receptive fields tile one larger window without gaps
-                f = field_changed(chg, e, st, py, px);
+                f = field_changed<BYTES>(chg, e, st, py, px);
             } else {
                 for (int a = 0; a < g.pool_k; ++a)
                     for (int b = 0; b < g.pool_k; ++b)
-                        f |= field_changed(chg, g, st, py * g.pool_k + a, px * g.pool_k + b);
+                        f |= field_changed<BYTES>(chg, g, st, py * g.pool_k + a, px * g.pool_k + b);
             }
         }
         const uint64_t word = __ballot(f);
@@ -222,7 +246,12 @@ hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, 
 {
     const int ub = (g.S * g.Ho * g.Wo + kBlock - 1) / kBlock;
     const int pb = (pool_bits && g.pool_k > 0) ? (g.S * g.Hp * g.Wp + kBlock - 1) / kBlock : 0;
-    hipLaunchKernelGGL(dilate_kernel, dim3(ub + pb), dim3(kBlock), 0, st, chg_bits, upd_bits, pool_bits, g, ub);
+    if (g.chg_bytes)
+        hipLaunchKernelGGL(dilate_kernel<true>, dim3(ub + pb), dim3(kBlock), 0, st, chg_bits, upd_bits, pool_bits, g,
+                           ub);
+    else
+        hipLaunchKernelGGL(dilate_kernel<false>, dim3(ub + pb), dim3(kBlock), 0, st, chg_bits, upd_bits, pool_bits, g,
+                           ub);
     return hipGetLastError();
 }
 
@@ -249,6 +278,22 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane)
     return v;
 }
 
+// Word i (64 pixels) of a job's map as a bit mask.  A byte map (one byte per pixel, nonzero =
+// set) is packed on the fly: the high bit of (x | (x & 0x7f..7f) + 0x7f..7f) marks nonzero bytes,
+// and the multiplication gathers those eight marks into one byte.
+__device__ __forceinline__ uint64_t map_word(const CompactJob &job, int i)
+{
+    if (!job.bytes) return job.bits[i];
+    uint64_t w = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const uint64_t x = job.bits[(size_t)i * 8 + k];
+        const uint64_t nz = ((x | ((x & 0x7f7f7f7f7f7f7f7full) + 0x7f7f7f7f7f7f7f7full)) & 0x8080808080808080ull) >> 7;
+        w |= ((nz * 0x0102040810204080ull) >> 56) << (8 * k);
+    }
+    return w;
+}
+
 __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
 {
     __shared__ int stage[kCompactWords * 64];
@@ -261,13 +306,13 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
 
     // set bits in all words before this workgroup's
     int before = 0;
-    for (int i = tid; i < w0; i += kBlock) before += __popcll(job.bits[i]);
+    for (int i = tid; i < w0; i += kBlock) before += __popcll(map_word(job, i));
     before = wave_incl_scan(before, lane);
     if (lane == 63) swave[wave] = before;
 
     // this workgroup's words, one per thread of the first two waves
     uint64_t mine = 0;
-    if (tid < kCompactWords && w0 + tid < job.nwords) mine = job.bits[w0 + tid];
+    if (tid < kCompactWords && w0 + tid < job.nwords) mine = map_word(job, w0 + tid);
     const int cnt = __popcll(mine);
     const int incl = wave_incl_scan(cnt, lane);
     if (lane == 63) swave2[wave] = incl;
@@ -311,7 +356,7 @@ __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restri
                                                              const float4 *__restrict__ in,
                                                              float4 *__restrict__ pooled, int V, int k, int Wo,
                                                              int No, int Wp, int Np,
-                                                             unsigned long long *__restrict__ next_chg,
+                                                             unsigned char *__restrict__ next_flags,
                                                              float next_tau, int next_force)
 {
     const long long total = (long long)(*count) * V;
@@ -333,7 +378,7 @@ __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restri
                 m.z = fmaxf(m.z, a.z);
                 m.w = fmaxf(m.w, a.w);
             }
-        if (next_chg) {
+        if (next_flags) {
             // Change detection of the layer this map feeds (Section 3.1, first formula): the value
             // being replaced is that layer's stored previous input, and positions that are not
             // recomputed cannot differ from it.
@@ -342,9 +387,9 @@ __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restri
             if (pow2) {
                 const unsigned long long B = __ballot(f);
                 const unsigned long long grp = (V == 64) ? ~0ull : (((1ull << V) - 1ull) << (lane & ~(V - 1)));
-                if (v == 0 && (B & grp) != 0ull) atomicOr(next_chg + (g >> 6), 1ull << (g & 63));
+                if (v == 0 && (B & grp) != 0ull) next_flags[g] = 1;
             } else if (f) {
-                atomicOr(next_chg + (g >> 6), 1ull << (g & 63));
+                next_flags[g] = 1;
             }
         }
         pooled[(long long)g * V + v] = m;
@@ -352,7 +397,7 @@ __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restri
 }
 
 hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const float *in,
-                       float *pooled, int Ms, int k, int Wo, int No, int Wp, int Np, uint64_t *next_chg,
+                       float *pooled, int Ms, int k, int Wo, int No, int Wp, int Np, unsigned char *next_flags,
                        float next_tau, int next_force)
 {
     const int V = Ms / 4;
@@ -362,7 +407,7 @@ hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int ma
     if (grid < 1) grid = 1;
     hipLaunchKernelGGL(pool_sparse_kernel, dim3((int)grid), dim3(kBlock), 0, st, list, count,
                        reinterpret_cast<const float4 *>(in), reinterpret_cast<float4 *>(pooled), V, k, Wo, No, Wp,
-                       Np, reinterpret_cast<unsigned long long *>(next_chg), next_tau, next_force);
+                       Np, next_flags, next_tau, next_force);
     return hipGetLastError();
 }
 
