@@ -51,6 +51,7 @@ static constexpr int NCONS = 256;   // consumer threads
 static constexpr int kStages = 3;   // K slices resident in LDS
 static constexpr int kMinIters = 4; // shortest K range worth giving to a workgroup
 static constexpr int kMaxGrid = 1024;
+static constexpr int kSmallTileFactor = 2; // big tiles are used from (workgroups / this) big tiles on
 
 template <int BM, int BN>
 struct TileSmem {
@@ -152,7 +153,7 @@ __device__ __forceinline__ void stage_rows(float *A, float *B, int r0, int v, co
 // first fragments of slice kc+1, so the matrix pipeline keeps running across the one barrier
 // per slice.
 template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_gather_kernel(GemmArgs a)
+__device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n, float *smem)
 {
     static_assert(WM * WN == 4, "four consumer waves");
     constexpr int TP = BN / WN / 16; // 16-pixel MFMA tiles per consumer wave
@@ -165,7 +166,6 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     static_assert(BK == 32, "two 16-wide fragment groups per slice");
     static_assert(TC * TP * 4 * NCONS == SLAB, "a slab holds every consumer lane's accumulators");
 
-    extern __shared__ __align__(16) float smem[];
     float *As = smem;                                      // [3][BN][LDK]  gathered image-matrix slices
     float *Bs = smem + kStages * ASZ;                      // [3][BM][LDK]  filter-matrix slices
     int *sU = reinterpret_cast<int *>(Bs + kStages * BSZ); // [BN] listed pixels of this tile (-1: none)
@@ -176,11 +176,6 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     const int wave = tid >> 6;
     const bool producer = wave >= 4;
 
-    CBK_STAMP(0);
-    // this layer's change bitmap has been condensed into the lists already: clear it for the next frame
-    if (a.clear_bits)
-        for (int i = blockIdx.x * NT + tid; i < a.clear_words; i += gridDim.x * NT) a.clear_bits[i] = 0ull;
-    const int n = *a.count;
     const int mtiles = a.Mpad / BM;
     const int nk = a.Kpad / BK;
     const int W = gridDim.x;
@@ -477,6 +472,29 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     }
 }
 
+// The kernel: clears this layer's change map for the next frame, reads the list length and runs
+// the tile shape that suits it -- BNB listed pixels per tile normally, BNS when even the deepest K
+// split of the big tiles would leave compute units idle (short lists): small tiles then need no
+// or fewer shared tiles, whose partial sums and reduction are pure overhead.
+template <int BM, int BNB, int WMB, int WNB, int BNS, int WMS, int WNS>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_gather_kernel(GemmArgs a)
+{
+    extern __shared__ __align__(16) float smem[];
+    const int tid = threadIdx.x;
+#ifdef CBK_TRACE
+    const int lane = tid & 63, wave = tid >> 6;
+#endif
+    CBK_STAMP(0);
+    if (a.clear_bits)
+        for (int i = blockIdx.x * NT + tid; i < a.clear_words; i += gridDim.x * NT) a.clear_bits[i] = 0ull;
+    const int n = *a.count;
+    const long long big_tiles = (long long)((n + BNB - 1) / BNB) * (a.Mpad / BM);
+    if (big_tiles * kSmallTileFactor >= (long long)gridDim.x)
+        gemm_gather_body<BM, BNB, WMB, WNB>(a, n, smem);
+    else
+        gemm_gather_body<BM, BNS, WMS, WNS>(a, n, smem);
+}
+
 // ---- host side --------------------------------------------------------------------------
 int gemm_k_multiple(void) { return BK; }
 
@@ -507,33 +525,37 @@ int gemm_grid(const GemmArgs &a, int compute_units)
     int W = compute_units & ~7;
     if (W < 8) W = 8;
     if (W > kMaxGrid) W = kMaxGrid;
-    const long long tiles = (long long)((a.max_pixels + bn - 1) / bn) * (a.Mpad / bm);
     const int nk = a.Kpad / BK;
     const int parts = nk / kMinIters > 1 ? nk / kMinIters : 1;
+    // with few pixels the small tile (64 pixels) is used: count those
+    const long long big = (long long)((a.max_pixels + bn - 1) / bn) * (a.Mpad / bm);
+    const long long tiles = big * kSmallTileFactor >= W ? big : (long long)((a.max_pixels + 63) / 64) * (a.Mpad / bm);
     long long need = tiles >= W ? W : (tiles * parts + 7) / 8 * 8;
     if (need < 8) need = 8;
     return (int)(need < W ? need : W);
 }
 
-#define CBK_VARIANTS(X) X(16, 256, 1, 4) X(32, 256, 1, 4) X(64, 256, 1, 4) X(128, 128, 2, 2)
+// BM, big tile (BN, WM, WN), small tile (BN, WM, WN)
+#define CBK_VARIANTS(X) X(16, 256, 1, 4, 64, 1, 4) X(32, 256, 1, 4, 64, 1, 4) X(64, 256, 1, 4, 64, 1, 4) X(128, 128, 2, 2, 64, 2, 2)
 
 hipError_t gemm_prepare(void)
 {
     hipError_t e = hipSuccess;
-#define X(BM_, BN_, WM_, WN_)                                                                            \
-    if (e == hipSuccess)                                                                                 \
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_gather_kernel<BM_, BN_, WM_, WN_>), \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, TileSmem<BM_, BN_>::bytes);
+#define X(BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_)                                                            \
+    if (e == hipSuccess)                                                                                      \
+        e = hipFuncSetAttribute(                                                                              \
+            reinterpret_cast<const void *>(&gemm_gather_kernel<BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_>),      \
+            hipFuncAttributeMaxDynamicSharedMemorySize, TileSmem<BM_, BNB_>::bytes);
     CBK_VARIANTS(X)
 #undef X
     return e;
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BNB, int WMB, int WNB, int BNS, int WMS, int WNS>
 static hipError_t launch(hipStream_t st, const GemmArgs &a)
 {
-    constexpr int smem_bytes = TileSmem<BM, BN>::bytes;
-    gemm_gather_kernel<BM, BN, WM, WN><<<dim3(a.grid), dim3(NT), smem_bytes, st>>>(a);
+    constexpr int smem_bytes = TileSmem<BM, BNB>::bytes;
+    gemm_gather_kernel<BM, BNB, WMB, WNB, BNS, WMS, WNS><<<dim3(a.grid), dim3(NT), smem_bytes, st>>>(a);
     return hipGetLastError();
 }
 
@@ -544,10 +566,10 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a)
         (a.grid & 7))
         return hipErrorInvalidValue;
     switch (bm) {
-    case 16: return launch<16, 256, 1, 4>(st, a);
-    case 32: return launch<32, 256, 1, 4>(st, a);
-    case 64: return launch<64, 256, 1, 4>(st, a);
-    default: return launch<128, 128, 2, 2>(st, a);
+    case 16: return launch<16, 256, 1, 4, 64, 1, 4>(st, a);
+    case 32: return launch<32, 256, 1, 4, 64, 1, 4>(st, a);
+    case 64: return launch<64, 256, 1, 4, 64, 1, 4>(st, a);
+    default: return launch<128, 128, 2, 2, 64, 2, 2>(st, a);
     }
 }
 
