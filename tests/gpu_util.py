@@ -79,3 +79,59 @@ def oracle_layer_inputs(layers, params, frames, tau, hold=False):
         for l in rec:
             rec[l].append(np.array(orc.trace[l]["x"], copy=True))
     return rec
+
+
+def compare_sampled(layer, params, frames, tau, *, n_samples=600, n_streams=1, seed=0, label=""):
+    """Full-size check of one convolution layer on inputs too large for a complete oracle run.
+    `frames`: planar inputs [S][C][H][W] (or [C][H][W]); frame 0 is evaluated densely.
+    Lists and counts are compared exactly on every frame (the oracle's detection, dilation and
+    extraction are cheap at any size).  Feature values are compared on sampled output positions
+    that the oracle computes one by one: a position recomputed in frame t must equal the
+    convolution of frame t's input, any other position the value of the last frame in which it was
+    recomputed."""
+    import torch
+    L = layer
+    frames = [np.asarray(f, dtype=np.float32).reshape((n_streams,) + f.shape[-3:]) for f in frames]
+    S, C, H, W = frames[0].shape
+    w, b = params
+    net = cb.CBInfer([L], [params], (C, H, W), tau, n_streams=S)
+    Ho, Wo = (H + 2 * L.pad - L.kh) // L.stride + 1, (W + 2 * L.pad - L.kw) // L.stride + 1
+    r = np.random.default_rng(seed)
+    last_update = [np.zeros(Ho * Wo, np.int64) for _ in range(S)]      # frame index of last recompute
+    try:
+        for t, fr in enumerate(frames):
+            got = net.process_frame(to_dev(fr)).cpu().numpy()
+            c_gpu = net.read_list(0, cb.LIST_CHANGED)
+            u_gpu = net.read_list(0, cb.LIST_UPDATE)
+            c_all, u_all = [], []
+            for s in range(S):
+                if t == 0:
+                    flags = np.ones((H, W), np.uint8)
+                else:
+                    flags = oracle.detect(fr[s], frames[t - 1][s], tau)
+                upd = oracle.update_set(flags, L.kh, L.kw, L.stride, L.pad)
+                c_all.append(oracle.extract(flags) + s * H * W)
+                ul = oracle.extract(upd)
+                u_all.append(ul + s * Ho * Wo)
+                last_update[s][ul] = t
+            what = "%s frame %d" % (label, t)
+            np.testing.assert_array_equal(c_gpu, np.concatenate(c_all), err_msg=what + " changed list")
+            np.testing.assert_array_equal(u_gpu, np.concatenate(u_all), err_msg=what + " update list")
+            assert net.layer_counts(0) == (c_gpu.size, u_gpu.size)
+            # sampled features: half of the samples among this frame's updates when there are any
+            for s in range(S if S <= 4 else 4):
+                ss = s if S <= 4 else int(r.integers(0, S))
+                pos = r.integers(0, Ho * Wo, n_samples // 2)
+                ul = u_all[ss] - ss * Ho * Wo
+                if ul.size:
+                    pos = np.concatenate([pos, r.choice(ul, n_samples // 2)])
+                pos = np.unique(pos).astype(np.int32)
+                for tt in np.unique(last_update[ss][pos]):
+                    sel = pos[last_update[ss][pos] == tt]
+                    want = np.zeros((L.cout, Ho, Wo), np.float32)
+                    oracle.conv_update(frames[int(tt)][ss], w, b, sel, want, L.stride, L.pad, L.relu)
+                    g = got[ss].reshape(L.cout, -1)[:, sel]
+                    assert_features_close(g, want.reshape(L.cout, -1)[:, sel],
+                                          "%s stream %d, positions last recomputed in frame %d" % (what, ss, tt))
+    finally:
+        net.destroy()
