@@ -37,6 +37,13 @@ def build_workload(args):
         cfg = get_config(2)
     elif args.workload == "cfg3":
         cfg = get_config(3, change_rate=args.rate, sigma=args.sigma, n_frames=args.frames or 24)
+    elif args.workload == "hbm":
+        # One 1x1 layer on a 3x4096x4096 frame with a handful of changing pixels: everything but
+        # change detection is negligible, and a frame's traffic (~0.7 GB) exceeds the last-level
+        # cache, so the detection kernel's rate is an HBM rate.
+        from workloads import Config, conv
+        cfg = Config("hbm-detect-4096x4096x3", 0, [conv(3, 4, 1, relu=False)], 4096, 4096, 3,
+                     args.frames or 3, 0.02, 0.0, video_kwargs={"n_objects": 2})
     else:
         raise SystemExit("unknown workload " + args.workload)
     if args.frames:
@@ -76,7 +83,7 @@ def cpu_baseline(cfg, budget_s: float):
                       "OpenMP over output positions), frame 0 untimed" % (cfg.name, n)}
 
 
-def main():
+def parse_args(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
@@ -87,7 +94,13 @@ def main():
     ap.add_argument("--frames", type=int, default=0, help="frames generated (default: the workload's)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg (0: skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel timing pass")
-    args = ap.parse_args()
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run three 256 MiB device copies (reference for profiler byte counters)")
+    return ap.parse_args(argv)
+
+
+def run(args) -> dict:
+    """One benchmark run; returns the result record that main() prints as a JSON line."""
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one process, one MI355X); --gpus %d is not "
               "supported" % args.gpus, file=sys.stderr)
@@ -100,6 +113,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
+
+    if args.calibrate_copy:
+        # a plain device copy of known size (256 MiB read + 256 MiB written) so that HBM byte
+        # counters of a profiler run over this process can be scaled
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cfg = build_workload(args)
     params = cfg.weights()
@@ -206,7 +229,11 @@ def main():
 
     net.destroy()
     result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds) if args.cpu_seconds > 0 else None
-    print(json.dumps(result))
+    return result
+
+
+def main():
+    print(json.dumps(run(parse_args())))
 
 
 if __name__ == "__main__":

@@ -67,7 +67,7 @@ struct Op {
     // workspace offsets (bytes); SIZE_MAX = absent
     size_t o_ref = SIZE_MAX, o_cur = SIZE_MAX, o_out = SIZE_MAX, o_wt = SIZE_MAX, o_bias = SIZE_MAX,
            o_taps = SIZE_MAX, o_chg = SIZE_MAX, o_upd = SIZE_MAX, o_pool = SIZE_MAX, o_clist = SIZE_MAX,
-           o_ulist = SIZE_MAX, o_counts = SIZE_MAX;
+           o_ulist = SIZE_MAX, o_counts = SIZE_MAX, o_groups = SIZE_MAX;
 };
 
 struct Plan {
@@ -199,6 +199,8 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
                 op.o_pool = cv.take(((size_t)words_for((long long)P.S * pp.Ho * pp.Wo) + 1) * 8);
             }
             op.o_clist = cv.take(in_px * 4);
+            // group counts of the three maps condensed per layer (changed, update, pooled)
+            op.o_groups = cv.take(3 * cbk::compact_group_count_bytes(words_for((long long)std::max(in_px, out_px))));
         }
     }
     P.iota_len = (int)max_px;
@@ -382,18 +384,25 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                     g.pool_k = pp.kh; g.Hp = pp.Ho; g.Wp = pp.Wo;
                     pool_bits = s->at<uint64_t>(op.o_pool);
                 }
-                {
+                // a 1x1 layer's outputs to update are its changed inputs: no dilation needed when the
+                // change map is already a bitmap and no pooled set is wanted
+                const bool identity = op.kh == 1 && op.kw == 1 && op.stride == 1 && op.pad == 0 && !fused_in &&
+                                      !pool_bits;
+                uint64_t *upd_bits = identity ? s->at<uint64_t>(op.o_chg) : s->at<uint64_t>(op.o_upd);
+                if (!identity) {
                     StepTimer t(s, l, CBINFER_STEP_DILATE);
-                    HIP_TRY(cbk::dilate(st, s->at<uint64_t>(op.o_chg), s->at<uint64_t>(op.o_upd), pool_bits, g));
+                    HIP_TRY(cbk::dilate(st, s->at<uint64_t>(op.o_chg), upd_bits, pool_bits, g));
                 }
                 cbk::CompactJob jobs[3];
                 int nj = 0;
-                jobs[nj++] = {s->at<uint64_t>(op.o_upd), 0, words_for((long long)S * No), s->at<int>(op.o_ulist), counts + 1};
-                jobs[nj++] = {s->at<uint64_t>(op.o_chg), fused_in ? 1 : 0, words_for((long long)S * N), s->at<int>(op.o_clist), counts + 0};
+                const size_t gstride = cbk::compact_group_count_bytes(words_for((long long)S * std::max(N, No))) / sizeof(int);
+                int *groups = s->at<int>(op.o_groups);
+                jobs[nj++] = {upd_bits, 0, words_for((long long)S * No), s->at<int>(op.o_ulist), counts + 1, groups};
+                jobs[nj++] = {s->at<uint64_t>(op.o_chg), fused_in ? 1 : 0, words_for((long long)S * N), s->at<int>(op.o_clist), counts + 0, groups + gstride};
                 if (op.pool_after >= 0) {
                     const Op &pp = P.ops[op.pool_after];
                     jobs[nj++] = {pool_bits, 0, words_for((long long)S * pp.Ho * pp.Wo), s->at<int>(pp.o_ulist),
-                                  s->at<int>(pp.o_counts) + 1};
+                                  s->at<int>(pp.o_counts) + 1, groups + 2 * gstride};
                 }
                 {
                     StepTimer t(s, l, CBINFER_STEP_COMPACT);

@@ -53,7 +53,11 @@ struct CompactJob {
     int nwords;           // 64-pixel words
     int *list;
     int *count;
+    int *group_counts;    // scratch of compact_group_count_bytes(nwords) bytes; needed (non-null) when
+                          // compact_two_level(nwords), i.e. for maps of several hundred thousand pixels
 };
+bool compact_two_level(int nwords);
+size_t compact_group_count_bytes(int nwords);
 hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs);
 
 // ---- gathered matrix generation + multiplication + output update (Section 3.1) -------------

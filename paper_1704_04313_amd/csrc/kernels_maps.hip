@@ -294,6 +294,24 @@ __device__ __forceinline__ uint64_t map_word(const CompactJob &job, int i)
     return w;
 }
 
+// Set bits per workgroup-sized group of words, for maps with so many groups that letting every
+// workgroup recount all preceding words would dominate (see compact_kernel).
+__global__ __launch_bounds__(kBlock) void compact_count_kernel(CompactJobs jobs)
+{
+    __shared__ int swave[4];
+    const CompactJob job = jobs.j[blockIdx.y];
+    const int w0 = blockIdx.x * kCompactWords;
+    if (w0 >= job.nwords) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int c = 0;
+    if (tid < kCompactWords && w0 + tid < job.nwords) c = __popcll(map_word(job, w0 + tid));
+    c = wave_incl_scan(c, lane);
+    if (lane == 63) swave[wave] = c;
+    __syncthreads();
+    if (tid == 0) job.group_counts[blockIdx.x] = swave[0] + swave[1] + swave[2] + swave[3];
+}
+
+template <bool TWO_LEVEL>
 __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
 {
     __shared__ int stage[kCompactWords * 64];
@@ -306,7 +324,11 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
 
     // set bits in all words before this workgroup's
     int before = 0;
-    for (int i = tid; i < w0; i += kBlock) before += __popcll(map_word(job, i));
+    if (TWO_LEVEL) {
+        for (int i = tid; i < (int)blockIdx.x; i += kBlock) before += job.group_counts[i];
+    } else {
+        for (int i = tid; i < w0; i += kBlock) before += __popcll(map_word(job, i));
+    }
     before = wave_incl_scan(before, lane);
     if (lane == 63) swave[wave] = before;
 
@@ -333,6 +355,10 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
     if (tid == 0 && w0 + kCompactWords >= job.nwords) *job.count = prefix + total;
 }
 
+bool compact_two_level(int nwords) { return nwords > kCompactWords * 48; }
+
+size_t compact_group_count_bytes(int nwords) { return ((size_t)nwords / kCompactWords + 2) * sizeof(int); }
+
 hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs)
 {
     if (njobs < 1 || njobs > 3) return hipErrorInvalidValue;
@@ -343,7 +369,14 @@ hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs)
         if (i < njobs && jobs[i].nwords > maxw) maxw = jobs[i].nwords;
     }
     const int gx = (maxw + kCompactWords - 1) / kCompactWords;
-    hipLaunchKernelGGL(compact_kernel, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+    if (compact_two_level(maxw)) {
+        for (int i = 0; i < njobs; ++i)
+            if (!jobs[i].group_counts) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(compact_count_kernel, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+        hipLaunchKernelGGL(compact_kernel<true>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+    } else {
+        hipLaunchKernelGGL(compact_kernel<false>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+    }
     return hipGetLastError();
 }
 
@@ -415,26 +448,35 @@ hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int ma
 // Stored map [S*No][Ms] -> planar [S][M][No].  Consecutive lanes take consecutive pixels of
 // one channel plane so the planar writes are coalesced.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void map_to_planar_kernel(const float *__restrict__ map,
-                                                               float *__restrict__ planar, int M, int Ms,
+__global__ __launch_bounds__(kBlock) void map_to_planar_kernel(const float4 *__restrict__ map,
+                                                               float *__restrict__ planar, int M, int V,
                                                                int No, long long total)
 {
+    // idx = (stream * V + channel group) * No + pixel: consecutive lanes read consecutive pixels'
+    // float4 (stride Ms floats) and write four planes, each a contiguous run per wave
     for (long long idx = (long long)blockIdx.x * kBlock + threadIdx.x; idx < total;
          idx += (long long)gridDim.x * kBlock) {
         const int q = (int)(idx % No);
-        const long long sc = idx / No;
-        const int c = (int)(sc % M);
-        const long long st = sc / M;
-        planar[idx] = map[(st * No + q) * Ms + c];
+        const long long sv = idx / No;
+        const int v = (int)(sv % V);
+        const long long st = sv / V;
+        const float4 a = map[(st * No + q) * V + v];
+        float *dst = planar + (st * M + 4 * v) * No + q;
+        dst[0] = a.x;
+        if (4 * v + 1 < M) dst[No] = a.y;
+        if (4 * v + 2 < M) dst[2 * (long long)No] = a.z;
+        if (4 * v + 3 < M) dst[3 * (long long)No] = a.w;
     }
 }
 
 hipError_t map_to_planar(hipStream_t st, const float *map, float *planar, int M, int Ms, int No, int S)
 {
-    const long long total = (long long)S * M * No;
+    const int V = Ms / 4;
+    const long long total = (long long)S * V * No;
     long long grid = (total + kBlock - 1) / kBlock;
-    if (grid > 4096) grid = 4096;
-    hipLaunchKernelGGL(map_to_planar_kernel, dim3((int)grid), dim3(kBlock), 0, st, map, planar, M, Ms, No, total);
+    if (grid > 8192) grid = 8192;
+    hipLaunchKernelGGL(map_to_planar_kernel, dim3((int)grid), dim3(kBlock), 0, st,
+                       reinterpret_cast<const float4 *>(map), planar, M, V, No, total);
     return hipGetLastError();
 }
 
