@@ -30,6 +30,16 @@
 namespace cbk {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+
+// Partial accumulators cross between workgroups that may sit on different XCDs (separate L2s).
+// They are written and read with buffer instructions carrying the sc1 bit: write-through to, and
+// read at, the level all XCDs share, so no cache-wide write-back or invalidate is needed.
+static constexpr int kDeviceCoherent = 0x10; // cache-policy operand: sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const float *p, int bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p), 0, bytes, 0x00020000);
+}
 
 #ifdef CBK_TRACE
 // timing study builds only: lane 0 of wave 0 (consumer) and of wave 4 (producer) stamp events
@@ -49,9 +59,15 @@ static constexpr int NT = 512;      // threads per workgroup: 4 consumer + 4 pro
 static constexpr int NPROD = 256;   // producer threads
 static constexpr int NCONS = 256;   // consumer threads
 static constexpr int kStages = 3;   // K slices resident in LDS
-static constexpr int kMinIters = 4; // shortest K range worth giving to a workgroup
+#ifndef CBK_MIN_ITERS
+#define CBK_MIN_ITERS 8
+#endif
+#ifndef CBK_SMALL_FACTOR
+#define CBK_SMALL_FACTOR 2
+#endif
+static constexpr int kMinIters = CBK_MIN_ITERS; // shortest K range worth giving to a workgroup
 static constexpr int kMaxGrid = 1024;
-static constexpr int kSmallTileFactor = 2; // big tiles are used from (workgroups / this) big tiles on
+static constexpr int kSmallTileFactor = CBK_SMALL_FACTOR; // big tiles are used from (workgroups / this) big tiles on
 
 template <int BM, int BN>
 struct TileSmem {
@@ -355,9 +371,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
 
         // ---- a shared tile: store this K range's accumulators, take a ticket; the workgroup
         //      holding the last ticket adds up all ranges (ascending K) and does the output update.
-        //      Slab traffic uses device-scope atomic stores and loads (write-through / read at the
-        //      level all XCDs share), completed before the ticket is taken, so no cache-wide
-        //      write-back or invalidate is needed to make the parts visible across XCDs.
+        //      Slab stores are complete (vmcnt(0)) before the ticket is taken.
         CBK_STAMP(4 + 6 * seg);
         bool finish = true;
         if (partial) {
@@ -367,22 +381,16 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             const int ctid = tid & (NCONS - 1);
             if (!producer) {
                 // slab 2*wsh + (0: first tile this workgroup touches, 1: a later one), register layout:
-                // accumulator halves as 64-bit words, consecutive lanes consecutive addresses
+                // one float4 per lane and accumulator, consecutive lanes consecutive addresses
                 const int first_j = (int)(it_begin / nk);
-                unsigned long long *slab = reinterpret_cast<unsigned long long *>(
-                    a.partial + (size_t)(2 * wsh + (shared_j == first_j ? 0 : 1)) * SLAB);
+                const __amdgpu_buffer_rsrc_t slab = slab_resource(
+                    a.partial + (size_t)(2 * wsh + (shared_j == first_j ? 0 : 1)) * SLAB, SLAB * 4);
 #pragma unroll
                 for (int j = 0; j < TC; ++j)
 #pragma unroll
                     for (int i = 0; i < TP; ++i)
-#pragma unroll
-                        for (int h = 0; h < 2; ++h) {
-                            union { float f[2]; unsigned long long u; } pk;
-                            pk.f[0] = acc[j][i][2 * h];
-                            pk.f[1] = acc[j][i][2 * h + 1];
-                            __hip_atomic_store(slab + ((j * TP + i) * 2 + h) * NCONS + ctid, pk.u, __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_AGENT);
-                        }
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, acc[j][i]), slab,
+                                                               ((j * TP + i) * NCONS + ctid) * 16, 0, kDeviceCoherent);
                 // all of this lane's slab stores have reached the device-coherent level
                 __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
             }
@@ -403,20 +411,20 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                         for (int i = 0; i < TP; ++i) acc[j][i] = (floatx4){0.f, 0.f, 0.f, 0.f};
                     for (int ww = w_first; ww <= w_last; ++ww) {
                         const int fj = (int)(share_begin(sch, ww) / nk);
-                        const unsigned long long *slab = reinterpret_cast<const unsigned long long *>(
-                            a.partial + (size_t)(2 * ww + (shared_j == fj ? 0 : 1)) * SLAB);
+                        const __amdgpu_buffer_rsrc_t slab = slab_resource(
+                            a.partial + (size_t)(2 * ww + (shared_j == fj ? 0 : 1)) * SLAB, SLAB * 4);
+                        floatx4 part[TC][TP];
 #pragma unroll
                         for (int j = 0; j < TC; ++j)
 #pragma unroll
                             for (int i = 0; i < TP; ++i)
+                                part[j][i] = __builtin_bit_cast(
+                                    floatx4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                 slab, ((j * TP + i) * NCONS + ctid) * 16, 0, kDeviceCoherent));
 #pragma unroll
-                                for (int h = 0; h < 2; ++h) {
-                                    union { float f[2]; unsigned long long u; } pk;
-                                    pk.u = __hip_atomic_load(slab + ((j * TP + i) * 2 + h) * NCONS + ctid,
-                                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                    acc[j][i][2 * h] += pk.f[0];
-                                    acc[j][i][2 * h + 1] += pk.f[1];
-                                }
+                        for (int j = 0; j < TC; ++j)
+#pragma unroll
+                            for (int i = 0; i < TP; ++i) acc[j][i] += part[j][i];
                     }
                 }
             }
