@@ -19,6 +19,10 @@ import numpy as np
 
 MI355X_HBM_GBS = 8000.0
 MI355X_FP32_MFMA_TFLOPS = 157.3
+# HBM bytes per launch of the dominant kernel (gathered GEMM of the 64->256 7x7 layer) on the
+# benchmark workload, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by a plain
+# copy of known size); the commands and figures are in profiles/cfg2_hbm_traffic.md.
+CFG2_DOMINANT_GEMM_HBM_BYTES = 61.9e6
 
 
 def frame_order(n_frames: int, count: int, start: int = 0):
@@ -37,6 +41,8 @@ def build_workload(args):
         cfg = get_config(2)
     elif args.workload == "cfg3":
         cfg = get_config(3, change_rate=args.rate, sigma=args.sigma, n_frames=args.frames or 24)
+    elif args.workload == "cfg5":
+        cfg = get_config(5, n_frames=args.frames or 12)
     elif args.workload == "hbm":
         # One 1x1 layer on a 3x4096x4096 frame with a handful of changing pixels: everything but
         # change detection is negligible, and a frame's traffic (~0.7 GB) exceeds the last-level
@@ -126,11 +132,14 @@ def run(args) -> dict:
 
     cfg = build_workload(args)
     params = cfg.weights()
-    video = cfg.video()
-    frames = np.stack([video.frame(t) for t in range(cfg.n_frames)])
+    videos = [cfg.video(s) for s in range(cfg.n_streams)]
+    if cfg.n_streams == 1:
+        frames = np.stack([videos[0].frame(t) for t in range(cfg.n_frames)])
+    else:   # [T][S][C][H][W]: one frame of every stream per step
+        frames = np.stack([np.stack([v.frame(t) for v in videos]) for t in range(cfg.n_frames)])
     frames_dev = torch.from_numpy(frames).cuda()
     in_shape = (cfg.channels, cfg.height, cfg.width)
-    net = cb.CBInfer(cfg.layers, params, in_shape, cfg.tau)
+    net = cb.CBInfer(cfg.layers, params, in_shape, cfg.tau, n_streams=cfg.n_streams)
     out = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
 
     W, K = args.warmup, args.steps
@@ -148,13 +157,13 @@ def run(args) -> dict:
 
     result = {
         "metric": "frames/s and speed-up vs dense HIP conv at 1/5/20% change rate; HBM GB/s",
-        "value": K / sec_cb, "unit": "frames/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "value": cfg.n_streams * K / sec_cb, "unit": "frames/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": 1e3 * sec_cb / K, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "frame": "%dx%dx%d" % (cfg.width, cfg.height, cfg.channels),
-                   "tau": cfg.tau, "sigma": cfg.sigma, "n_frames": cfg.n_frames, "n_streams": 1,
+                   "tau": cfg.tau, "sigma": cfg.sigma, "n_frames": cfg.n_frames, "n_streams": cfg.n_streams,
                    "reference_update": "previous frame"},
-        "dense_hip_frames_per_s": K / sec_dense,
+        "dense_hip_frames_per_s": cfg.n_streams * K / sec_dense,
         "speedup_vs_dense_hip": sec_dense / sec_cb,
         "paper_context": "8.6x (Tegra X1) / 7.6x (GTX 1080) over cuDNN, 327.6 GOp/s/W; other hardware, other data",
     }
@@ -186,7 +195,7 @@ def run(args) -> dict:
             L = cfg.layers[l]
             c_in, h_in, w_in = shapes[l]
             c_out, h_out, w_out = shapes[l + 1]
-            n_c, n_u = sums[l] / P
+            n_c, n_u = sums[l] / P / cfg.n_streams
             if L.kind == "conv":
                 rates["L%d" % l] = {"changed_in": n_c / (h_in * w_in), "updated_out": n_u / (h_out * w_out)}
             else:
@@ -196,10 +205,10 @@ def run(args) -> dict:
                     continue
                 e = {"us": 1e3 * ms}
                 if name == "detect":
-                    by = 12.0 * c_in * h_in * w_in + h_in * w_in / 8.0
+                    by = cfg.n_streams * (12.0 * c_in * h_in * w_in + h_in * w_in / 8.0)
                     e.update(bytes=by, GBps=by / (ms * 1e-3) / 1e9, frac_hbm=by / (ms * 1e-3) / 1e9 / MI355X_HBM_GBS)
                 elif name == "gemm":
-                    fl = 2.0 * L.cout * L.cin * L.kh * L.kw * n_u
+                    fl = 2.0 * L.cout * L.cin * L.kh * L.kw * n_u * cfg.n_streams
                     e.update(flops=fl, TFLOPs=fl / (ms * 1e-3) / 1e12,
                              frac_mfma=fl / (ms * 1e-3) / 1e12 / MI355X_FP32_MFMA_TFLOPS)
                 elif name == "compact":
@@ -217,13 +226,15 @@ def run(args) -> dict:
         else:
             roof = {"bound": "hbm", "achieved": d.get("GBps"), "peak": MI355X_HBM_GBS, "unit": "GB/s",
                     "frac": (d.get("GBps") or 0.0) / MI355X_HBM_GBS, "traffic": None}
+        if cfg.name.startswith("cfg2") and dom == "L4.gemm":
+            roof["traffic"] = CFG2_DOMINANT_GEMM_HBM_BYTES
         roof["kernel"] = dom
         roof["avg_us"] = d["us"]
         roof["sum_kernel_us_per_frame"] = sum(k["us"] for k in kernels.values())
         result["roofline"] = roof
         result["kernels"] = kernels
         result["change_rates"] = rates
-        result["dense_gflop_per_frame"] = sum(dense_flops(cfg.layers, *in_shape)) / 1e9
+        result["dense_gflop_per_frame"] = sum(dense_flops(cfg.layers, *in_shape)) / 1e9    # per stream
     else:
         result["roofline"] = None
 
