@@ -278,45 +278,59 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             }
             const float *wrow = a.wt + (size_t)(mt * BM + r0) * a.Kpad + v * 4;
             const int2 *taps = a.taps + v;
-            floatx4 ra[PA], rb[PB], ra2[PA], rb2[PB];
-            // prologue: slices kc0 and kc0+1 into ring slots 0 and 1, slice kc0+2 into registers.
-            // The tap descriptor of a slice is loaded ahead of the operand loads that need it.
-            const int2 t0 = taps[kc0 * (BK / 4)];
-            const int2 t1 = taps[(kc0 + 1 < kc1 ? kc0 + 1 : kc0) * (BK / 4)];
-            int2 tp = taps[(kc0 + 2 < kc1 ? kc0 + 2 : kc0) * (BK / 4)];
-            gather_rows<PA>(a, t0, iy0, ix0, base, ra);
-            load_filter_rows<BM, PB>(wrow, a.Kpad, kc0, r0, rb);
+            // Two register sets: while the slice loaded two iterations ago is stored to LDS, the
+            // loads of the slice after next are already in flight (a slice of MFMA work is shorter
+            // than a global-memory round trip for the small tiles).  The tap descriptor of a slice
+            // is loaded before the operand loads that need it.
+            floatx4 raA[PA], rbA[PB], raB[PA], rbB[PB];
+            auto tap = [&](int kc) { return taps[(kc < kc1 ? kc : kc0) * (BK / 4)]; };
+            int2 tpA = tap(kc0), tpB = tap(kc0 + 1);
+            const int2 t2 = tap(kc0 + 2), t3 = tap(kc0 + 3);
+            // prologue: slices kc0 and kc0+1 into ring slots 0 and 1, slices kc0+2 and kc0+3 in flight
+            gather_rows<PA>(a, tpA, iy0, ix0, base, raA);
+            load_filter_rows<BM, PB>(wrow, a.Kpad, kc0, r0, rbA);
             if (kc0 + 1 < kc1) {
-                gather_rows<PA>(a, t1, iy0, ix0, base, ra2);
-                load_filter_rows<BM, PB>(wrow, a.Kpad, kc0 + 1, r0, rb2);
+                gather_rows<PA>(a, tpB, iy0, ix0, base, raB);
+                load_filter_rows<BM, PB>(wrow, a.Kpad, kc0 + 1, r0, rbB);
             }
-            stage_rows<BM, PA, PB>(As, Bs, r0, v, ra, rb);
-            if (kc0 + 1 < kc1) stage_rows<BM, PA, PB>(As + ASZ, Bs + BSZ, r0, v, ra2, rb2);
+            tpA = tap(kc0 + 4);
+            tpB = tap(kc0 + 5);
+            stage_rows<BM, PA, PB>(As, Bs, r0, v, raA, rbA);
+            if (kc0 + 1 < kc1) stage_rows<BM, PA, PB>(As + ASZ, Bs + BSZ, r0, v, raB, rbB);
             if (kc0 + 2 < kc1) {
-                gather_rows<PA>(a, tp, iy0, ix0, base, ra);
-                load_filter_rows<BM, PB>(wrow, a.Kpad, kc0 + 2, r0, rb);
-                if (kc0 + 3 < kc1) tp = taps[(kc0 + 3) * (BK / 4)];
+                gather_rows<PA>(a, t2, iy0, ix0, base, raA);
+                load_filter_rows<BM, PB>(wrow, a.Kpad, kc0 + 2, r0, rbA);
+            }
+            if (kc0 + 3 < kc1) {
+                gather_rows<PA>(a, t3, iy0, ix0, base, raB);
+                load_filter_rows<BM, PB>(wrow, a.Kpad, kc0 + 3, r0, rbB);
             }
             __syncthreads();
             CBK_STAMP(3 + 6 * seg);
             int slot = 2; // ring slot of slice kc+2
-            for (int kc = kc0; kc < kc1; ++kc) {
+            for (int kc = kc0; kc < kc1; kc += 2) {
                 if (kc + 2 < kc1) {
-#ifndef CBK_EXP_NOSTAGE
-                    stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, v, ra, rb);
-#endif
-                    if (kc + 3 < kc1) {
-#ifndef CBK_EXP_NOGATHER
-                        gather_rows<PA>(a, tp, iy0, ix0, base, ra);
-#endif
-#ifndef CBK_EXP_NOFILTER
-                        load_filter_rows<BM, PB>(wrow, a.Kpad, kc + 3, r0, rb);
-#endif
-                        if (kc + 4 < kc1) tp = taps[(kc + 4) * (BK / 4)];
+                    stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, v, raA, rbA);
+                    if (kc + 4 < kc1) {
+                        gather_rows<PA>(a, tpA, iy0, ix0, base, raA);
+                        load_filter_rows<BM, PB>(wrow, a.Kpad, kc + 4, r0, rbA);
+                        tpA = tap(kc + 6);
                     }
                 }
                 slot = slot == kStages - 1 ? 0 : slot + 1;
                 __syncthreads();
+                if (kc + 1 < kc1) {
+                    if (kc + 3 < kc1) {
+                        stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, v, raB, rbB);
+                        if (kc + 5 < kc1) {
+                            gather_rows<PA>(a, tpB, iy0, ix0, base, raB);
+                            load_filter_rows<BM, PB>(wrow, a.Kpad, kc + 5, r0, rbB);
+                            tpB = tap(kc + 7);
+                        }
+                    }
+                    slot = slot == kStages - 1 ? 0 : slot + 1;
+                    __syncthreads();
+                }
             }
         } else {
             const float *A0 = As + (wpx0 + lrow) * LDK + lk * 4;
