@@ -97,7 +97,7 @@ def _last_error(lib) -> str:
     return (lib.cbinfer_last_error() or b"").decode("utf-8", "replace")
 
 
-def _describe(layers, params, in_shape, n_streams, flags, tau_per_layer, dense_layers, keep):
+def _describe(layers, params, in_shape, n_streams, flags, tau_per_layer, dense_layers, keep, dtype=F32):
     """Build the C network description.  `keep` collects every numpy array the pointers refer to."""
     arr = (cbinfer_layer * len(layers))()
     for l, L in enumerate(layers):
@@ -124,16 +124,16 @@ def _describe(layers, params, in_shape, n_streams, flags, tau_per_layer, dense_l
     net.layers = arr
     net.in_c, net.in_h, net.in_w = (int(v) for v in in_shape)
     net.n_streams = int(n_streams)
-    net.dtype = F32
+    net.dtype = int(dtype)
     net.flags = int(flags)
     keep.append(arr)
     return net
 
 
-def cbinfer_workspace_bytes(layers, params, in_shape, n_streams=1, flags=0) -> int:
+def cbinfer_workspace_bytes(layers, params, in_shape, n_streams=1, flags=0, dtype=F32) -> int:
     lib = load_library()
     keep: list = []
-    net = _describe(layers, params, in_shape, n_streams, flags, None, (), keep)
+    net = _describe(layers, params, in_shape, n_streams, flags, None, (), keep, dtype)
     n = lib.cbinfer_workspace_bytes(C.byref(net))
     if n == 0:
         raise CBInferError(-1, _last_error(lib))
@@ -145,7 +145,7 @@ class CBInfer:
     all work is enqueued on the torch stream that was current at construction."""
 
     def __init__(self, layers, params, in_shape, tau, *, n_streams: int = 1, hold_reference: bool = False,
-                 dense_layers: Sequence[int] = (), caller_workspace: bool = True):
+                 dense_layers: Sequence[int] = (), caller_workspace: bool = True, dtype: int = F32):
         import torch
         self._torch = torch
         self.lib = load_library()
@@ -158,7 +158,9 @@ class CBInfer:
         global_tau = float(tau) if np.isscalar(tau) else 0.0
         keep: list = []
         flags = FLAG_HOLD_REFERENCE if hold_reference else 0
-        net = _describe(self.layers, params, self.in_shape, n_streams, flags, per_layer, set(dense_layers), keep)
+        self.dtype = int(dtype)
+        net = _describe(self.layers, params, self.in_shape, n_streams, flags, per_layer, set(dense_layers), keep,
+                        self.dtype)
         self.stream = torch.cuda.current_stream()
         net.stream = C.c_void_p(self.stream.cuda_stream)
         self.workspace = None

@@ -74,6 +74,7 @@ struct Plan {
     std::vector<Op> ops;
     int S = 1, in_c = 0, in_h = 0, in_w = 0;
     bool hold = false;
+    int dtype = cbk::kF32; // storage of maps and filter matrices
     size_t o_iota = 0, o_const = 0, o_partial = 0, o_tickets = 0;
     int compute_units = 256; // sizes the GEMM grids; the device's count replaces it in cbinfer_create
     int iota_len = 0;
@@ -99,9 +100,8 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
         return fail(CBINFER_EINVAL, "frame shape must be positive (got %d x %d x %d)", net->in_c, net->in_h,
                     net->in_w);
     if (net->n_streams <= 0) return fail(CBINFER_EINVAL, "n_streams must be >= 1");
-    if (net->dtype != CBINFER_F32)
-        return fail(net->dtype == CBINFER_BF16 ? CBINFER_EUNSUPPORTED : CBINFER_EINVAL,
-                    "only CBINFER_F32 storage is implemented");
+    if (net->dtype != CBINFER_F32 && net->dtype != CBINFER_BF16)
+        return fail(CBINFER_EINVAL, "dtype must be CBINFER_F32 or CBINFER_BF16");
     if (net->flags & ~(uint32_t)CBINFER_FLAG_HOLD_REFERENCE) return fail(CBINFER_EINVAL, "unknown flag bits");
     if (need_threshold && !(threshold >= 0.0f && std::isfinite(threshold))) {
         bool all_own = true;
@@ -114,6 +114,9 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
     P.in_h = net->in_h;
     P.in_w = net->in_w;
     P.hold = (net->flags & CBINFER_FLAG_HOLD_REFERENCE) != 0;
+    P.dtype = net->dtype == CBINFER_BF16 ? cbk::kBF16 : cbk::kF32;
+    const int eu = cbk::elems_per_unit(P.dtype);
+    const size_t esz = (size_t)cbk::elem_bytes(P.dtype);
     P.ops.clear();
     int c = net->in_c, h = net->in_h, w = net->in_w;
     const long long lim = (1ll << 31) - 1;
@@ -123,7 +126,7 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
         Op op;
         op.kind = L.kind;
         op.C = c;
-        op.Cs = round_up(c, 4);
+        op.Cs = round_up(c, eu);
         op.H = h;
         op.W = w;
         if (L.kind == CBINFER_OP_CONV) {
@@ -143,11 +146,11 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
             op.dense = L.dense != 0;
             op.tau = L.threshold >= 0.0f ? L.threshold : threshold;
             op.M = L.cout;
-            op.Ms = round_up(op.M, 4);
+            op.Ms = round_up(op.M, eu);
             op.Ho = (h + 2 * L.pad - L.kh) / L.stride + 1;
             op.Wo = (w + 2 * L.pad - L.kw) / L.stride + 1;
             op.K = L.kh * L.kw * op.Cs;
-            op.Kpad = round_up(op.K, cbk::gemm_k_multiple());
+            op.Kpad = round_up(op.K, cbk::gemm_k_multiple(P.dtype));
             op.Mpad = round_up(op.M, cbk::gemm_channel_tile(op.M));
             c = op.M;
         } else if (L.kind == CBINFER_OP_MAXPOOL) {
@@ -158,7 +161,7 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
             if (h % L.kh || w % L.kh) return fail(CBINFER_EINVAL, "layer %d: map %d x %d is not a multiple of the pooling window", l, h, w);
             op.kh = op.kw = op.stride = L.kh;
             op.M = c;
-            op.Ms = round_up(c, 4);
+            op.Ms = round_up(c, eu);
             op.Ho = h / L.kh;
             op.Wo = w / L.kh;
             op.conv_before = l - 1;
@@ -180,17 +183,17 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
     for (size_t l = 0; l < P.ops.size(); ++l) {
         Op &op = P.ops[l];
         const size_t in_px = (size_t)P.S * op.H * op.W, out_px = (size_t)P.S * op.Ho * op.Wo;
-        op.o_out = cv.take(out_px * op.Ms * 4);
+        op.o_out = cv.take(out_px * op.Ms * esz);
         op.o_ulist = cv.take(out_px * 4);
         op.o_counts = cv.take(4 * 4);
         if (op.kind == CBINFER_OP_CONV) {
             // Layers behind the first keep no copy of their previous input unless asked to hold it
             // or to run densely: their previous input is the stored output of the op before them.
-            if (l == 0 || P.hold || op.dense) op.o_ref = cv.take(in_px * op.Cs * 4);
-            if (l == 0 && P.hold) op.o_cur = cv.take(in_px * op.Cs * 4);
-            op.o_wt = cv.take((size_t)op.Mpad * op.Kpad * 4);
+            if (l == 0 || P.hold || op.dense) op.o_ref = cv.take(in_px * op.Cs * esz);
+            if (l == 0 && P.hold) op.o_cur = cv.take(in_px * op.Cs * esz);
+            op.o_wt = cv.take((size_t)op.Mpad * op.Kpad * esz);
             op.o_bias = cv.take((size_t)op.Mpad * 4);
-            op.o_taps = cv.take((size_t)op.Kpad / 4 * sizeof(int2));
+            op.o_taps = cv.take((size_t)op.Kpad / eu * sizeof(int2));
             // change map: one bit per pixel, or one byte per pixel when the op before fills it in
             op.o_chg = cv.take(((size_t)words_for((long long)in_px) + 1) * 64);
             op.o_upd = cv.take(((size_t)words_for((long long)out_px) + 1) * 8);
@@ -296,28 +299,39 @@ int collect_profile(cbinfer_state *s)
     return CBINFER_OK;
 }
 
-// Filter matrix K (Section 3) re-laid-out for the gather: row o, column k = (j*kw + i)*Cs + c.
-void build_filter_matrix(const Op &op, const float *w, std::vector<float> &wt)
+// Filter matrix K (Section 3) re-laid-out for the gather: row o, column k = (j*kw + i)*Cs + c,
+// as float32 or bfloat16 (round to nearest even) bytes.
+void build_filter_matrix(const Op &op, int dtype, const float *w, std::vector<unsigned char> &bytes)
 {
-    wt.assign((size_t)op.Mpad * op.Kpad, 0.0f);
+    std::vector<float> wt((size_t)op.Mpad * op.Kpad, 0.0f);
     for (int o = 0; o < op.M; ++o)
         for (int c = 0; c < op.C; ++c)
             for (int j = 0; j < op.kh; ++j)
                 for (int i = 0; i < op.kw; ++i)
                     wt[(size_t)o * op.Kpad + (size_t)(j * op.kw + i) * op.Cs + c] =
                         w[(((size_t)o * op.C + c) * op.kh + j) * op.kw + i];
+    if (dtype == cbk::kBF16) {
+        bytes.resize(wt.size() * 2);
+        unsigned short *b = reinterpret_cast<unsigned short *>(bytes.data());
+        for (size_t i = 0; i < wt.size(); ++i) b[i] = cbk::bf16_bits(wt[i]);
+    } else {
+        bytes.resize(wt.size() * 4);
+        memcpy(bytes.data(), wt.data(), bytes.size());
+    }
 }
 
-void build_taps(const Op &op, std::vector<int2> &taps)
+// One entry per 16-byte unit of a filter-matrix row: where its tap sits relative to the window origin.
+void build_taps(const Op &op, int dtype, std::vector<int2> &taps)
 {
-    taps.resize(op.Kpad / 4);
-    for (int v = 0; v < op.Kpad / 4; ++v) {
-        const int k = v * 4;
+    const int eu = cbk::elems_per_unit(dtype);
+    taps.resize(op.Kpad / eu);
+    for (int v = 0; v < op.Kpad / eu; ++v) {
+        const int k = v * eu;
         int2 t;
         if (k < op.K) {
             const int tap = k / op.Cs, c = k - tap * op.Cs;
             const int j = tap / op.kw, i = tap - j * op.kw;
-            t.x = (j * op.W + i) * op.Cs + c;
+            t.x = ((j * op.W + i) * op.Cs + c) / eu;
             t.y = j | (i << 8) | (1 << 16);
         } else {
             t.x = 0;
@@ -347,8 +361,9 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
         const Op &op = P.ops[l];
         if (op.kind == CBINFER_OP_CONV) {
             const int N = op.H * op.W, No = op.Ho * op.Wo;
-            const float *x = nullptr;
-            float *ref = s->at<float>(op.o_ref);
+            const void *x = nullptr;
+            const int eu = cbk::elems_per_unit(P.dtype);
+            void *ref = s->at<void>(op.o_ref);
             int *counts = s->at<int>(op.o_counts);
             const bool all = first || op.dense || s->force_dense;
             // A layer fed by a stored map finds its changes while that map is updated (the op
@@ -359,15 +374,15 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             if (l == 0) {
                 StepTimer t(s, l, CBINFER_STEP_DETECT);
                 const int hold = (P.hold && !s->force_dense) ? 1 : 0;
-                HIP_TRY(cbk::detect_frame(st, frame, ref, s->at<float>(op.o_cur), s->at<uint64_t>(op.o_chg), op.C,
-                                          op.Cs, N, S, op.tau, hold, all ? 1 : 0));
-                x = hold ? s->at<float>(op.o_cur) : ref;
+                HIP_TRY(cbk::detect_frame(st, frame, ref, s->at<void>(op.o_cur), s->at<uint64_t>(op.o_chg), op.C,
+                                          op.Cs / eu, N, S, op.tau, hold, all ? 1 : 0, P.dtype));
+                x = hold ? s->at<void>(op.o_cur) : ref;
             } else {
-                x = s->at<float>(P.ops[l - 1].o_out);
+                x = s->at<void>(P.ops[l - 1].o_out);
                 if (!s->force_dense && !fused_in) {
                     StepTimer t(s, l, CBINFER_STEP_DETECT);
-                    HIP_TRY(cbk::detect_map(st, x, ref, s->at<uint64_t>(op.o_chg), op.Cs, S * N, op.tau,
-                                            P.hold ? 1 : 0, all ? 1 : 0));
+                    HIP_TRY(cbk::detect_map(st, x, ref, s->at<uint64_t>(op.o_chg), op.Cs / eu, S * N, op.tau,
+                                            P.hold ? 1 : 0, all ? 1 : 0, P.dtype));
                 }
             }
             const int *ulist = iota;
@@ -413,15 +428,16 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             }
             // --- gathered matrix generation + multiplication + output update
             cbk::GemmArgs a;
+            a.dtype = P.dtype;
             a.x = x;
-            a.wt = s->at<float>(op.o_wt);
+            a.wt = s->at<void>(op.o_wt);
             a.bias = s->at<float>(op.o_bias);
             a.taps = s->at<int2>(op.o_taps);
             a.list = ulist;
             a.count = ucount;
-            a.out = s->at<float>(op.o_out);
+            a.out = s->at<void>(op.o_out);
             a.N = N; a.H = op.H; a.W = op.W; a.No = No; a.Wo = op.Wo;
-            a.stride = op.stride; a.pad = op.pad; a.Cs = op.Cs; a.Kpad = op.Kpad;
+            a.stride = op.stride; a.pad = op.pad; a.V = op.Cs / eu; a.Kpad = op.Kpad;
             a.M = op.M; a.Mpad = op.Mpad; a.Ms = op.Ms; a.relu = op.relu;
             a.max_pixels = S * No;
             a.partial = s->at<float>(P.o_partial);
@@ -455,14 +471,16 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                 next_tau = P.ops[l + 1].tau;
             }
             StepTimer t(s, l, CBINFER_STEP_POOL);
-            HIP_TRY(cbk::pool_sparse(st, plist, pcount, S * Np, s->at<float>(cv.o_out), s->at<float>(op.o_out), op.Ms,
-                                     op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np, next_flags, next_tau, first ? 1 : 0));
+            HIP_TRY(cbk::pool_sparse(st, plist, pcount, S * Np, s->at<void>(cv.o_out), s->at<void>(op.o_out),
+                                     op.Ms / cbk::elems_per_unit(P.dtype), op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np,
+                                     next_flags, next_tau, first ? 1 : 0, P.dtype));
         }
     }
     const Op &last = P.ops.back();
     {
         StepTimer t(s, nops - 1, CBINFER_STEP_OUTPUT);
-        HIP_TRY(cbk::map_to_planar(st, s->at<float>(last.o_out), out, last.M, last.Ms, last.Ho * last.Wo, S));
+        HIP_TRY(cbk::map_to_planar(st, s->at<void>(last.o_out), out, last.M, last.Ms / cbk::elems_per_unit(P.dtype),
+                                   last.Ho * last.Wo, S, P.dtype));
     }
     s->initialised = true;
     s->have_frame = true;
@@ -526,6 +544,7 @@ cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold)
     for (Op &op : s->plan.ops) {
         if (op.kind != CBINFER_OP_CONV) continue;
         cbk::GemmArgs a{};
+        a.dtype = P.dtype;
         a.M = op.M; a.Mpad = op.Mpad; a.Kpad = op.Kpad;
         a.max_pixels = P.S * op.Ho * op.Wo;
         op.gemm_grid = cbk::gemm_grid(a, s->plan.compute_units);
@@ -536,7 +555,8 @@ cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold)
     auto setup = [&]() -> int {
         HIP_TRY(cbk::gemm_prepare());
         HIP_TRY(hipMemsetAsync(s->ws, 0, P.bytes, s->stream));
-        std::vector<float> wt, bias;
+        std::vector<unsigned char> wt;
+        std::vector<float> bias;
         std::vector<int2> taps;
         std::vector<int> consts(P.ops.size() * 2, 0);
         for (size_t l = 0; l < P.ops.size(); ++l) {
@@ -544,13 +564,13 @@ cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold)
             consts[2 * l] = P.S * op.Ho * op.Wo;
             if (op.kind != CBINFER_OP_CONV) continue;
             const cbinfer_layer &L = net->layers[l];
-            build_filter_matrix(op, static_cast<const float *>(L.weight), wt);
+            build_filter_matrix(op, P.dtype, static_cast<const float *>(L.weight), wt);
             bias.assign(op.Mpad, 0.0f);
             if (L.bias)
                 for (int o = 0; o < op.M; ++o) bias[o] = L.bias[o];
-            build_taps(op, taps);
+            build_taps(op, P.dtype, taps);
             // the staging vectors are reused for the next layer: wait for the copies first
-            HIP_TRY(hipMemcpyAsync(s->at<float>(op.o_wt), wt.data(), wt.size() * 4, hipMemcpyHostToDevice, s->stream));
+            HIP_TRY(hipMemcpyAsync(s->at<void>(op.o_wt), wt.data(), wt.size(), hipMemcpyHostToDevice, s->stream));
             HIP_TRY(hipMemcpyAsync(s->at<float>(op.o_bias), bias.data(), bias.size() * 4, hipMemcpyHostToDevice, s->stream));
             HIP_TRY(hipMemcpyAsync(s->at<int2>(op.o_taps), taps.data(), taps.size() * sizeof(int2), hipMemcpyHostToDevice, s->stream));
             HIP_TRY(hipStreamSynchronize(s->stream));
@@ -675,28 +695,38 @@ int cbinfer_read_map(cbinfer_state *s, int layer, int which, float *host, size_t
     if (!host) return fail(CBINFER_EINVAL, "host buffer is NULL");
     const Op &op = s->plan.ops[layer];
     int C, Cs, HW;
-    const float *src;
+    const void *src;
     if (which == CBINFER_MAP_REFERENCE) {
         if (op.kind != CBINFER_OP_CONV) return fail(CBINFER_EINVAL, "layer %d has no stored previous input", layer);
         if (s->force_dense && layer > 0) return fail(CBINFER_ESTATE, "dense mode keeps no previous input for layer %d", layer);
         C = op.C; Cs = op.Cs; HW = op.H * op.W;
         // a layer that keeps no copy of its own: its previous input is the stored map that feeds it
-        src = op.o_ref != SIZE_MAX ? s->at<float>(op.o_ref) : s->at<float>(s->plan.ops[layer - 1].o_out);
+        src = op.o_ref != SIZE_MAX ? s->at<void>(op.o_ref) : s->at<void>(s->plan.ops[layer - 1].o_out);
     } else if (which == CBINFER_MAP_OUTPUT) {
         C = op.M; Cs = op.Ms; HW = op.Ho * op.Wo;
-        src = s->at<float>(op.o_out);
+        src = s->at<void>(op.o_out);
     } else {
         return fail(CBINFER_EINVAL, "unknown map %d", which);
     }
     const size_t need = (size_t)s->plan.S * C * HW;
     if (count != need) return fail(CBINFER_EINVAL, "map has %zu values, buffer holds %zu", need, count);
-    std::vector<float> tmp((size_t)s->plan.S * HW * Cs);
+    const size_t n_el = (size_t)s->plan.S * HW * Cs;
     HIP_TRY(hipStreamSynchronize(s->stream));
-    HIP_TRY(hipMemcpy(tmp.data(), src, tmp.size() * 4, hipMemcpyDeviceToHost));
-    for (int st = 0; st < s->plan.S; ++st)
-        for (int c = 0; c < C; ++c)
-            for (int p = 0; p < HW; ++p)
-                host[((size_t)st * C + c) * HW + p] = tmp[((size_t)st * HW + p) * Cs + c];
+    if (s->plan.dtype == cbk::kBF16) {
+        std::vector<unsigned short> tmp(n_el);
+        HIP_TRY(hipMemcpy(tmp.data(), src, n_el * 2, hipMemcpyDeviceToHost));
+        for (int st = 0; st < s->plan.S; ++st)
+            for (int c = 0; c < C; ++c)
+                for (int p = 0; p < HW; ++p)
+                    host[((size_t)st * C + c) * HW + p] = cbk::bf16_value(tmp[((size_t)st * HW + p) * Cs + c]);
+    } else {
+        std::vector<float> tmp(n_el);
+        HIP_TRY(hipMemcpy(tmp.data(), src, n_el * 4, hipMemcpyDeviceToHost));
+        for (int st = 0; st < s->plan.S; ++st)
+            for (int c = 0; c < C; ++c)
+                for (int p = 0; p < HW; ++p)
+                    host[((size_t)st * C + c) * HW + p] = tmp[((size_t)st * HW + p) * Cs + c];
+    }
     return CBINFER_OK;
 }
 

@@ -2,8 +2,9 @@
 // given stream and returns the hipError_t of the launch; nothing synchronises or allocates.
 //
 // Internal data layout (all device memory):
-//   maps      [stream][y][x][Cs]  float32, channel-contiguous, Cs = channels rounded up to 4;
-//             the padding channels are zero.  "pixel g" = stream*H*W + y*W + x.
+//   maps      [stream][y][x][Cs], channel-contiguous, float32 or bfloat16; Cs = channels rounded
+//             up to a whole number of 16-byte units (4 floats / 8 bfloat16), padding channels are
+//             zero.  Sizes are passed in units: V = units per pixel.  "pixel g" = stream*H*W + y*W + x.
 //   bitmaps   one bit per pixel g, packed in uint64 words (bit g%64 of word g/64);
 //             bits at or beyond the pixel count are zero.
 //   lists     int32 pixel indices g, ascending, with their length in an int32 counter.
@@ -13,25 +14,84 @@
 
 namespace cbk {
 
-// One subtraction, one absolute value and one strict comparison per channel (Section 3.1);
-// a NaN difference compares false and does not flag.
-__device__ __forceinline__ bool exceeds(const float4 a, const float4 r, const float tau)
+enum { kF32 = 0, kBF16 = 1 }; // storage type of maps and filter matrices (accumulation is float32)
+inline int elems_per_unit(int dt) { return dt == kBF16 ? 8 : 4; }
+inline int elem_bytes(int dt) { return dt == kBF16 ? 2 : 4; }
+
+// float -> bfloat16 bits, round to nearest even; NaN stays a (quiet) NaN.
+__host__ __device__ inline unsigned short bf16_bits(float f)
 {
-    return (fabsf(a.x - r.x) > tau) || (fabsf(a.y - r.y) > tau) || (fabsf(a.z - r.z) > tau) ||
-           (fabsf(a.w - r.w) > tau);
+    union { float f; unsigned int u; } c;
+    c.f = f;
+    unsigned int u = c.u;
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+__host__ __device__ inline float bf16_value(unsigned short b)
+{
+    union { float f; unsigned int u; } c;
+    c.u = (unsigned int)b << 16;
+    return c.f;
+}
+
+// One 16-byte unit of a map: 4 floats or 8 bfloat16.
+template <int DT>
+struct Unit;
+template <>
+struct Unit<kF32> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ float get(const uint4 &u, int i) { return __uint_as_float((&u.x)[i]); }
+    static __device__ __forceinline__ void set(uint4 &u, int i, float f) { (&u.x)[i] = __float_as_uint(f); }
+};
+template <>
+struct Unit<kBF16> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ float get(const uint4 &u, int i)
+    {
+        const unsigned int w = (&u.x)[i >> 1];
+        return __uint_as_float((i & 1) ? (w & 0xffff0000u) : (w << 16));
+    }
+    static __device__ __forceinline__ void set(uint4 &u, int i, float f) // rounds to bfloat16
+    {
+        const unsigned int b = bf16_bits(f);
+        unsigned int &w = (&u.x)[i >> 1];
+        w = (i & 1) ? ((w & 0x0000ffffu) | (b << 16)) : ((w & 0xffff0000u) | b);
+    }
+};
+
+// Change test on one unit: one subtraction, one absolute value and one strict comparison per
+// channel, in float (Section 3.1); a NaN difference compares false and does not flag.
+template <int DT>
+__device__ __forceinline__ bool unit_exceeds(const uint4 &a, const uint4 &r, const float tau)
+{
+    bool f = false;
+#pragma unroll
+    for (int i = 0; i < Unit<DT>::N; ++i) f = f || (fabsf(Unit<DT>::get(a, i) - Unit<DT>::get(r, i)) > tau);
+    return f;
+}
+
+template <int DT>
+__device__ __forceinline__ uint4 unit_max(const uint4 &a, const uint4 &b)
+{
+    uint4 m = a;
+#pragma unroll
+    for (int i = 0; i < Unit<DT>::N; ++i) Unit<DT>::set(m, i, fmaxf(Unit<DT>::get(a, i), Unit<DT>::get(b, i)));
+    return m;
 }
 
 // ---- change detection (Section 3.1, first formula) ---------------------------------------
-// Planar float32 frame [S][C][N] against the stored previous input kept as a map.
+// Planar float32 frame [S][C][N] against the stored previous input kept as a map of V units per
+// pixel (bfloat16 storage: the frame is rounded to bfloat16 first and compared as such).
 // Writes the change bitmap; refreshes the stored input (hold == 0: everywhere;
 // hold == 1: `cur` receives the frame as a map and `ref` is refreshed only where flagged).
 // force != 0: every pixel is flagged and ref is not read (first frame / dense mode).
-hipError_t detect_frame(hipStream_t st, const float *frame, float *ref, float *cur, uint64_t *bits,
-                        int C, int Cs, int N, int S, float tau, int hold, int force);
+hipError_t detect_frame(hipStream_t st, const float *frame, void *ref, void *cur, uint64_t *bits, int C, int V,
+                        int N, int S, float tau, int hold, int force, int dtype);
 
-// Map against map (layers fed by a stored output map).  x and ref are [S*N][Cs].
-hipError_t detect_map(hipStream_t st, const float *x, float *ref, uint64_t *bits, int Cs, int total,
-                      float tau, int hold, int force);
+// Map against map (layers fed by a stored output map).  x and ref are [S*N][V units].
+hipError_t detect_map(hipStream_t st, const void *x, void *ref, uint64_t *bits, int V, int total, float tau,
+                      int hold, int force, int dtype);
 
 // ---- dilation by the filter support (Section 3.1, second formula) -------------------------
 // upd bit (stream, qy, qx) = OR of the change bits inside that output's receptive field.
@@ -62,15 +122,20 @@ hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs);
 
 // ---- gathered matrix generation + multiplication + output update (Section 3.1) -------------
 struct GemmArgs {
-    const float *x;     // input map [S*N][Cs]
-    const float *wt;    // filter matrix, [Mpad][Kpad], k = (j*kw + i)*Cs + c, zero padded
-    const float *bias;  // [Mpad]
-    const int2 *taps;   // [Kpad/4]: .x = element offset of the tap from the window origin,
-                        //           .y = j | i << 8 | valid << 16
+    int dtype;          // kF32 or kBF16: storage of x, wt and out
+    const void *x;      // input map [S*N][V units]
+    const void *wt;     // filter matrix, [Mpad][Kpad], k = (j*kw + i)*Cs + c, zero padded
+    const float *bias;  // [Mpad] float32
+    const int2 *taps;   // one entry per 16-byte unit of a filter-matrix row:
+                        //   .x = offset of the tap, in units, from the window origin in the input map,
+                        //   .y = j | i << 8 | valid << 16
     const int *list;    // output pixels to recompute
     const int *count;   // their number (device)
-    float *out;         // stored output map [S*No][Ms]
-    int N, H, W, No, Wo, stride, pad, Cs, Kpad, M, Mpad, Ms, relu;
+    void *out;          // stored output map [S*No][Ms]
+    int N, H, W, No, Wo, stride, pad;
+    int V;              // units per input pixel
+    int Kpad;           // filter-matrix row length in elements, a multiple of gemm_k_multiple(dtype)
+    int M, Mpad, Ms, relu;
     int max_pixels;     // upper bound of *count
     float *partial;     // scratch for partial accumulators, gemm_partial_bytes(M, grid) bytes
     int *tickets;       // gemm_ticket_bytes(grid) bytes, zero before the first launch (each launch
@@ -92,7 +157,7 @@ struct GemmArgs {
 #endif
 };
 int gemm_channel_tile(int M);   // channel tile BM used for M output channels (Mpad = M rounded up to it)
-int gemm_k_multiple(void);      // Kpad must be a multiple of this
+int gemm_k_multiple(int dtype); // Kpad must be a multiple of this many elements (128 bytes)
 int gemm_grid(const GemmArgs &a, int compute_units); // needs M, Mpad, Kpad, max_pixels
 size_t gemm_partial_bytes(int M, int grid);
 size_t gemm_ticket_bytes(int grid);
@@ -105,12 +170,12 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a);
 // this very map; compare each recomputed value with the one it replaces against next_tau and set
 // the position's byte in that layer's change map (one byte per pixel, zero on entry).
 // next_force != 0: flag every recomputed position (first frame).
-hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const float *in,
-                       float *pooled, int Ms, int k, int Wo, int No, int Wp, int Np, unsigned char *next_flags,
-                       float next_tau, int next_force);
+hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const void *in,
+                       void *pooled, int V, int k, int Wo, int No, int Wp, int Np, unsigned char *next_flags,
+                       float next_tau, int next_force, int dtype);
 
 // ---- stored map -> caller's planar output --------------------------------------------------
-hipError_t map_to_planar(hipStream_t st, const float *map, float *planar, int M, int Ms, int No, int S);
+hipError_t map_to_planar(hipStream_t st, const void *map, float *planar, int M, int V, int No, int S, int dtype);
 
 // helpers
 hipError_t fill_iota(hipStream_t st, int *list, int n);

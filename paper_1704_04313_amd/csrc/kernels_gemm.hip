@@ -31,6 +31,7 @@ namespace cbk {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 // Partial accumulators cross between workgroups that may sit on different XCDs (separate L2s).
 // They are written and read with buffer instructions carrying the sc1 bit: write-through to, and
@@ -52,9 +53,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const float *p, 
 #define CBK_STAMP(slot) do { } while (0)
 #endif
 
-static constexpr int BK = 32;       // K slice per pipeline stage (floats)
-static constexpr int LDK = BK + 4;  // LDS row pitch: 36 floats keeps 16-byte alignment and makes
-                                    // the rows read by one ds_read_b128 phase hit distinct banks
+static constexpr int BK = 32;       // K slice per pipeline stage: 128 bytes = 32 floats or 64 bfloat16,
+                                    // i.e. 8 units of 16 bytes
+static constexpr int KU = 8;        // units per slice
+static constexpr int LDK = BK + 4;  // LDS row pitch in 4-byte words: 144 bytes keeps 16-byte alignment and
+                                    // makes the rows read by one ds_read_b128 phase hit distinct banks
 static constexpr int NT = 512;      // threads per workgroup: 4 consumer + 4 producer waves
 static constexpr int NPROD = 256;   // producer threads
 static constexpr int NCONS = 256;   // consumer threads
@@ -122,29 +125,30 @@ __device__ __forceinline__ int share_owner(const Schedule &s, long long it)
 }
 
 // Image-matrix rows gathered by one producer thread for one K slice: PA rows (32 apart), one
-// float4 each.  tp is the slice's tap descriptor for this thread's float4 column.
+// 16-byte unit each.  tp is the slice's tap descriptor for this thread's unit column.
 template <int PA>
 __device__ __forceinline__ void gather_rows(const GemmArgs &a, const int2 tp, const int (&iy0)[PA],
                                             const int (&ix0)[PA], const int (&base)[PA], floatx4 (&ra)[PA])
 {
+    const floatx4 *x = static_cast<const floatx4 *>(a.x);
     const int tj = tp.y & 0xff, ti = (tp.y >> 8) & 0xff;
     const bool tv = (tp.y >> 16) != 0;
 #pragma unroll
     for (int ps = 0; ps < PA; ++ps) {
         const bool ok = tv && (unsigned)(iy0[ps] + tj) < (unsigned)a.H && (unsigned)(ix0[ps] + ti) < (unsigned)a.W;
-        ra[ps] = ok ? *reinterpret_cast<const floatx4 *>(a.x + (base[ps] + tp.x)) : (floatx4){0.f, 0.f, 0.f, 0.f};
+        ra[ps] = ok ? x[base[ps] + tp.x] : (floatx4){0.f, 0.f, 0.f, 0.f};
     }
 }
 
+// wrow: this thread's unit column in its first filter-matrix row; krow = units per row.
 template <int BM, int PB>
-__device__ __forceinline__ void load_filter_rows(const float *wrow, int kpad, int kc, int r0, floatx4 (&rb)[PB])
+__device__ __forceinline__ void load_filter_rows(const floatx4 *wrow, int krow, int kc, int r0, floatx4 (&rb)[PB])
 {
     if constexpr (BM >= 32) {
 #pragma unroll
-        for (int ps = 0; ps < PB; ++ps)
-            rb[ps] = *reinterpret_cast<const floatx4 *>(wrow + (size_t)(32 * ps) * kpad + kc * BK);
+        for (int ps = 0; ps < PB; ++ps) rb[ps] = wrow[(size_t)(32 * ps) * krow + kc * KU];
     } else {
-        if (r0 < BM) rb[0] = *reinterpret_cast<const floatx4 *>(wrow + kc * BK);
+        if (r0 < BM) rb[0] = wrow[kc * KU];
     }
 }
 
@@ -168,7 +172,7 @@ __device__ __forceinline__ void stage_rows(float *A, float *B, int r0, int v, co
 // the global loads of slice kc+3, while the consumers multiply slice kc and already read the
 // first fragments of slice kc+1, so the matrix pipeline keeps running across the one barrier
 // per slice.
-template <int BM, int BN, int WM, int WN>
+template <int DT, int BM, int BN, int WM, int WN>
 __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n, float *smem)
 {
     static_assert(WM * WN == 4, "four consumer waves");
@@ -193,7 +197,8 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
     const bool producer = wave >= 4;
 
     const int mtiles = a.Mpad / BM;
-    const int nk = a.Kpad / BK;
+    const int krow = a.Kpad / Unit<DT>::N; // units per filter-matrix row
+    const int nk = krow / KU;
     const int W = gridDim.x;
     const Schedule sch = make_schedule(n, BN, mtiles, nk, W);
     if (sch.tiles == 0) return;
@@ -211,7 +216,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
 
     int round = 0;
     long long it = it_begin;
-    int seg = 0;
+    [[maybe_unused]] int seg = 0; // numbers the time stamps of timing-study builds
     CBK_STAMP(1);
     while (true) {
         // ---- next segment of this workgroup: a whole tile, or part of a shared tile's K range
@@ -269,29 +274,29 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                     const int qy = q / a.Wo, qx = q - qy * a.Wo;
                     iy0[ps] = qy * a.stride - a.pad;
                     ix0[ps] = qx * a.stride - a.pad;
-                    base[ps] = ((st * a.H + iy0[ps]) * a.W + ix0[ps]) * a.Cs;
+                    base[ps] = ((st * a.H + iy0[ps]) * a.W + ix0[ps]) * a.V;
                 } else {
                     iy0[ps] = -(1 << 28);
                     ix0[ps] = -(1 << 28);
                     base[ps] = 0;
                 }
             }
-            const float *wrow = a.wt + (size_t)(mt * BM + r0) * a.Kpad + v * 4;
+            const floatx4 *wrow = static_cast<const floatx4 *>(a.wt) + (size_t)(mt * BM + r0) * krow + v;
             const int2 *taps = a.taps + v;
             // Two register sets: while the slice loaded two iterations ago is stored to LDS, the
             // loads of the slice after next are already in flight (a slice of MFMA work is shorter
             // than a global-memory round trip for the small tiles).  The tap descriptor of a slice
             // is loaded before the operand loads that need it.
             floatx4 raA[PA], rbA[PB], raB[PA], rbB[PB];
-            auto tap = [&](int kc) { return taps[(kc < kc1 ? kc : kc0) * (BK / 4)]; };
+            auto tap = [&](int kc) { return taps[(kc < kc1 ? kc : kc0) * KU]; };
             int2 tpA = tap(kc0), tpB = tap(kc0 + 1);
             const int2 t2 = tap(kc0 + 2), t3 = tap(kc0 + 3);
             // prologue: slices kc0 and kc0+1 into ring slots 0 and 1, slices kc0+2 and kc0+3 in flight
             gather_rows<PA>(a, tpA, iy0, ix0, base, raA);
-            load_filter_rows<BM, PB>(wrow, a.Kpad, kc0, r0, rbA);
+            load_filter_rows<BM, PB>(wrow, krow, kc0, r0, rbA);
             if (kc0 + 1 < kc1) {
                 gather_rows<PA>(a, tpB, iy0, ix0, base, raB);
-                load_filter_rows<BM, PB>(wrow, a.Kpad, kc0 + 1, r0, rbB);
+                load_filter_rows<BM, PB>(wrow, krow, kc0 + 1, r0, rbB);
             }
             tpA = tap(kc0 + 4);
             tpB = tap(kc0 + 5);
@@ -299,11 +304,11 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             if (kc0 + 1 < kc1) stage_rows<BM, PA, PB>(As + ASZ, Bs + BSZ, r0, v, raB, rbB);
             if (kc0 + 2 < kc1) {
                 gather_rows<PA>(a, t2, iy0, ix0, base, raA);
-                load_filter_rows<BM, PB>(wrow, a.Kpad, kc0 + 2, r0, rbA);
+                load_filter_rows<BM, PB>(wrow, krow, kc0 + 2, r0, rbA);
             }
             if (kc0 + 3 < kc1) {
                 gather_rows<PA>(a, t3, iy0, ix0, base, raB);
-                load_filter_rows<BM, PB>(wrow, a.Kpad, kc0 + 3, r0, rbB);
+                load_filter_rows<BM, PB>(wrow, krow, kc0 + 3, r0, rbB);
             }
             __syncthreads();
             CBK_STAMP(3 + 6 * seg);
@@ -313,7 +318,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                     stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, v, raA, rbA);
                     if (kc + 4 < kc1) {
                         gather_rows<PA>(a, tpA, iy0, ix0, base, raA);
-                        load_filter_rows<BM, PB>(wrow, a.Kpad, kc + 4, r0, rbA);
+                        load_filter_rows<BM, PB>(wrow, krow, kc + 4, r0, rbA);
                         tpA = tap(kc + 6);
                     }
                 }
@@ -324,7 +329,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                         stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, v, raB, rbB);
                         if (kc + 5 < kc1) {
                             gather_rows<PA>(a, tpB, iy0, ix0, base, raB);
-                            load_filter_rows<BM, PB>(wrow, a.Kpad, kc + 5, r0, rbB);
+                            load_filter_rows<BM, PB>(wrow, krow, kc + 5, r0, rbB);
                             tpB = tap(kc + 7);
                         }
                     }
@@ -349,14 +354,25 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                 for (int j = 0; j < TC; ++j) bf[set][j] = *reinterpret_cast<const floatx4 *>(B + j * 16 * LDK);
             };
             auto multiply = [&](int set) {
-#pragma unroll
-                for (int s = 0; s < 4; ++s)
+                if constexpr (DT == kBF16) {
+                    // one 16-byte fragment = 8 consecutive k: v_mfma_f32_16x16x32_bf16 takes it whole
 #pragma unroll
                     for (int j = 0; j < TC; ++j)
 #pragma unroll
                         for (int i = 0; i < TP; ++i)
-                            acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[set][j][s], af[set][i][s], acc[j][i],
-                                                                             0, 0, 0);
+                            acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf16x8, bf[set][j]), __builtin_bit_cast(bf16x8, af[set][i]),
+                                acc[j][i], 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+#pragma unroll
+                        for (int j = 0; j < TC; ++j)
+#pragma unroll
+                            for (int i = 0; i < TP; ++i)
+                                acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[set][j][s], af[set][i][s],
+                                                                                 acc[j][i], 0, 0, 0);
+                }
             };
             __syncthreads();
             CBK_STAMP(3 + 6 * seg);
@@ -471,9 +487,30 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                             o.z = fmaxf(o.z, 0.f);
                             o.w = fmaxf(o.w, 0.f);
                         }
-                        float4 *dst = reinterpret_cast<float4 *>(a.out + (size_t)g * a.Ms + ch);
-                        if (detect) changed[i] |= exceeds(o, *dst, a.next_tau);
-                        *dst = o;
+                        if constexpr (DT == kBF16) {
+                            // four consecutive bfloat16 channels: one 8-byte word
+                            uint2 *dst = reinterpret_cast<uint2 *>(static_cast<unsigned short *>(a.out) +
+                                                                   (size_t)g * a.Ms + ch);
+                            uint2 nv;
+                            nv.x = (unsigned)bf16_bits(o.x) | ((unsigned)bf16_bits(o.y) << 16);
+                            nv.y = (unsigned)bf16_bits(o.z) | ((unsigned)bf16_bits(o.w) << 16);
+                            if (detect) {
+                                const uint2 ov = *dst;
+                                changed[i] |= fabsf(bf16_value(nv.x & 0xffff) - bf16_value(ov.x & 0xffff)) > a.next_tau ||
+                                              fabsf(bf16_value(nv.x >> 16) - bf16_value(ov.x >> 16)) > a.next_tau ||
+                                              fabsf(bf16_value(nv.y & 0xffff) - bf16_value(ov.y & 0xffff)) > a.next_tau ||
+                                              fabsf(bf16_value(nv.y >> 16) - bf16_value(ov.y >> 16)) > a.next_tau;
+                            }
+                            *dst = nv;
+                        } else {
+                            float4 *dst = reinterpret_cast<float4 *>(static_cast<float *>(a.out) + (size_t)g * a.Ms + ch);
+                            if (detect) {
+                                const float4 ov = *dst;
+                                changed[i] |= fabsf(o.x - ov.x) > a.next_tau || fabsf(o.y - ov.y) > a.next_tau ||
+                                              fabsf(o.z - ov.z) > a.next_tau || fabsf(o.w - ov.w) > a.next_tau;
+                            }
+                            *dst = o;
+                        }
                     }
                 }
             }
@@ -498,7 +535,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
 // the tile shape that suits it -- BNB listed pixels per tile normally, BNS when even the deepest K
 // split of the big tiles would leave compute units idle (short lists): small tiles then need no
 // or fewer shared tiles, whose partial sums and reduction are pure overhead.
-template <int BM, int BNB, int WMB, int WNB, int BNS, int WMS, int WNS>
+template <int DT, int BM, int BNB, int WMB, int WNB, int BNS, int WMS, int WNS>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_gather_kernel(GemmArgs a)
 {
     extern __shared__ __align__(16) float smem[];
@@ -512,13 +549,13 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     const int n = *a.count;
     const long long big_tiles = (long long)((n + BNB - 1) / BNB) * (a.Mpad / BM);
     if (big_tiles * kSmallTileFactor >= (long long)gridDim.x)
-        gemm_gather_body<BM, BNB, WMB, WNB>(a, n, smem);
+        gemm_gather_body<DT, BM, BNB, WMB, WNB>(a, n, smem);
     else
-        gemm_gather_body<BM, BNS, WMS, WNS>(a, n, smem);
+        gemm_gather_body<DT, BM, BNS, WMS, WNS>(a, n, smem);
 }
 
 // ---- host side --------------------------------------------------------------------------
-int gemm_k_multiple(void) { return BK; }
+int gemm_k_multiple(int dtype) { return BK * 4 / elem_bytes(dtype); }
 
 int gemm_channel_tile(int M)
 {
@@ -547,7 +584,7 @@ int gemm_grid(const GemmArgs &a, int compute_units)
     int W = compute_units & ~7;
     if (W < 8) W = 8;
     if (W > kMaxGrid) W = kMaxGrid;
-    const int nk = a.Kpad / BK;
+    const int nk = a.Kpad / gemm_k_multiple(a.dtype);
     const int parts = nk / kMinIters > 1 ? nk / kMinIters : 1;
     // with few pixels the small tile (64 pixels) is used: count those
     const long long big = (long long)((a.max_pixels + bn - 1) / bn) * (a.Mpad / bm);
@@ -563,10 +600,14 @@ int gemm_grid(const GemmArgs &a, int compute_units)
 hipError_t gemm_prepare(void)
 {
     hipError_t e = hipSuccess;
-#define X(BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_)                                                            \
-    if (e == hipSuccess)                                                                                      \
-        e = hipFuncSetAttribute(                                                                              \
-            reinterpret_cast<const void *>(&gemm_gather_kernel<BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_>),      \
+#define X(BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_)                                                                  \
+    if (e == hipSuccess)                                                                                            \
+        e = hipFuncSetAttribute(                                                                                    \
+            reinterpret_cast<const void *>(&gemm_gather_kernel<kF32, BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_>),      \
+            hipFuncAttributeMaxDynamicSharedMemorySize, TileSmem<BM_, BNB_>::bytes);                                \
+    if (e == hipSuccess)                                                                                            \
+        e = hipFuncSetAttribute(                                                                                    \
+            reinterpret_cast<const void *>(&gemm_gather_kernel<kBF16, BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_>),     \
             hipFuncAttributeMaxDynamicSharedMemorySize, TileSmem<BM_, BNB_>::bytes);
     CBK_VARIANTS(X)
 #undef X
@@ -577,15 +618,19 @@ template <int BM, int BNB, int WMB, int WNB, int BNS, int WMS, int WNS>
 static hipError_t launch(hipStream_t st, const GemmArgs &a)
 {
     constexpr int smem_bytes = TileSmem<BM, BNB>::bytes;
-    gemm_gather_kernel<BM, BNB, WMB, WNB, BNS, WMS, WNS><<<dim3(a.grid), dim3(NT), smem_bytes, st>>>(a);
+    if (a.dtype == kBF16)
+        gemm_gather_kernel<kBF16, BM, BNB, WMB, WNB, BNS, WMS, WNS><<<dim3(a.grid), dim3(NT), smem_bytes, st>>>(a);
+    else
+        gemm_gather_kernel<kF32, BM, BNB, WMB, WNB, BNS, WMS, WNS><<<dim3(a.grid), dim3(NT), smem_bytes, st>>>(a);
     return hipGetLastError();
 }
 
 hipError_t gemm_gather(hipStream_t st, const GemmArgs &a)
 {
     const int bm = gemm_channel_tile(a.M);
-    if (a.Mpad % bm != 0 || a.Kpad % BK != 0 || a.Cs % 4 != 0 || !a.partial || !a.tickets || a.grid < 8 ||
-        (a.grid & 7))
+    const int eu = elems_per_unit(a.dtype);
+    if (a.Mpad % bm != 0 || a.Kpad % gemm_k_multiple(a.dtype) != 0 || a.Ms % eu != 0 || a.V < 1 || !a.partial ||
+        !a.tickets || a.grid < 8 || (a.grid & 7))
         return hipErrorInvalidValue;
     switch (bm) {
     case 16: return launch<16, 256, 1, 4, 64, 1, 4>(st, a);

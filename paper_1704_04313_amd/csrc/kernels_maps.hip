@@ -8,69 +8,73 @@ namespace cbk {
 static constexpr int kBlock = 256;
 
 // ------------------------------------------------------------------------------------------
-// Change detection on a planar frame: one thread per pixel, channels in groups of four.
+// Change detection on a planar frame: one thread per pixel, channels in 16-byte units.
 // Frame reads are coalesced per channel plane; the stored map is read and written as one
-// float4 per lane and group.  Each wave emits one 64-bit word of the change bitmap.
+// unit per lane and step.  Each wave emits one 64-bit word of the change bitmap.
 // ------------------------------------------------------------------------------------------
-template <int HOLD>
+template <int DT, int HOLD>
 __global__ __launch_bounds__(kBlock) void detect_frame_kernel(const float *__restrict__ frame,
-                                                              float *__restrict__ ref,
-                                                              float *__restrict__ cur,
-                                                              uint64_t *__restrict__ bits, int C, int Cs,
-                                                              int N, int total, float tau, int force)
+                                                              uint4 *__restrict__ ref, uint4 *__restrict__ cur,
+                                                              uint64_t *__restrict__ bits, int C, int V, int N,
+                                                              int total, float tau, int force)
 {
+    constexpr int E = Unit<DT>::N;
     const int g = blockIdx.x * kBlock + threadIdx.x;
     bool flag = false;
     if (g < total) {
         const int st = g / N;
         const int p = g - st * N;
         const float *fp = frame + (size_t)st * C * N + p;
-        float4 *rp = reinterpret_cast<float4 *>(ref + (size_t)g * Cs);
-        float4 *cp = HOLD ? reinterpret_cast<float4 *>(cur + (size_t)g * Cs) : nullptr;
-        for (int c0 = 0; c0 < Cs; c0 += 4) {
-            float4 xv;
-            xv.x = fp[(size_t)c0 * N];
-            xv.y = (c0 + 1 < C) ? fp[(size_t)(c0 + 1) * N] : 0.0f;
-            xv.z = (c0 + 2 < C) ? fp[(size_t)(c0 + 2) * N] : 0.0f;
-            xv.w = (c0 + 3 < C) ? fp[(size_t)(c0 + 3) * N] : 0.0f;
-            if (!force) flag |= exceeds(xv, rp[c0 >> 2], tau);
+        uint4 *rp = ref + (size_t)g * V;
+        uint4 *cp = HOLD ? cur + (size_t)g * V : nullptr;
+        for (int u = 0; u < V; ++u) {
+            uint4 xv = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int i = 0; i < E; ++i) {
+                const int c = u * E + i;
+                if (c < C) Unit<DT>::set(xv, i, fp[(size_t)c * N]);
+            }
+            if (!force) flag |= unit_exceeds<DT>(xv, rp[u], tau);
             if (HOLD)
-                cp[c0 >> 2] = xv;
+                cp[u] = xv;
             else
-                rp[c0 >> 2] = xv;
+                rp[u] = xv;
         }
         if (force) flag = true;
         if (HOLD && flag)
-            for (int c4 = 0; c4 < (Cs >> 2); ++c4) rp[c4] = cp[c4];
+            for (int u = 0; u < V; ++u) rp[u] = cp[u];
     }
     const uint64_t word = __ballot(flag);
     const int g0 = g & ~63;
     if ((threadIdx.x & 63) == 0 && g0 < total) bits[g0 >> 6] = word;
 }
 
-hipError_t detect_frame(hipStream_t st, const float *frame, float *ref, float *cur, uint64_t *bits, int C,
-                        int Cs, int N, int S, float tau, int hold, int force)
+hipError_t detect_frame(hipStream_t st, const float *frame, void *ref, void *cur, uint64_t *bits, int C, int V,
+                        int N, int S, float tau, int hold, int force, int dtype)
 {
     const int total = S * N;
     const int grid = (total + kBlock - 1) / kBlock;
-    if (hold)
-        hipLaunchKernelGGL(detect_frame_kernel<1>, dim3(grid), dim3(kBlock), 0, st, frame, ref, cur, bits, C,
-                           Cs, N, total, tau, force);
-    else
-        hipLaunchKernelGGL(detect_frame_kernel<0>, dim3(grid), dim3(kBlock), 0, st, frame, ref, cur, bits, C,
-                           Cs, N, total, tau, force);
+    uint4 *r = static_cast<uint4 *>(ref), *c = static_cast<uint4 *>(cur);
+#define CBK_LAUNCH(DT_, HOLD_)                                                                                  \
+    hipLaunchKernelGGL((detect_frame_kernel<DT_, HOLD_>), dim3(grid), dim3(kBlock), 0, st, frame, r, c, bits, C, \
+                       V, N, total, tau, force)
+    if (dtype == kBF16) {
+        if (hold) CBK_LAUNCH(kBF16, 1); else CBK_LAUNCH(kBF16, 0);
+    } else {
+        if (hold) CBK_LAUNCH(kF32, 1); else CBK_LAUNCH(kF32, 0);
+    }
+#undef CBK_LAUNCH
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------
 // Change detection map against map.  One workgroup per 64 pixels (one bitmap word); its
-// waves take turns over the 64*V float4 of those pixels, so every access is a fully
-// coalesced 1 KiB wave transaction.  A wave-wide ballot of "this float4 exceeded" is folded
-// into per-pixel flags by masking the ballot with each pixel's float4 range.
+// waves take turns over the 64*V units of those pixels, so every access is a fully
+// coalesced 1 KiB wave transaction.  A wave-wide ballot of "this unit exceeded" is folded
+// into per-pixel flags by masking the ballot with each pixel's unit range.
 // ------------------------------------------------------------------------------------------
-template <int HOLD>
-__global__ __launch_bounds__(1024) void detect_map_kernel(const float4 *__restrict__ x,
-                                                          float4 *__restrict__ ref,
+template <int DT, int HOLD>
+__global__ __launch_bounds__(1024) void detect_map_kernel(const uint4 *__restrict__ x, uint4 *__restrict__ ref,
                                                           uint64_t *__restrict__ bits, int V, int total,
                                                           float tau, int force)
 {
@@ -89,8 +93,8 @@ __global__ __launch_bounds__(1024) void detect_map_kernel(const float4 *__restri
         const int f = t * 64 + lane;
         bool e = false;
         if (f < nf) {
-            const float4 a = x[base + f];
-            if (!force) e = exceeds(a, ref[base + f], tau);
+            const uint4 a = x[base + f];
+            if (!force) e = unit_exceeds<DT>(a, ref[base + f], tau);
             if (!HOLD) ref[base + f] = a;
         }
         const uint64_t B = __ballot(e);
@@ -121,21 +125,23 @@ __global__ __launch_bounds__(1024) void detect_map_kernel(const float4 *__restri
     }
 }
 
-hipError_t detect_map(hipStream_t st, const float *x, float *ref, uint64_t *bits, int Cs, int total, float tau,
-                      int hold, int force)
+hipError_t detect_map(hipStream_t st, const void *x, void *ref, uint64_t *bits, int V, int total, float tau,
+                      int hold, int force, int dtype)
 {
-    const int V = Cs / 4;
     const int words = (total + 63) / 64;
     int nw = V < 16 ? V : 16;
     if (nw < 1) nw = 1;
-    const float4 *x4 = reinterpret_cast<const float4 *>(x);
-    float4 *r4 = reinterpret_cast<float4 *>(ref);
-    if (hold)
-        hipLaunchKernelGGL(detect_map_kernel<1>, dim3(words), dim3(nw * 64), 0, st, x4, r4, bits, V, total, tau,
-                           force);
-    else
-        hipLaunchKernelGGL(detect_map_kernel<0>, dim3(words), dim3(nw * 64), 0, st, x4, r4, bits, V, total, tau,
-                           force);
+    const uint4 *x4 = static_cast<const uint4 *>(x);
+    uint4 *r4 = static_cast<uint4 *>(ref);
+#define CBK_LAUNCH(DT_, HOLD_)                                                                                  \
+    hipLaunchKernelGGL((detect_map_kernel<DT_, HOLD_>), dim3(words), dim3(nw * 64), 0, st, x4, r4, bits, V, total, \
+                       tau, force)
+    if (dtype == kBF16) {
+        if (hold) CBK_LAUNCH(kBF16, 1); else CBK_LAUNCH(kBF16, 0);
+    } else {
+        if (hold) CBK_LAUNCH(kF32, 1); else CBK_LAUNCH(kF32, 0);
+    }
+#undef CBK_LAUNCH
     return hipGetLastError();
 }
 
@@ -382,12 +388,13 @@ hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs)
 
 // ------------------------------------------------------------------------------------------
 // Max-pooling at the listed pooled positions only: each is the maximum over its k x k window
-// of the stored (already updated, post-activation) map.  One thread per (position, 4 channels).
+// of the stored (already updated, post-activation) map.  One thread per (position, 16-byte unit of channels).
 // ------------------------------------------------------------------------------------------
+template <int DT>
 __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restrict__ list,
                                                              const int *__restrict__ count,
-                                                             const float4 *__restrict__ in,
-                                                             float4 *__restrict__ pooled, int V, int k, int Wo,
+                                                             const uint4 *__restrict__ in,
+                                                             uint4 *__restrict__ pooled, int V, int k, int Wo,
                                                              int No, int Wp, int Np,
                                                              unsigned char *__restrict__ next_flags,
                                                              float next_tau, int next_force)
@@ -402,21 +409,15 @@ __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restri
         const int st = g / Np, pp = g - st * Np;
         const int py = pp / Wp, px = pp - py * Wp;
         const long long base = (long long)st * No + (long long)(py * k) * Wo + px * k;
-        float4 m = in[base * V + v];
+        uint4 m = in[base * V + v];
         for (int j = 0; j < k; ++j)
-            for (int i = 0; i < k; ++i) {
-                const float4 a = in[(base + (long long)j * Wo + i) * V + v];
-                m.x = fmaxf(m.x, a.x);
-                m.y = fmaxf(m.y, a.y);
-                m.z = fmaxf(m.z, a.z);
-                m.w = fmaxf(m.w, a.w);
-            }
+            for (int i = 0; i < k; ++i) m = unit_max<DT>(m, in[(base + (long long)j * Wo + i) * V + v]);
         if (next_flags) {
             // Change detection of the layer this map feeds (Section 3.1, first formula): the value
             // being replaced is that layer's stored previous input, and positions that are not
             // recomputed cannot differ from it.
             bool f = next_force != 0;
-            if (!f) f = exceeds(m, pooled[(long long)g * V + v], next_tau);
+            if (!f) f = unit_exceeds<DT>(m, pooled[(long long)g * V + v], next_tau);
             if (pow2) {
                 const unsigned long long B = __ballot(f);
                 const unsigned long long grp = (V == 64) ? ~0ull : (((1ull << V) - 1ull) << (lane & ~(V - 1)));
@@ -429,54 +430,62 @@ __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restri
     }
 }
 
-hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const float *in,
-                       float *pooled, int Ms, int k, int Wo, int No, int Wp, int Np, unsigned char *next_flags,
-                       float next_tau, int next_force)
+hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const void *in,
+                       void *pooled, int V, int k, int Wo, int No, int Wp, int Np, unsigned char *next_flags,
+                       float next_tau, int next_force, int dtype)
 {
-    const int V = Ms / 4;
     long long work = (long long)max_count * V;
     long long grid = (work + kBlock - 1) / kBlock;
     if (grid > 2048) grid = 2048;
     if (grid < 1) grid = 1;
-    hipLaunchKernelGGL(pool_sparse_kernel, dim3((int)grid), dim3(kBlock), 0, st, list, count,
-                       reinterpret_cast<const float4 *>(in), reinterpret_cast<float4 *>(pooled), V, k, Wo, No, Wp,
-                       Np, next_flags, next_tau, next_force);
+    const uint4 *i4 = static_cast<const uint4 *>(in);
+    uint4 *p4 = static_cast<uint4 *>(pooled);
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(pool_sparse_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, list, count, i4, p4, V, k,
+                           Wo, No, Wp, Np, next_flags, next_tau, next_force);
+    else
+        hipLaunchKernelGGL(pool_sparse_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, list, count, i4, p4, V, k,
+                           Wo, No, Wp, Np, next_flags, next_tau, next_force);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------
-// Stored map [S*No][Ms] -> planar [S][M][No].  Consecutive lanes take consecutive pixels of
-// one channel plane so the planar writes are coalesced.
+// Stored map [S*No][V units] -> planar float32 [S][M][No].  Consecutive lanes take consecutive
+// pixels' units (16-byte reads) and write one contiguous run per channel plane.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void map_to_planar_kernel(const float4 *__restrict__ map,
+template <int DT>
+__global__ __launch_bounds__(kBlock) void map_to_planar_kernel(const uint4 *__restrict__ map,
                                                                float *__restrict__ planar, int M, int V,
                                                                int No, long long total)
 {
-    // idx = (stream * V + channel group) * No + pixel: consecutive lanes read consecutive pixels'
-    // float4 (stride Ms floats) and write four planes, each a contiguous run per wave
+    constexpr int E = Unit<DT>::N;
     for (long long idx = (long long)blockIdx.x * kBlock + threadIdx.x; idx < total;
          idx += (long long)gridDim.x * kBlock) {
         const int q = (int)(idx % No);
         const long long sv = idx / No;
         const int v = (int)(sv % V);
         const long long st = sv / V;
-        const float4 a = map[(st * No + q) * V + v];
-        float *dst = planar + (st * M + 4 * v) * No + q;
-        dst[0] = a.x;
-        if (4 * v + 1 < M) dst[No] = a.y;
-        if (4 * v + 2 < M) dst[2 * (long long)No] = a.z;
-        if (4 * v + 3 < M) dst[3 * (long long)No] = a.w;
+        const uint4 a = map[(st * No + q) * V + v];
+        float *dst = planar + (st * M + (long long)E * v) * No + q;
+#pragma unroll
+        for (int i = 0; i < E; ++i)
+            if (E * v + i < M) dst[(long long)i * No] = Unit<DT>::get(a, i);
     }
 }
 
-hipError_t map_to_planar(hipStream_t st, const float *map, float *planar, int M, int Ms, int No, int S)
+hipError_t map_to_planar(hipStream_t st, const void *map, float *planar, int M, int V, int No, int S, int dtype)
 {
-    const int V = Ms / 4;
     const long long total = (long long)S * V * No;
     long long grid = (total + kBlock - 1) / kBlock;
     if (grid > 8192) grid = 8192;
-    hipLaunchKernelGGL(map_to_planar_kernel, dim3((int)grid), dim3(kBlock), 0, st,
-                       reinterpret_cast<const float4 *>(map), planar, M, V, No, total);
+    if (grid < 1) grid = 1;
+    const uint4 *m4 = static_cast<const uint4 *>(map);
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(map_to_planar_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, m4, planar, M, V, No,
+                           total);
+    else
+        hipLaunchKernelGGL(map_to_planar_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, m4, planar, M, V, No,
+                           total);
     return hipGetLastError();
 }
 

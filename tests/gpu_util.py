@@ -8,18 +8,24 @@ import oracle
 import paper_1704_04313_amd as cb
 
 RTOL, ATOL = 1e-4, 1e-5     # feature maps, float32 (stated tolerance of the build target)
+# bfloat16 storage: both sides round the same float-accurate sum to 8 significant bits, so they
+# agree exactly or, where the sums straddle a rounding boundary, differ by one bfloat16 step
+# (2^-7 of the value's power of two, at most 2^-7 |b| (1 + 2^-8)); the absolute term covers the
+# float32 accumulation error near zero, as above.
+RTOL_BF16 = 2.0 ** -7 * (1 + 2.0 ** -7)
 
 
-def assert_features_close(got, want, what=""):
+def assert_features_close(got, want, what="", bf16=False):
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape, (what, got.shape, want.shape)
     err = np.abs(got - want)
-    lim = ATOL + RTOL * np.abs(want)
+    rtol = RTOL_BF16 if bf16 else RTOL
+    lim = ATOL + rtol * np.abs(want)
     if not np.all(err <= lim):
         k = int(np.argmax(err - lim))
-        raise AssertionError("%s: %d of %d values outside |a-b| <= 1e-5 + 1e-4|b|; worst at flat index %d: "
-                             "got %r want %r" % (what, int((err > lim).sum()), err.size, k,
+        raise AssertionError("%s: %d of %d values outside |a-b| <= 1e-5 + %.3g|b|; worst at flat index %d: "
+                             "got %r want %r" % (what, int((err > lim).sum()), err.size, rtol, k,
                                                  got.ravel()[k], want.ravel()[k]))
 
 
@@ -28,18 +34,20 @@ def to_dev(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
 
-def compare_sequence(layers, params, inputs, tau, *, hold=False, dense_layers=(), label=""):
+def compare_sequence(layers, params, inputs, tau, *, hold=False, dense_layers=(), label="", bf16=False):
     """Feed the same planar inputs (one array [C][H][W] per frame) to the HIP library and to the
     oracle.  Lists and the stored previous input must agree exactly on every frame; stored
-    output maps within the float32 tolerance.  Only valid when no layer's input depends on
+    output maps within the float32 tolerance (bf16: both sides store bfloat16, tolerance one
+    bfloat16 step).  Only valid when no layer's input depends on
     another layer's floating-point output being bit-identical, i.e. for a single convolution
     layer optionally followed by pooling (teacher-forced comparison)."""
     import torch
     n_conv = sum(1 for L in layers if L.kind == "conv")
     assert n_conv == 1, "teacher-forced comparison is per convolution layer"
     in_shape = inputs[0].shape
-    net = cb.CBInfer(layers, params, in_shape, tau, hold_reference=hold, dense_layers=dense_layers)
-    orc = oracle.OracleCBNet(layers, params, tau, ref_mode=1 if hold else 0, dense_layers=dense_layers)
+    net = cb.CBInfer(layers, params, in_shape, tau, hold_reference=hold, dense_layers=dense_layers,
+                     dtype=cb.BF16 if bf16 else cb.F32)
+    orc = oracle.OracleCBNet(layers, params, tau, ref_mode=1 if hold else 0, dense_layers=dense_layers, bf16=bf16)
     stats = []
     try:
         for t, x in enumerate(inputs):
@@ -56,23 +64,23 @@ def compare_sequence(layers, params, inputs, tau, *, hold=False, dense_layers=()
             assert (nc, nu) == (tr["C"].size, tr["U"].size), what
             np.testing.assert_array_equal(net.read_map(0, cb.MAP_REFERENCE)[0], orc.ref[0],
                                           err_msg=what + " stored previous input")
-            assert_features_close(net.read_map(0, cb.MAP_OUTPUT)[0], orc.out[0], what + " conv output")
+            assert_features_close(net.read_map(0, cb.MAP_OUTPUT)[0], orc.out[0], what + " conv output", bf16)
             if len(layers) > 1:
                 np.testing.assert_array_equal(net.read_list(1, cb.LIST_UPDATE), orc.trace[1]["P"],
                                               err_msg=what + " pooled list")
                 assert net.layer_counts(1) == (-1, orc.trace[1]["P"].size)
-                assert_features_close(net.read_map(1, cb.MAP_OUTPUT)[0], orc.out[1], what + " pooled map")
-            assert_features_close(got.cpu().numpy()[0], want, what + " returned output")
+                assert_features_close(net.read_map(1, cb.MAP_OUTPUT)[0], orc.out[1], what + " pooled map", bf16)
+            assert_features_close(got.cpu().numpy()[0], want, what + " returned output", bf16)
             stats.append((tr["C"].size, tr["U"].size))
     finally:
         net.destroy()
     return stats
 
 
-def oracle_layer_inputs(layers, params, frames, tau, hold=False):
+def oracle_layer_inputs(layers, params, frames, tau, hold=False, bf16=False):
     """Run the oracle network over the frames and record every convolution layer's input
     sequence (copies).  Returns {layer index: [x_0, x_1, ...]}."""
-    orc = oracle.OracleCBNet(layers, params, tau, ref_mode=1 if hold else 0)
+    orc = oracle.OracleCBNet(layers, params, tau, ref_mode=1 if hold else 0, bf16=bf16)
     rec = {l: [] for l, L in enumerate(layers) if L.kind == "conv"}
     for f in frames:
         orc.process_frame(f)
@@ -81,7 +89,7 @@ def oracle_layer_inputs(layers, params, frames, tau, hold=False):
     return rec
 
 
-def compare_sampled(layer, params, frames, tau, *, n_samples=600, n_streams=1, seed=0, label=""):
+def compare_sampled(layer, params, frames, tau, *, n_samples=600, n_streams=1, seed=0, label="", bf16=False):
     """Full-size check of one convolution layer on inputs too large for a complete oracle run.
     `frames`: planar inputs [S][C][H][W] (or [C][H][W]); frame 0 is evaluated densely.
     Lists and counts are compared exactly on every frame (the oracle's detection, dilation and
@@ -94,7 +102,10 @@ def compare_sampled(layer, params, frames, tau, *, n_samples=600, n_streams=1, s
     frames = [np.asarray(f, dtype=np.float32).reshape((n_streams,) + f.shape[-3:]) for f in frames]
     S, C, H, W = frames[0].shape
     w, b = params
-    net = cb.CBInfer([L], [params], (C, H, W), tau, n_streams=S)
+    if bf16:   # what both sides store: frames and weights rounded to bfloat16
+        frames = [oracle.round_bf16(f.copy()) for f in frames]
+        w = oracle.round_bf16(np.array(w, dtype=np.float32))
+    net = cb.CBInfer([L], [params], (C, H, W), tau, n_streams=S, dtype=cb.BF16 if bf16 else cb.F32)
     Ho, Wo = (H + 2 * L.pad - L.kh) // L.stride + 1, (W + 2 * L.pad - L.kw) // L.stride + 1
     r = np.random.default_rng(seed)
     last_update = [np.zeros(Ho * Wo, np.int64) for _ in range(S)]      # frame index of last recompute
@@ -129,9 +140,10 @@ def compare_sampled(layer, params, frames, tau, *, n_samples=600, n_streams=1, s
                 for tt in np.unique(last_update[ss][pos]):
                     sel = pos[last_update[ss][pos] == tt]
                     want = np.zeros((L.cout, Ho, Wo), np.float32)
-                    oracle.conv_update(frames[int(tt)][ss], w, b, sel, want, L.stride, L.pad, L.relu)
+                    oracle.conv_update(frames[int(tt)][ss], w, b, sel, want, L.stride, L.pad, L.relu, bf16)
                     g = got[ss].reshape(L.cout, -1)[:, sel]
                     assert_features_close(g, want.reshape(L.cout, -1)[:, sel],
-                                          "%s stream %d, positions last recomputed in frame %d" % (what, ss, tt))
+                                          "%s stream %d, positions last recomputed in frame %d" % (what, ss, tt),
+                                          bf16)
     finally:
         net.destroy()

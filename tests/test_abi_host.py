@@ -50,7 +50,7 @@ def _net_for(layers, params, shape, **kw):
     ("odd_pool", "multiple of the pooling window"),
     ("streams", "n_streams"),
     ("pool_first", "pooling must directly follow"),
-    ("bf16", "CBINFER_F32"),
+    ("dtype", "dtype must be"),
     ("flags", "flag"),
     ("shape", "frame shape"),
 ])
@@ -74,8 +74,8 @@ def test_invalid_descriptions_are_rejected(case, msg):
     net, keep = _net_for(layers, params, shape, **kw)
     if case == "pad":
         net.layers[0].pad = 3
-    if case == "bf16":
-        net.dtype = binding.BF16
+    if case == "dtype":
+        net.dtype = 7
     assert lib.cbinfer_workspace_bytes(C.byref(net)) == 0
     assert msg in lib.cbinfer_last_error().decode()
 
