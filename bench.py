@@ -6,7 +6,8 @@ dilation, gathered matrix multiplication with output update, change propagation 
 pooling) of the 320x240 scene-labeling workload.  Frames are synthetic, seeded and already
 resident in HBM when the timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg1] [--rate R]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg3|cfg4|cfg5|hbm] [--rate R]
+                    [--dtype f32|bf16]
 """
 from __future__ import annotations
 
@@ -19,6 +20,7 @@ import numpy as np
 
 MI355X_HBM_GBS = 8000.0
 MI355X_FP32_MFMA_TFLOPS = 157.3
+MI355X_BF16_MFMA_TFLOPS = 2500.0
 # HBM bytes per launch of the dominant kernel (gathered GEMM of the 64->256 7x7 layer) on the
 # benchmark workload, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by a plain
 # copy of known size); the commands and figures are in profiles/cfg2_hbm_traffic.md.
@@ -41,6 +43,8 @@ def build_workload(args):
         cfg = get_config(2)
     elif args.workload == "cfg3":
         cfg = get_config(3, change_rate=args.rate, sigma=args.sigma, n_frames=args.frames or 24)
+    elif args.workload == "cfg4":
+        cfg = get_config(4, n_frames=args.frames or 24)
     elif args.workload == "cfg5":
         cfg = get_config(5, n_frames=args.frames or 12)
     elif args.workload == "hbm":
@@ -54,6 +58,8 @@ def build_workload(args):
         raise SystemExit("unknown workload " + args.workload)
     if args.frames:
         cfg.n_frames = args.frames
+    if args.dtype:
+        cfg.dtype = args.dtype
     return cfg
 
 
@@ -75,7 +81,7 @@ def cpu_baseline(cfg, budget_s: float):
     import oracle
     params = cfg.weights()
     video = cfg.video()
-    net = oracle.OracleCBNet(cfg.layers, params, cfg.tau)
+    net = oracle.OracleCBNet(cfg.layers, params, cfg.tau, bf16=cfg.dtype == "bf16")
     net.process_frame(video.frame(0))
     n, spent = 0, 0.0
     while (spent < budget_s and n < cfg.n_frames - 1) or n == 0:
@@ -96,6 +102,8 @@ def parse_args(argv=None):
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--rate", type=float, default=0.02, help="cfg3: nominal changed-pixel share")
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default=None,
+                    help="storage type of maps and weights (default: the workload's)")
     ap.add_argument("--sigma", type=float, default=None, help="override sensor noise")
     ap.add_argument("--frames", type=int, default=0, help="frames generated (default: the workload's)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg (0: skip)")
@@ -139,7 +147,11 @@ def run(args) -> dict:
         frames = np.stack([np.stack([v.frame(t) for v in videos]) for t in range(cfg.n_frames)])
     frames_dev = torch.from_numpy(frames).cuda()
     in_shape = (cfg.channels, cfg.height, cfg.width)
-    net = cb.CBInfer(cfg.layers, params, in_shape, cfg.tau, n_streams=cfg.n_streams)
+    bf16 = cfg.dtype == "bf16"
+    esz = 2.0 if bf16 else 4.0         # bytes per stored map element
+    mfma_peak = MI355X_BF16_MFMA_TFLOPS if bf16 else MI355X_FP32_MFMA_TFLOPS
+    net = cb.CBInfer(cfg.layers, params, in_shape, cfg.tau, n_streams=cfg.n_streams,
+                     dtype=cb.BF16 if bf16 else cb.F32)
     out = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
 
     W, K = args.warmup, args.steps
@@ -159,7 +171,7 @@ def run(args) -> dict:
         "metric": "frames/s and speed-up vs dense HIP conv at 1/5/20% change rate; HBM GB/s",
         "value": cfg.n_streams * K / sec_cb, "unit": "frames/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": 1e3 * sec_cb / K, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "frame": "%dx%dx%d" % (cfg.width, cfg.height, cfg.channels),
                    "tau": cfg.tau, "sigma": cfg.sigma, "n_frames": cfg.n_frames, "n_streams": cfg.n_streams,
                    "reference_update": "previous frame"},
@@ -205,28 +217,29 @@ def run(args) -> dict:
                     continue
                 e = {"us": 1e3 * ms}
                 if name == "detect":
-                    by = cfg.n_streams * (12.0 * c_in * h_in * w_in + h_in * w_in / 8.0)
+                    # frame read (float32) + stored input read and written
+                    by = cfg.n_streams * ((4.0 + 2.0 * esz) * c_in * h_in * w_in + h_in * w_in / 8.0)
                     e.update(bytes=by, GBps=by / (ms * 1e-3) / 1e9, frac_hbm=by / (ms * 1e-3) / 1e9 / MI355X_HBM_GBS)
                 elif name == "gemm":
                     fl = 2.0 * L.cout * L.cin * L.kh * L.kw * n_u * cfg.n_streams
                     e.update(flops=fl, TFLOPs=fl / (ms * 1e-3) / 1e12,
-                             frac_mfma=fl / (ms * 1e-3) / 1e12 / MI355X_FP32_MFMA_TFLOPS)
+                             frac_mfma=fl / (ms * 1e-3) / 1e12 / mfma_peak)
                 elif name == "compact":
                     by = (h_in * w_in + h_out * w_out) / 8.0 + 4.0 * (n_c + n_u)
                     e.update(bytes=by, GBps=by / (ms * 1e-3) / 1e9)
                 elif name == "pool":
-                    by = 4.0 * n_u + 5.0 * 4.0 * c_out * n_u
+                    by = 4.0 * n_u + 5.0 * esz * c_out * n_u
                     e.update(bytes=by, GBps=by / (ms * 1e-3) / 1e9)
                 kernels["L%d.%s" % (l, name)] = e
         dom = max(kernels, key=lambda k: kernels[k]["us"])
         d = kernels[dom]
         if "TFLOPs" in d:
-            roof = {"bound": "mfma", "achieved": d["TFLOPs"], "peak": MI355X_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+            roof = {"bound": "mfma", "achieved": d["TFLOPs"], "peak": mfma_peak, "unit": "TFLOP/s",
                     "frac": d["frac_mfma"], "traffic": None}
         else:
             roof = {"bound": "hbm", "achieved": d.get("GBps"), "peak": MI355X_HBM_GBS, "unit": "GB/s",
                     "frac": (d.get("GBps") or 0.0) / MI355X_HBM_GBS, "traffic": None}
-        if cfg.name.startswith("cfg2") and dom == "L4.gemm":
+        if cfg.name.startswith("cfg2") and dom == "L4.gemm" and not bf16:
             roof["traffic"] = CFG2_DOMINANT_GEMM_HBM_BYTES
         roof["kernel"] = dom
         roof["avg_us"] = d["us"]

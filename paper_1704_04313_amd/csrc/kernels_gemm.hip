@@ -49,15 +49,31 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const float *p, 
         if (lane == 0 && (wave == 0 || wave == 4) && (slot) < 16)                               \
             a.trace[((size_t)blockIdx.x * 2 + (wave >> 2)) * 16 + (slot)] = wall_clock64();      \
     } while (0)
+#define CBK_CYCLES(slot)                                                                        \
+    do {                                                                                        \
+        if (lane == 0 && (wave == 0 || wave == 4) && seg == 0)                                  \
+            a.trace[((size_t)blockIdx.x * 2 + (wave >> 2)) * 16 + (slot)] = clock64();          \
+    } while (0)
 #else
 #define CBK_STAMP(slot) do { } while (0)
+#define CBK_CYCLES(slot) do { } while (0)
 #endif
+
+#ifdef CBK_EXP_NOBARRIER
+#define CBK_LOOP_BARRIER() do { } while (0)
+#else
+#define CBK_LOOP_BARRIER() __syncthreads()
+#endif
+#define CBK_LOOP_BARRIER0() __syncthreads()
 
 static constexpr int BK = 32;       // K slice per pipeline stage: 128 bytes = 32 floats or 64 bfloat16,
                                     // i.e. 8 units of 16 bytes
 static constexpr int KU = 8;        // units per slice
-static constexpr int LDK = BK + 4;  // LDS row pitch in 4-byte words: 144 bytes keeps 16-byte alignment and
-                                    // makes the rows read by one ds_read_b128 phase hit distinct banks
+static constexpr int LDK = BK;      // LDS row pitch in 4-byte words: 128 bytes, no padding.  The eight 16-byte
+                                    // units of a row are stored permuted (unit u of row r sits in slot
+                                    // u ^ lds_swizzle(r)) so that the 16-lane groups of a ds_read_b128
+                                    // (16 rows, one or two neighbouring units) and of a ds_write_b128 (two rows,
+                                    // all units) each cover all 64 banks once
 static constexpr int NT = 512;      // threads per workgroup: 4 consumer + 4 producer waves
 static constexpr int NPROD = 256;   // producer threads
 static constexpr int NCONS = 256;   // consumer threads
@@ -136,7 +152,11 @@ __device__ __forceinline__ void gather_rows(const GemmArgs &a, const int2 tp, co
 #pragma unroll
     for (int ps = 0; ps < PA; ++ps) {
         const bool ok = tv && (unsigned)(iy0[ps] + tj) < (unsigned)a.H && (unsigned)(ix0[ps] + ti) < (unsigned)a.W;
+#ifdef CBK_EXP_NOGATHER
+        ra[ps] = ok ? (floatx4){1.f, 0.f, 0.f, 0.f} : (floatx4){0.f, 0.f, 0.f, 0.f};
+#else
         ra[ps] = ok ? x[base[ps] + tp.x] : (floatx4){0.f, 0.f, 0.f, 0.f};
+#endif
     }
 }
 
@@ -144,6 +164,10 @@ __device__ __forceinline__ void gather_rows(const GemmArgs &a, const int2 tp, co
 template <int BM, int PB>
 __device__ __forceinline__ void load_filter_rows(const floatx4 *wrow, int krow, int kc, int r0, floatx4 (&rb)[PB])
 {
+#ifdef CBK_EXP_NOFILTER
+    for (int ps = 0; ps < PB; ++ps) rb[ps] = (floatx4){(float)kc, 0.f, 0.f, 0.f};
+    return;
+#endif
     if constexpr (BM >= 32) {
 #pragma unroll
         for (int ps = 0; ps < PB; ++ps) rb[ps] = wrow[(size_t)(32 * ps) * krow + kc * KU];
@@ -152,10 +176,23 @@ __device__ __forceinline__ void load_filter_rows(const floatx4 *wrow, int krow, 
     }
 }
 
+__device__ __forceinline__ int lds_swizzle(int row) { return (row >> 1) & 7; }
+
+// v: this thread's slot in the row, i.e. its unit column already permuted for row r0 (rows 32 apart
+// share the permutation).
 template <int BM, int PA, int PB>
 __device__ __forceinline__ void stage_rows(float *A, float *B, int r0, int v, const floatx4 (&ra)[PA],
                                            const floatx4 (&rb)[PB])
 {
+#ifdef CBK_EXP_NOSTAGE
+    if (r0 >= 0) {
+        float t = 0.f;
+        for (int ps = 0; ps < PA; ++ps) t += ra[ps][0];
+        for (int ps = 0; ps < PB; ++ps) t += rb[ps][0];
+        if (t == 12345.678f) A[0] = t;
+        return;
+    }
+#endif
 #pragma unroll
     for (int ps = 0; ps < PA; ++ps) *reinterpret_cast<floatx4 *>(A + (r0 + 32 * ps) * LDK + v * 4) = ra[ps];
     if constexpr (BM >= 32) {
@@ -261,10 +298,17 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             for (int i = 0; i < TP; ++i) acc[j][i] = (floatx4){0.f, 0.f, 0.f, 0.f};
 
         // Both roles execute the same number of barriers: one after the prologue, one per slice.
+#ifdef CBK_EXP_IDLEPROD
+        if (producer) {
+            CBK_LOOP_BARRIER0();
+            for (int kc = kc0; kc < kc1; ++kc) CBK_LOOP_BARRIER();
+        } else
+#endif
         if (producer) {
             const int ptid = tid & (NPROD - 1);
-            const int v = ptid & 7;   // float4 column inside the K slice
+            const int v = ptid & 7;   // 16-byte unit column inside the K slice
             const int r0 = ptid >> 3; // first row this thread stages
+            const int vs = v ^ lds_swizzle(r0); // slot of that unit in those rows
             int iy0[PA], ix0[PA], base[PA];
 #pragma unroll
             for (int ps = 0; ps < PA; ++ps) {
@@ -300,8 +344,8 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             }
             tpA = tap(kc0 + 4);
             tpB = tap(kc0 + 5);
-            stage_rows<BM, PA, PB>(As, Bs, r0, v, raA, rbA);
-            if (kc0 + 1 < kc1) stage_rows<BM, PA, PB>(As + ASZ, Bs + BSZ, r0, v, raB, rbB);
+            stage_rows<BM, PA, PB>(As, Bs, r0, vs, raA, rbA);
+            if (kc0 + 1 < kc1) stage_rows<BM, PA, PB>(As + ASZ, Bs + BSZ, r0, vs, raB, rbB);
             if (kc0 + 2 < kc1) {
                 gather_rows<PA>(a, t2, iy0, ix0, base, raA);
                 load_filter_rows<BM, PB>(wrow, krow, kc0 + 2, r0, rbA);
@@ -315,7 +359,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             int slot = 2; // ring slot of slice kc+2
             for (int kc = kc0; kc < kc1; kc += 2) {
                 if (kc + 2 < kc1) {
-                    stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, v, raA, rbA);
+                    stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, vs, raA, rbA);
                     if (kc + 4 < kc1) {
                         gather_rows<PA>(a, tpA, iy0, ix0, base, raA);
                         load_filter_rows<BM, PB>(wrow, krow, kc + 4, r0, rbA);
@@ -323,10 +367,10 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                     }
                 }
                 slot = slot == kStages - 1 ? 0 : slot + 1;
-                __syncthreads();
+                CBK_LOOP_BARRIER();
                 if (kc + 1 < kc1) {
                     if (kc + 3 < kc1) {
-                        stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, v, raB, rbB);
+                        stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, vs, raB, rbB);
                         if (kc + 5 < kc1) {
                             gather_rows<PA>(a, tpB, iy0, ix0, base, raB);
                             load_filter_rows<BM, PB>(wrow, krow, kc + 5, r0, rbB);
@@ -334,26 +378,40 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                         }
                     }
                     slot = slot == kStages - 1 ? 0 : slot + 1;
-                    __syncthreads();
+                    CBK_LOOP_BARRIER();
                 }
             }
         } else {
-            const float *A0 = As + (wpx0 + lrow) * LDK + lk * 4;
-            const float *B0 = Bs + (wch0 + lrow) * LDK + lk * 4;
+            // fragment group kk of this lane's row: unit 4*kk + lk, stored in slot (4*kk + lk) ^ swizzle
+            const int u0 = (lk ^ lds_swizzle(lrow)) * 4;
+            const float *A0 = As + (wpx0 + lrow) * LDK;
+            const float *B0 = Bs + (wch0 + lrow) * LDK;
             // Each lane reads four consecutive k of its row; MFMA step s then contracts
             // k = 16*group + 4*slot + s for slot = 0..3 -- both operands use the same permutation.
             // D = (filter rows) x (pixel columns): D[4*slot + r][lane%16] lands in this lane,
             // i.e. four consecutive channels of one pixel per accumulator.
             floatx4 af[2][TP], bf[2][TC];
             auto read_frags = [&](int set, int slot, int kk) {
-                const float *A = A0 + slot * ASZ + kk * 16;
-                const float *B = B0 + slot * BSZ + kk * 16;
+#ifdef CBK_EXP_NOREADS
+                if (kc0 >= 0) {
+                    for (int i = 0; i < TP; ++i) af[set][i] = (floatx4){(float)slot, 1.f, 2.f, (float)kk};
+                    for (int j = 0; j < TC; ++j) bf[set][j] = (floatx4){(float)slot, 1.f, 2.f, (float)kk};
+                    return;
+                }
+#endif
+                const float *A = A0 + slot * ASZ + (u0 ^ (kk * 16));
+                const float *B = B0 + slot * BSZ + (u0 ^ (kk * 16));
 #pragma unroll
                 for (int i = 0; i < TP; ++i) af[set][i] = *reinterpret_cast<const floatx4 *>(A + i * 16 * LDK);
 #pragma unroll
                 for (int j = 0; j < TC; ++j) bf[set][j] = *reinterpret_cast<const floatx4 *>(B + j * 16 * LDK);
             };
             auto multiply = [&](int set) {
+#ifdef CBK_EXP_NOMFMA
+                for (int j = 0; j < TC; ++j)
+                    for (int i = 0; i < TP; ++i) acc[j][i] += bf[set][j] + af[set][i];
+                return;
+#endif
                 if constexpr (DT == kBF16) {
                     // one 16-byte fragment = 8 consecutive k: v_mfma_f32_16x16x32_bf16 takes it whole
 #pragma unroll
@@ -376,6 +434,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             };
             __syncthreads();
             CBK_STAMP(3 + 6 * seg);
+            CBK_CYCLES(14);
             // the wave feeding the matrix pipeline wins instruction-issue arbitration on its SIMD
             __builtin_amdgcn_s_setprio(3);
             read_frags(0, 0, 0);
@@ -383,7 +442,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             for (int kc = kc0; kc < kc1; ++kc) {
                 const int nslot = slot == kStages - 1 ? 0 : slot + 1;
                 // The scheduling barriers pin the order "issue the LDS reads of the next fragment
-                // group, then the 64 MFMAs of the current one", so that LDS latency and bandwidth
+                // group, then the MFMAs of the current one", so that LDS latency and bandwidth
                 // are spent while the matrix pipeline is busy.
                 read_frags(1, slot, 1);
                 __builtin_amdgcn_sched_barrier(0);
@@ -394,9 +453,10 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                 multiply(1);
                 __builtin_amdgcn_sched_barrier(0);
                 slot = nslot;
-                __syncthreads();
+                CBK_LOOP_BARRIER();
             }
             __builtin_amdgcn_s_setprio(0);
+            CBK_CYCLES(15);
         }
 
         // ---- a shared tile: store this K range's accumulators, take a ticket; the workgroup
