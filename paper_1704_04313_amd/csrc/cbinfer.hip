@@ -62,6 +62,9 @@ struct Op {
     float tau = 0.f;
     int K = 0, Kpad = 0, Mpad = 0;
     int gemm_grid = 0;
+    bool select = false; // CONV: maps small enough for the GEMM (and the pooling after it) to pick their
+                         // positions from the update maps themselves; index lists are then only
+                         // extracted when the caller asks for them
     int pool_after = -1; // CONV: index of the pooling op that directly follows, or -1
     int conv_before = -1; // MAXPOOL: index of the conv it follows
     // workspace offsets (bytes); SIZE_MAX = absent
@@ -76,6 +79,8 @@ struct Plan {
     bool hold = false;
     int dtype = cbk::kF32; // storage of maps and filter matrices
     size_t o_iota = 0, o_const = 0, o_partial = 0, o_tickets = 0;
+    size_t o_flags = 0;        // the byte change maps of all layers behind the first, contiguous
+    long long flag_words = 0;  // their total size in 64-bit words
     int compute_units = 256; // sizes the GEMM grids; the device's count replaces it in cbinfer_create
     int iota_len = 0;
     size_t bytes = 0;
@@ -194,8 +199,8 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
             op.o_wt = cv.take((size_t)op.Mpad * op.Kpad * esz);
             op.o_bias = cv.take((size_t)op.Mpad * 4);
             op.o_taps = cv.take((size_t)op.Kpad / eu * sizeof(int2));
-            // change map: one bit per pixel, or one byte per pixel when the op before fills it in
-            op.o_chg = cv.take(((size_t)words_for((long long)in_px) + 1) * 64);
+            // change map of the first layer: one bit per pixel
+            if (l == 0) op.o_chg = cv.take(((size_t)words_for((long long)in_px) + 1) * 8);
             op.o_upd = cv.take(((size_t)words_for((long long)out_px) + 1) * 8);
             if (op.pool_after >= 0) {
                 const Op &pp = P.ops[op.pool_after];
@@ -206,6 +211,19 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
             op.o_groups = cv.take(3 * cbk::compact_group_count_bytes(words_for((long long)std::max(in_px, out_px))));
         }
     }
+    // Change maps of the layers behind the first: one bit per pixel, or one byte per pixel when the
+    // op before fills it in.  Contiguous, so that one range clear at the start of a frame covers them.
+    P.o_flags = cv.off;
+    for (size_t l = 1; l < P.ops.size(); ++l) {
+        Op &op = P.ops[l];
+        if (op.kind != CBINFER_OP_CONV) continue;
+        op.o_chg = cv.take(((size_t)words_for((long long)P.S * op.H * op.W) + 1) * 64);
+    }
+    P.flag_words = (long long)(cv.off - P.o_flags) / 8;
+    for (Op &op : P.ops)
+        if (op.kind == CBINFER_OP_CONV)
+            op.select = words_for((long long)P.S * op.Ho * op.Wo) <= cbk::gemm_select_max_words() &&
+                        words_for((long long)P.S * op.H * op.W) <= cbk::gemm_select_max_words();
     P.iota_len = (int)max_px;
     P.o_iota = cv.take((size_t)P.iota_len * 4);
     P.o_const = cv.take(P.ops.size() * 2 * 4);
@@ -237,6 +255,7 @@ struct cbinfer_state {
     bool force_dense = false;
     bool broken = false;
     bool have_frame = false;
+    bool lists_stale = false; // layers in selection mode have not had their index lists extracted for the last frame
     bool profiling = false;
     std::vector<EventPair> events;
     size_t events_used = 0;
@@ -347,11 +366,58 @@ bool fuses_detection(const Plan &P, int l, bool force_dense)
     return l > 0 && !P.hold && !P.ops[l].dense && !force_dense;
 }
 
+// The maps of convolution op l in a change-based frame.
+struct LayerMaps {
+    uint64_t *chg;   // changed input positions: one bit per pixel, or one byte when chg_bytes
+    int chg_bytes;
+    uint64_t *upd;   // output positions to recompute (the change map itself for a 1x1 layer without pooling)
+    int upd_bytes;
+    uint64_t *pool;  // pooled positions to recompute, nullptr without pooling
+    bool identity;   // upd == chg: no dilation launch
+};
+
+LayerMaps layer_maps(const cbinfer_state *s, int l)
+{
+    const Plan &P = s->plan;
+    const Op &op = P.ops[l];
+    LayerMaps m;
+    m.chg = s->at<uint64_t>(op.o_chg);
+    m.chg_bytes = fuses_detection(P, l, s->force_dense) ? 1 : 0;
+    m.pool = op.pool_after >= 0 ? s->at<uint64_t>(op.o_pool) : nullptr;
+    m.identity = op.kh == 1 && op.kw == 1 && op.stride == 1 && op.pad == 0 && !m.pool;
+    m.upd = m.identity ? m.chg : s->at<uint64_t>(op.o_upd);
+    m.upd_bytes = m.identity ? m.chg_bytes : 0;
+    return m;
+}
+
+// Change-index extraction for op l (and the pooling op behind it): maps -> ascending lists and counts.
+hipError_t extract_lists(const cbinfer_state *s, int l, const LayerMaps &m)
+{
+    const Plan &P = s->plan;
+    const Op &op = P.ops[l];
+    const long long N = (long long)P.S * op.H * op.W, No = (long long)P.S * op.Ho * op.Wo;
+    int *counts = s->at<int>(op.o_counts);
+    cbk::CompactJob jobs[3];
+    int nj = 0;
+    const size_t gstride = cbk::compact_group_count_bytes(words_for(std::max(N, No))) / sizeof(int);
+    int *groups = s->at<int>(op.o_groups);
+    jobs[nj++] = {m.upd, m.upd_bytes, words_for(No), s->at<int>(op.o_ulist), counts + 1, groups};
+    jobs[nj++] = {m.chg, m.chg_bytes, words_for(N), s->at<int>(op.o_clist), counts + 0, groups + gstride};
+    if (m.pool) {
+        const Op &pp = P.ops[op.pool_after];
+        jobs[nj++] = {m.pool, 0, words_for((long long)P.S * pp.Ho * pp.Wo), s->at<int>(pp.o_ulist),
+                      s->at<int>(pp.o_counts) + 1, groups + 2 * gstride};
+    }
+    return cbk::compact(s->stream, jobs, nj);
+}
+
+
 int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
 {
     const Plan &P = s->plan;
     hipStream_t st = s->stream;
     const bool first = !s->initialised;
+    s->lists_stale = false;
     const int S = P.S;
     int *iota = s->at<int>(P.o_iota);
     int *consts = s->at<int>(P.o_const);
@@ -374,8 +440,10 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             if (l == 0) {
                 StepTimer t(s, l, CBINFER_STEP_DETECT);
                 const int hold = (P.hold && !s->force_dense) ? 1 : 0;
+                // the same launch zeroes the byte change maps that this frame's kernels fill in
+                uint64_t *flags = s->force_dense ? nullptr : reinterpret_cast<uint64_t *>(s->ws + P.o_flags);
                 HIP_TRY(cbk::detect_frame(st, frame, ref, s->at<void>(op.o_cur), s->at<uint64_t>(op.o_chg), op.C,
-                                          op.Cs / eu, N, S, op.tau, hold, all ? 1 : 0, P.dtype));
+                                          op.Cs / eu, N, S, op.tau, hold, all ? 1 : 0, P.dtype, flags, P.flag_words));
                 x = hold ? s->at<void>(op.o_cur) : ref;
             } else {
                 x = s->at<void>(P.ops[l - 1].o_out);
@@ -387,44 +455,35 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             }
             const int *ulist = iota;
             const int *ucount = consts + 2 * l;
+            const uint64_t *sel_map = nullptr;
+            int sel_bytes = 0;
             if (!s->force_dense) {
-                cbk::DilateGeom g;
-                g.S = S; g.H = op.H; g.W = op.W; g.Ho = op.Ho; g.Wo = op.Wo;
-                g.kh = op.kh; g.kw = op.kw; g.stride = op.stride; g.pad = op.pad;
-                g.pool_k = 0; g.Hp = 0; g.Wp = 0;
-                g.chg_bytes = fused_in ? 1 : 0;
-                uint64_t *pool_bits = nullptr;
-                if (op.pool_after >= 0) {
-                    const Op &pp = P.ops[op.pool_after];
-                    g.pool_k = pp.kh; g.Hp = pp.Ho; g.Wp = pp.Wo;
-                    pool_bits = s->at<uint64_t>(op.o_pool);
-                }
-                // a 1x1 layer's outputs to update are its changed inputs: no dilation needed when the
-                // change map is already a bitmap and no pooled set is wanted
-                const bool identity = op.kh == 1 && op.kw == 1 && op.stride == 1 && op.pad == 0 && !fused_in &&
-                                      !pool_bits;
-                uint64_t *upd_bits = identity ? s->at<uint64_t>(op.o_chg) : s->at<uint64_t>(op.o_upd);
-                if (!identity) {
+                const LayerMaps m = layer_maps(s, l);
+                if (!m.identity) {
+                    cbk::DilateGeom g;
+                    g.S = S; g.H = op.H; g.W = op.W; g.Ho = op.Ho; g.Wo = op.Wo;
+                    g.kh = op.kh; g.kw = op.kw; g.stride = op.stride; g.pad = op.pad;
+                    g.pool_k = 0; g.Hp = 0; g.Wp = 0;
+                    g.chg_bytes = m.chg_bytes;
+                    if (op.pool_after >= 0) {
+                        const Op &pp = P.ops[op.pool_after];
+                        g.pool_k = pp.kh; g.Hp = pp.Ho; g.Wp = pp.Wo;
+                    }
                     StepTimer t(s, l, CBINFER_STEP_DILATE);
-                    HIP_TRY(cbk::dilate(st, s->at<uint64_t>(op.o_chg), upd_bits, pool_bits, g));
+                    HIP_TRY(cbk::dilate(st, m.chg, m.upd, m.pool, g));
                 }
-                cbk::CompactJob jobs[3];
-                int nj = 0;
-                const size_t gstride = cbk::compact_group_count_bytes(words_for((long long)S * std::max(N, No))) / sizeof(int);
-                int *groups = s->at<int>(op.o_groups);
-                jobs[nj++] = {upd_bits, 0, words_for((long long)S * No), s->at<int>(op.o_ulist), counts + 1, groups};
-                jobs[nj++] = {s->at<uint64_t>(op.o_chg), fused_in ? 1 : 0, words_for((long long)S * N), s->at<int>(op.o_clist), counts + 0, groups + gstride};
-                if (op.pool_after >= 0) {
-                    const Op &pp = P.ops[op.pool_after];
-                    jobs[nj++] = {pool_bits, 0, words_for((long long)S * pp.Ho * pp.Wo), s->at<int>(pp.o_ulist),
-                                  s->at<int>(pp.o_counts) + 1, groups + 2 * gstride};
-                }
-                {
+                if (op.select) {
+                    sel_map = m.upd;
+                    sel_bytes = m.upd_bytes;
+                    ulist = nullptr;
+                    ucount = nullptr;
+                    s->lists_stale = true;
+                } else {
                     StepTimer t(s, l, CBINFER_STEP_COMPACT);
-                    HIP_TRY(cbk::compact(st, jobs, nj));
+                    HIP_TRY(extract_lists(s, l, m));
+                    ulist = s->at<int>(op.o_ulist);
+                    ucount = counts + 1;
                 }
-                ulist = s->at<int>(op.o_ulist);
-                ucount = counts + 1;
             }
             // --- gathered matrix generation + multiplication + output update
             cbk::GemmArgs a;
@@ -435,6 +494,9 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             a.taps = s->at<int2>(op.o_taps);
             a.list = ulist;
             a.count = ucount;
+            a.sel_map = sel_map;
+            a.sel_bytes = sel_bytes;
+            a.sel_words = sel_map ? words_for((long long)S * No) : 0;
             a.out = s->at<void>(op.o_out);
             a.N = N; a.H = op.H; a.W = op.W; a.No = No; a.Wo = op.Wo;
             a.stride = op.stride; a.pad = op.pad; a.V = op.Cs / eu; a.Kpad = op.Kpad;
@@ -450,8 +512,6 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                 a.next_flags = s->at<unsigned char>(P.ops[l + 1].o_chg);
                 a.next_tau = P.ops[l + 1].tau;
             }
-            a.clear_bits = fused_in ? s->at<uint64_t>(op.o_chg) : nullptr;
-            a.clear_words = words_for((long long)S * N) * 8; // 64 bytes per 64 pixels
 #ifdef CBK_TRACE
             a.trace = cbk_trace_buffer();
 #endif
@@ -471,9 +531,14 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                 next_tau = P.ops[l + 1].tau;
             }
             StepTimer t(s, l, CBINFER_STEP_POOL);
-            HIP_TRY(cbk::pool_sparse(st, plist, pcount, S * Np, s->at<void>(cv.o_out), s->at<void>(op.o_out),
-                                     op.Ms / cbk::elems_per_unit(P.dtype), op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np,
-                                     next_flags, next_tau, first ? 1 : 0, P.dtype));
+            if (cv.select && !s->force_dense)
+                HIP_TRY(cbk::pool_masked(st, s->at<uint64_t>(cv.o_pool), S * Np, s->at<void>(cv.o_out),
+                                         s->at<void>(op.o_out), op.Ms / cbk::elems_per_unit(P.dtype), op.kh, cv.Wo,
+                                         cv.Ho * cv.Wo, op.Wo, Np, next_flags, next_tau, first ? 1 : 0, P.dtype));
+            else
+                HIP_TRY(cbk::pool_sparse(st, plist, pcount, S * Np, s->at<void>(cv.o_out), s->at<void>(op.o_out),
+                                         op.Ms / cbk::elems_per_unit(P.dtype), op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np,
+                                         next_flags, next_tau, first ? 1 : 0, P.dtype));
         }
     }
     const Op &last = P.ops.back();
@@ -615,9 +680,26 @@ void cbinfer_destroy(cbinfer_state *s)
     delete s;
 }
 
+// Layers in selection mode keep their maps and skip index extraction in the frame itself; the
+// lists and counts of the last frame are extracted here, the first time they are asked for.
+static int refresh_lists(cbinfer_state *s)
+{
+    if (!s->lists_stale) return CBINFER_OK;
+    for (int l = 0; l < (int)s->plan.ops.size(); ++l) {
+        const Op &op = s->plan.ops[l];
+        if (op.kind == CBINFER_OP_CONV && op.select) HIP_TRY(extract_lists(s, l, layer_maps(s, l)));
+    }
+    s->lists_stale = false;
+    return CBINFER_OK;
+}
+
 int cbinfer_set_mode(cbinfer_state *s, int force_dense)
 {
     if (!s) return fail(CBINFER_EINVAL, "state is NULL");
+    if (!s->broken && s->have_frame) {
+        const int rc = refresh_lists(s); // under the mode the last frame ran in
+        if (rc) return rc;
+    }
     s->force_dense = force_dense != 0;
     s->initialised = false;
     return CBINFER_OK;
@@ -647,6 +729,7 @@ int cbinfer_layer_counts(cbinfer_state *s, int layer, int64_t *n_changed, int64_
 {
     int rc = check_query(s, layer);
     if (rc) return rc;
+    if ((rc = refresh_lists(s)) != CBINFER_OK) return rc;
     const Op &op = s->plan.ops[layer];
     int c[2] = {0, 0};
     if (s->force_dense) {
@@ -671,6 +754,7 @@ int cbinfer_read_list(cbinfer_state *s, int layer, int which, int32_t *host, int
     if (which == CBINFER_LIST_CHANGED && op.kind != CBINFER_OP_CONV)
         return fail(CBINFER_EINVAL, "layer %d is a pooling layer and has no changed-input list", layer);
     if (cap < 0 || (cap > 0 && !host)) return fail(CBINFER_EINVAL, "bad host buffer");
+    if ((rc = refresh_lists(s)) != CBINFER_OK) return rc;
     HIP_TRY(hipStreamSynchronize(s->stream));
     int count = 0;
     const int *src = nullptr;

@@ -86,8 +86,11 @@ __device__ __forceinline__ uint4 unit_max(const uint4 &a, const uint4 &b)
 // Writes the change bitmap; refreshes the stored input (hold == 0: everywhere;
 // hold == 1: `cur` receives the frame as a map and `ref` is refreshed only where flagged).
 // force != 0: every pixel is flagged and ref is not read (first frame / dense mode).
+// clear_words 64-bit words starting at clear are zeroed by the same launch (the byte change maps
+// that later kernels of the frame fill in); they must not overlap bits.
 hipError_t detect_frame(hipStream_t st, const float *frame, void *ref, void *cur, uint64_t *bits, int C, int V,
-                        int N, int S, float tau, int hold, int force, int dtype);
+                        int N, int S, float tau, int hold, int force, int dtype, uint64_t *clear,
+                        long long clear_words);
 
 // Map against map (layers fed by a stored output map).  x and ref are [S*N][V units].
 hipError_t detect_map(hipStream_t st, const void *x, void *ref, uint64_t *bits, int V, int total, float tau,
@@ -131,6 +134,13 @@ struct GemmArgs {
                         //   .y = j | i << 8 | valid << 16
     const int *list;    // output pixels to recompute
     const int *count;   // their number (device)
+    // Alternative to list/count for maps of at most gemm_select_max_words() words: the map of
+    // outputs to recompute itself (bit g of word g/64, or one byte per pixel when sel_bytes != 0,
+    // padded to whole words).  Every workgroup then ranks the set positions itself and picks those
+    // of its tile, which saves the separate extraction launch.  sel_words == 0: use list/count.
+    const uint64_t *sel_map;
+    int sel_bytes;
+    int sel_words;
     void *out;          // stored output map [S*No][Ms]
     int N, H, W, No, Wo, stride, pad;
     int V;              // units per input pixel
@@ -144,14 +154,11 @@ struct GemmArgs {
     // Change detection of the next layer fused into the output update (used when that layer's
     // stored previous input is this layer's stored output): positions whose new value differs
     // from the replaced one by more than next_tau get their byte set in next_flags (one byte per
-    // pixel, zero on entry; several workgroups may store the same 1, no atomics needed).
+    // pixel, zeroed at the start of the frame; several workgroups may store the same 1, no atomics
+    // needed).
     unsigned char *next_flags; // nullptr: off
     float next_tau;
     int next_force;            // flag every recomputed position (first frame)
-    // Map this launch clears for the next frame (this layer's own change map, already
-    // condensed into lists when the multiplication runs); nullptr: none.
-    uint64_t *clear_bits;
-    int clear_words;
 #ifdef CBK_TRACE
     unsigned long long *trace; // timing study builds only: [grid][2 roles][16] timestamps
 #endif
@@ -159,6 +166,7 @@ struct GemmArgs {
 int gemm_channel_tile(int M);   // channel tile BM used for M output channels (Mpad = M rounded up to it)
 int gemm_k_multiple(int dtype); // Kpad must be a multiple of this many elements (128 bytes)
 int gemm_grid(const GemmArgs &a, int compute_units); // needs M, Mpad, Kpad, max_pixels
+int gemm_select_max_words(void);
 size_t gemm_partial_bytes(int M, int grid);
 size_t gemm_ticket_bytes(int grid);
 hipError_t gemm_prepare(void);  // one-time function attributes (dynamic LDS size)
@@ -168,11 +176,15 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a);
 // ---- max-pooling at listed pooled positions -----------------------------------------------
 // next_flags != nullptr: the pooled map feeds a convolution layer whose stored previous input is
 // this very map; compare each recomputed value with the one it replaces against next_tau and set
-// the position's byte in that layer's change map (one byte per pixel, zero on entry).
+// the position's byte in that layer's change map (one byte per pixel, zeroed at the start of the frame).
 // next_force != 0: flag every recomputed position (first frame).
 hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const void *in,
                        void *pooled, int V, int k, int Wo, int No, int Wp, int Np, unsigned char *next_flags,
                        float next_tau, int next_force, int dtype);
+// The same at the positions whose bit is set in a bitmap over the total pooled positions (no list).
+hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int total, const void *in, void *pooled, int V, int k,
+                       int Wo, int No, int Wp, int Np, unsigned char *next_flags, float next_tau, int next_force,
+                       int dtype);
 
 // ---- stored map -> caller's planar output --------------------------------------------------
 hipError_t map_to_planar(hipStream_t st, const void *map, float *planar, int M, int V, int No, int S, int dtype);

@@ -88,12 +88,131 @@ static constexpr int kMinIters = CBK_MIN_ITERS; // shortest K range worth giving
 static constexpr int kMaxGrid = 1024;
 static constexpr int kSmallTileFactor = CBK_SMALL_FACTOR; // big tiles are used from (workgroups / this) big tiles on
 
+static constexpr int kSelWordsPerThread = 4;
+static constexpr int kSelMaxWords = kSelWordsPerThread * NT; // largest selection map ranked in-kernel (131072 pixels)
+
 template <int BM, int BN>
 struct TileSmem {
     static constexpr int a_floats = BN * LDK;
     static constexpr int b_floats = BM * LDK;
-    static constexpr int bytes = kStages * (a_floats + b_floats) * 4 + BN * 4 + 16;
+    static constexpr int tile_bytes = kStages * (a_floats + b_floats) * 4 + BN * 4 + 16; // + list, ticket, range
+    // behind the tile: the selection map's words, their exclusive ranks, and the wave totals of the scan
+    static constexpr int sel_offset = (tile_bytes + 15) / 16 * 16;
+    static constexpr int bytes = sel_offset + kSelMaxWords * 12 + 64;
 };
+
+// Selection-map mode: the words of the map and the rank of each word's first set bit, in LDS.
+struct Selection {
+    const uint64_t *words; // nullptr: list mode
+    const int *rank;
+    int nwords;
+};
+
+// Loads the selection map into LDS (sW) and ranks it: sRank[i] = number of selected pixels in
+// the words before word i.  Returns the number of selected pixels.  All NT threads take part;
+// thread t ranks the kSelWordsPerThread consecutive words starting at kSelWordsPerThread * t.
+__device__ __forceinline__ int rank_selection(const GemmArgs &a, uint64_t *sW, int *sRank, int *sTot)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nw = a.sel_words;
+    uint64_t w[kSelWordsPerThread];
+    if (a.sel_bytes) {
+        // One byte per pixel: eight pixels per 64-bit load.  The high bit of
+        // (x | (x & 0x7f..7f) + 0x7f..7f) marks the nonzero bytes and the multiplication gathers
+        // the eight marks into one byte, which is byte i of the bitmap in LDS.
+        unsigned char *sB = reinterpret_cast<unsigned char *>(sW);
+        const int n8 = nw * 8;
+        for (int i0 = 0; i0 < n8; i0 += 4 * NT) {
+            uint64_t x[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = i0 + j * NT + tid;
+                x[j] = i < n8 ? a.sel_map[i] : 0ull;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = i0 + j * NT + tid;
+                const uint64_t nz =
+                    ((x[j] | ((x[j] & 0x7f7f7f7f7f7f7f7full) + 0x7f7f7f7f7f7f7f7full)) & 0x8080808080808080ull) >> 7;
+                if (i < n8) sB[i] = (unsigned char)((nz * 0x0102040810204080ull) >> 56);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < kSelWordsPerThread; ++j) {
+            const int i = kSelWordsPerThread * tid + j;
+            w[j] = i < nw ? sW[i] : 0ull;
+        }
+#pragma unroll
+        for (int j = 0; j < kSelWordsPerThread; ++j) sW[kSelWordsPerThread * tid + j] = w[j]; // zero beyond the map
+    } else {
+#pragma unroll
+        for (int j = 0; j < kSelWordsPerThread; ++j) {
+            const int i = kSelWordsPerThread * tid + j;
+            w[j] = i < nw ? a.sel_map[i] : 0ull;
+        }
+#pragma unroll
+        for (int j = 0; j < kSelWordsPerThread; ++j) sW[kSelWordsPerThread * tid + j] = w[j];
+    }
+    int c[kSelWordsPerThread], sum = 0;
+#pragma unroll
+    for (int j = 0; j < kSelWordsPerThread; ++j) {
+        c[j] = __popcll(w[j]);
+        sum += c[j];
+    }
+    int incl = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) sTot[wave] = incl;
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int i = 0; i < NT / 64; ++i) {
+        const int t = sTot[i];
+        if (i < wave) before += t;
+        total += t;
+    }
+    int e = before + incl - sum;
+#pragma unroll
+    for (int j = 0; j < kSelWordsPerThread; ++j) {
+        sRank[kSelWordsPerThread * tid + j] = e;
+        e += c[j];
+    }
+    __syncthreads();
+    return total;
+}
+
+// The selected pixels of rank r0 .. r0 + BN - 1 into sU (-1 where the selection ends before).
+// sRange: two ints of LDS.  All NT threads take part.
+template <int BN>
+__device__ __forceinline__ void select_tile(const Selection &sel, int n, int r0, int *sU, int *sRange)
+{
+    const int tid = threadIdx.x;
+    const int r1 = (r0 + BN < n ? r0 + BN : n) - 1; // last rank wanted (r0 <= r1: the tile is not empty)
+    for (int i = tid; i < BN; i += NT) sU[i] = -1;
+    // the words holding rank r0 and rank r1: each is found by the one thread that ranks it
+#pragma unroll
+    for (int j = 0; j < kSelWordsPerThread; ++j) {
+        const int i = kSelWordsPerThread * tid + j;
+        const int e = sel.rank[i], c = __popcll(sel.words[i]);
+        if (e <= r0 && r0 < e + c) sRange[0] = i;
+        if (e <= r1 && r1 < e + c) sRange[1] = i;
+    }
+    __syncthreads();
+    const int wlo = sRange[0], whi = sRange[1];
+    // one lane per pixel of those words
+    for (int idx = tid; idx < (whi - wlo + 1) * 64; idx += NT) {
+        const int i = wlo + (idx >> 6), b = idx & 63;
+        const uint64_t bits = sel.words[i];
+        if ((bits >> b) & 1ull) {
+            const int r = sel.rank[i] + __popcll(bits & ((1ull << b) - 1ull)) - r0;
+            if ((unsigned)r < (unsigned)BN) sU[r] = i * 64 + b;
+        }
+    }
+}
 
 // The split of one launch's work over W workgroups; a pure function of its arguments.
 struct Schedule {
@@ -210,7 +329,7 @@ __device__ __forceinline__ void stage_rows(float *A, float *B, int r0, int v, co
 // first fragments of slice kc+1, so the matrix pipeline keeps running across the one barrier
 // per slice.
 template <int DT, int BM, int BN, int WM, int WN>
-__device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n, float *smem)
+__device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n, float *smem, const Selection sel)
 {
     static_assert(WM * WN == 4, "four consumer waves");
     constexpr int TP = BN / WN / 16; // 16-pixel MFMA tiles per consumer wave
@@ -279,9 +398,13 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
 
         CBK_STAMP(2 + 6 * seg);
         __syncthreads(); // the previous segment's LDS reads are done
-        for (int i = tid; i < BN; i += NT) {
-            const int u = pt * BN + i;
-            sU[i] = (u < n) ? a.list[u] : -1;
+        if (sel.words) {
+            select_tile<BN>(sel, n, pt * BN, sU, sFlag + 1);
+        } else {
+            for (int i = tid; i < BN; i += NT) {
+                const int u = pt * BN + i;
+                sU[i] = (u < n) ? a.list[u] : -1;
+            }
         }
         __syncthreads();
 
@@ -591,7 +714,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
     }
 }
 
-// The kernel: clears this layer's change map for the next frame, reads the list length and runs
+// The kernel: reads the list length (or ranks the selection map) and runs
 // the tile shape that suits it -- BNB listed pixels per tile normally, BNS when even the deepest K
 // split of the big tiles would leave compute units idle (short lists): small tiles then need no
 // or fewer shared tiles, whose partial sums and reduction are pure overhead.
@@ -599,23 +722,34 @@ template <int DT, int BM, int BNB, int WMB, int WNB, int BNS, int WMS, int WNS>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_gather_kernel(GemmArgs a)
 {
     extern __shared__ __align__(16) float smem[];
-    const int tid = threadIdx.x;
 #ifdef CBK_TRACE
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #endif
     CBK_STAMP(0);
-    if (a.clear_bits)
-        for (int i = blockIdx.x * NT + tid; i < a.clear_words; i += gridDim.x * NT) a.clear_bits[i] = 0ull;
-    const int n = *a.count;
+    Selection sel = {nullptr, nullptr, 0};
+    int n;
+    if (a.sel_words > 0) {
+        char *base = reinterpret_cast<char *>(smem) + TileSmem<BM, BNB>::sel_offset;
+        uint64_t *sW = reinterpret_cast<uint64_t *>(base);
+        int *sRank = reinterpret_cast<int *>(base + kSelMaxWords * 8);
+        n = rank_selection(a, sW, sRank, sRank + kSelMaxWords);
+        sel.words = sW;
+        sel.rank = sRank;
+        sel.nwords = a.sel_words;
+    } else {
+        n = *a.count;
+    }
     const long long big_tiles = (long long)((n + BNB - 1) / BNB) * (a.Mpad / BM);
     if (big_tiles * kSmallTileFactor >= (long long)gridDim.x)
-        gemm_gather_body<DT, BM, BNB, WMB, WNB>(a, n, smem);
+        gemm_gather_body<DT, BM, BNB, WMB, WNB>(a, n, smem, sel);
     else
-        gemm_gather_body<DT, BM, BNS, WMS, WNS>(a, n, smem);
+        gemm_gather_body<DT, BM, BNS, WMS, WNS>(a, n, smem, sel);
 }
 
 // ---- host side --------------------------------------------------------------------------
 int gemm_k_multiple(int dtype) { return BK * 4 / elem_bytes(dtype); }
+
+int gemm_select_max_words(void) { return kSelMaxWords; }
 
 int gemm_channel_tile(int M)
 {
@@ -691,6 +825,9 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a)
     const int eu = elems_per_unit(a.dtype);
     if (a.Mpad % bm != 0 || a.Kpad % gemm_k_multiple(a.dtype) != 0 || a.Ms % eu != 0 || a.V < 1 || !a.partial ||
         !a.tickets || a.grid < 8 || (a.grid & 7))
+        return hipErrorInvalidValue;
+    if (a.sel_words < 0 || a.sel_words > kSelMaxWords || (a.sel_words > 0 && !a.sel_map) ||
+        (a.sel_words == 0 && (!a.list || !a.count)) || (long long)a.sel_words * 64 < a.max_pixels * (a.sel_words > 0))
         return hipErrorInvalidValue;
     switch (bm) {
     case 16: return launch<16, 256, 1, 4, 64, 1, 4>(st, a);

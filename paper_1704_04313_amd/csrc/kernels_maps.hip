@@ -16,10 +16,12 @@ template <int DT, int HOLD>
 __global__ __launch_bounds__(kBlock) void detect_frame_kernel(const float *__restrict__ frame,
                                                               uint4 *__restrict__ ref, uint4 *__restrict__ cur,
                                                               uint64_t *__restrict__ bits, int C, int V, int N,
-                                                              int total, float tau, int force)
+                                                              int total, float tau, int force,
+                                                              uint64_t *__restrict__ clear, long long clear_words)
 {
     constexpr int E = Unit<DT>::N;
     const int g = blockIdx.x * kBlock + threadIdx.x;
+    for (long long i = g; i < clear_words; i += (long long)gridDim.x * kBlock) clear[i] = 0ull;
     bool flag = false;
     if (g < total) {
         const int st = g / N;
@@ -50,14 +52,16 @@ __global__ __launch_bounds__(kBlock) void detect_frame_kernel(const float *__res
 }
 
 hipError_t detect_frame(hipStream_t st, const float *frame, void *ref, void *cur, uint64_t *bits, int C, int V,
-                        int N, int S, float tau, int hold, int force, int dtype)
+                        int N, int S, float tau, int hold, int force, int dtype, uint64_t *clear,
+                        long long clear_words)
 {
+    if (!clear) clear_words = 0;
     const int total = S * N;
     const int grid = (total + kBlock - 1) / kBlock;
     uint4 *r = static_cast<uint4 *>(ref), *c = static_cast<uint4 *>(cur);
 #define CBK_LAUNCH(DT_, HOLD_)                                                                                  \
     hipLaunchKernelGGL((detect_frame_kernel<DT_, HOLD_>), dim3(grid), dim3(kBlock), 0, st, frame, r, c, bits, C, \
-                       V, N, total, tau, force)
+                       V, N, total, tau, force, clear, clear_words)
     if (dtype == kBF16) {
         if (hold) CBK_LAUNCH(kBF16, 1); else CBK_LAUNCH(kBF16, 0);
     } else {
@@ -390,6 +394,45 @@ hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs)
 // Max-pooling at the listed pooled positions only: each is the maximum over its k x k window
 // of the stored (already updated, post-activation) map.  One thread per (position, 16-byte unit of channels).
 // ------------------------------------------------------------------------------------------
+// One pooled position g, one unit v of its channels: the maximum over the window, the optional
+// comparison with the value it replaces (all lanes of the wave must call this together: the
+// flag of a position is combined across its V lanes with a ballot when V is a power of two).
+template <int DT>
+__device__ __forceinline__ void pool_unit(bool active, int g, int v, const uint4 *__restrict__ in,
+                                          uint4 *__restrict__ pooled, int V, int k, int Wo, int No, int Wp, int Np,
+                                          unsigned char *__restrict__ next_flags, float next_tau, int next_force)
+{
+    const int lane = threadIdx.x & 63;
+    const bool pow2 = (V & (V - 1)) == 0 && V <= 64;
+    uint4 m = make_uint4(0u, 0u, 0u, 0u);
+    bool f = false;
+    if (active) {
+        const int st = g / Np, pp = g - st * Np;
+        const int py = pp / Wp, px = pp - py * Wp;
+        const long long base = (long long)st * No + (long long)(py * k) * Wo + px * k;
+        m = in[base * V + v];
+        for (int j = 0; j < k; ++j)
+            for (int i = 0; i < k; ++i) m = unit_max<DT>(m, in[(base + (long long)j * Wo + i) * V + v]);
+        if (next_flags) {
+            // Change detection of the layer this map feeds (Section 3.1, first formula): the value
+            // being replaced is that layer's stored previous input, and positions that are not
+            // recomputed cannot differ from it.
+            f = next_force != 0;
+            if (!f) f = unit_exceeds<DT>(m, pooled[(long long)g * V + v], next_tau);
+        }
+    }
+    if (next_flags) {
+        if (pow2) {
+            const unsigned long long B = __ballot(f);
+            const unsigned long long grp = (V == 64) ? ~0ull : (((1ull << V) - 1ull) << (lane & ~(V - 1)));
+            if (active && v == 0 && (B & grp) != 0ull) next_flags[g] = 1;
+        } else if (f) {
+            next_flags[g] = 1;
+        }
+    }
+    if (active) pooled[(long long)g * V + v] = m;
+}
+
 template <int DT>
 __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restrict__ list,
                                                              const int *__restrict__ count,
@@ -400,33 +443,33 @@ __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restri
                                                              float next_tau, int next_force)
 {
     const long long total = (long long)(*count) * V;
-    const int lane = threadIdx.x & 63;
-    const bool pow2 = (V & (V - 1)) == 0 && V <= 64;
-    for (long long idx = (long long)blockIdx.x * kBlock + threadIdx.x; idx < total;
-         idx += (long long)gridDim.x * kBlock) {
-        const int u = (int)(idx / V), v = (int)(idx - (long long)u * V);
-        const int g = list[u];
-        const int st = g / Np, pp = g - st * Np;
-        const int py = pp / Wp, px = pp - py * Wp;
-        const long long base = (long long)st * No + (long long)(py * k) * Wo + px * k;
-        uint4 m = in[base * V + v];
-        for (int j = 0; j < k; ++j)
-            for (int i = 0; i < k; ++i) m = unit_max<DT>(m, in[(base + (long long)j * Wo + i) * V + v]);
-        if (next_flags) {
-            // Change detection of the layer this map feeds (Section 3.1, first formula): the value
-            // being replaced is that layer's stored previous input, and positions that are not
-            // recomputed cannot differ from it.
-            bool f = next_force != 0;
-            if (!f) f = unit_exceeds<DT>(m, pooled[(long long)g * V + v], next_tau);
-            if (pow2) {
-                const unsigned long long B = __ballot(f);
-                const unsigned long long grp = (V == 64) ? ~0ull : (((1ull << V) - 1ull) << (lane & ~(V - 1)));
-                if (v == 0 && (B & grp) != 0ull) next_flags[g] = 1;
-            } else if (f) {
-                next_flags[g] = 1;
-            }
-        }
-        pooled[(long long)g * V + v] = m;
+    const long long step = (long long)gridDim.x * kBlock;
+    // whole waves iterate together (the last round with some lanes inactive)
+    for (long long i0 = (long long)blockIdx.x * kBlock; i0 < total; i0 += step) {
+        const long long idx = i0 + threadIdx.x;
+        const bool active = idx < total;
+        const int u = active ? (int)(idx / V) : 0, v = active ? (int)(idx - (long long)u * V) : 0;
+        const int g = active ? list[u] : 0;
+        pool_unit<DT>(active, g, v, in, pooled, V, k, Wo, No, Wp, Np, next_flags, next_tau, next_force);
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kBlock) void pool_masked_kernel(const uint64_t *__restrict__ bits, int total_px,
+                                                             const uint4 *__restrict__ in,
+                                                             uint4 *__restrict__ pooled, int V, int k, int Wo,
+                                                             int No, int Wp, int Np,
+                                                             unsigned char *__restrict__ next_flags,
+                                                             float next_tau, int next_force)
+{
+    const long long total = (long long)total_px * V;
+    const long long step = (long long)gridDim.x * kBlock;
+    for (long long i0 = (long long)blockIdx.x * kBlock; i0 < total; i0 += step) {
+        const long long idx = i0 + threadIdx.x;
+        bool active = idx < total;
+        const int g = active ? (int)(idx / V) : 0, v = active ? (int)(idx - (long long)g * V) : 0;
+        if (active) active = ((bits[g >> 6] >> (g & 63)) & 1ull) != 0ull;
+        pool_unit<DT>(active, g, v, in, pooled, V, k, Wo, No, Wp, Np, next_flags, next_tau, next_force);
     }
 }
 
@@ -445,6 +488,25 @@ hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int ma
                            Wo, No, Wp, Np, next_flags, next_tau, next_force);
     else
         hipLaunchKernelGGL(pool_sparse_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, list, count, i4, p4, V, k,
+                           Wo, No, Wp, Np, next_flags, next_tau, next_force);
+    return hipGetLastError();
+}
+
+hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int total, const void *in, void *pooled, int V, int k,
+                       int Wo, int No, int Wp, int Np, unsigned char *next_flags, float next_tau, int next_force,
+                       int dtype)
+{
+    long long work = (long long)total * V;
+    long long grid = (work + kBlock - 1) / kBlock;
+    if (grid > 4096) grid = 4096;
+    if (grid < 1) grid = 1;
+    const uint4 *i4 = static_cast<const uint4 *>(in);
+    uint4 *p4 = static_cast<uint4 *>(pooled);
+    if (dtype == kBF16)
+        hipLaunchKernelGGL(pool_masked_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, bits, total, i4, p4, V, k,
+                           Wo, No, Wp, Np, next_flags, next_tau, next_force);
+    else
+        hipLaunchKernelGGL(pool_masked_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, bits, total, i4, p4, V, k,
                            Wo, No, Wp, Np, next_flags, next_tau, next_force);
     return hipGetLastError();
 }
