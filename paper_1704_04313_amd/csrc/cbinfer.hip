@@ -188,14 +188,15 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
     for (size_t l = 0; l < P.ops.size(); ++l) {
         Op &op = P.ops[l];
         const size_t in_px = (size_t)P.S * op.H * op.W, out_px = (size_t)P.S * op.Ho * op.Wo;
-        op.o_out = cv.take(out_px * op.Ms * esz);
+        // every map is followed by one 16-byte unit of zeros, which gathers outside the image read
+        op.o_out = cv.take(out_px * op.Ms * esz + 16);
         op.o_ulist = cv.take(out_px * 4);
         op.o_counts = cv.take(4 * 4);
         if (op.kind == CBINFER_OP_CONV) {
             // Layers behind the first keep no copy of their previous input unless asked to hold it
             // or to run densely: their previous input is the stored output of the op before them.
-            if (l == 0 || P.hold || op.dense) op.o_ref = cv.take(in_px * op.Cs * esz);
-            if (l == 0 && P.hold) op.o_cur = cv.take(in_px * op.Cs * esz);
+            if (l == 0 || P.hold || op.dense) op.o_ref = cv.take(in_px * op.Cs * esz + 16);
+            if (l == 0 && P.hold) op.o_cur = cv.take(in_px * op.Cs * esz + 16);
             op.o_wt = cv.take((size_t)op.Mpad * op.Kpad * esz);
             op.o_bias = cv.take((size_t)op.Mpad * 4);
             op.o_taps = cv.take((size_t)op.Kpad / eu * sizeof(int2));
@@ -500,6 +501,7 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             a.out = s->at<void>(op.o_out);
             a.N = N; a.H = op.H; a.W = op.W; a.No = No; a.Wo = op.Wo;
             a.stride = op.stride; a.pad = op.pad; a.V = op.Cs / eu; a.Kpad = op.Kpad;
+            a.zero_unit = S * N * a.V;
             a.M = op.M; a.Mpad = op.Mpad; a.Ms = op.Ms; a.relu = op.relu;
             a.max_pixels = S * No;
             a.partial = s->at<float>(P.o_partial);

@@ -126,7 +126,7 @@ hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs);
 // ---- gathered matrix generation + multiplication + output update (Section 3.1) -------------
 struct GemmArgs {
     int dtype;          // kF32 or kBF16: storage of x, wt and out
-    const void *x;      // input map [S*N][V units]
+    const void *x;      // input map [S*N][V units], followed by at least one unit of zeros
     const void *wt;     // filter matrix, [Mpad][Kpad], k = (j*kw + i)*Cs + c, zero padded
     const float *bias;  // [Mpad] float32
     const int2 *taps;   // one entry per 16-byte unit of a filter-matrix row:
@@ -144,6 +144,7 @@ struct GemmArgs {
     void *out;          // stored output map [S*No][Ms]
     int N, H, W, No, Wo, stride, pad;
     int V;              // units per input pixel
+    int zero_unit;      // index of a 16-byte unit of zeros relative to x (gathers outside the image read it)
     int Kpad;           // filter-matrix row length in elements, a multiple of gemm_k_multiple(dtype)
     int M, Mpad, Ms, relu;
     int max_pixels;     // upper bound of *count

@@ -271,11 +271,10 @@ __device__ __forceinline__ void gather_rows(const GemmArgs &a, const int2 tp, co
 #pragma unroll
     for (int ps = 0; ps < PA; ++ps) {
         const bool ok = tv && (unsigned)(iy0[ps] + tj) < (unsigned)a.H && (unsigned)(ix0[ps] + ti) < (unsigned)a.W;
-#ifdef CBK_EXP_NOGATHER
-        ra[ps] = ok ? (floatx4){1.f, 0.f, 0.f, 0.f} : (floatx4){0.f, 0.f, 0.f, 0.f};
-#else
-        ra[ps] = ok ? x[base[ps] + tp.x] : (floatx4){0.f, 0.f, 0.f, 0.f};
-#endif
+        // outside the image (or no pixel in this row): the zero unit kept behind the map, so that the
+        // load needs no predication and the registers no clearing
+        const unsigned idx = ok ? (unsigned)(base[ps] + tp.x) : (unsigned)a.zero_unit;
+        ra[ps] = x[idx];
     }
 }
 
