@@ -33,7 +33,7 @@ typedef struct cbinfer_state cbinfer_state; /* opaque; owns all per-layer state 
 enum {
     CBINFER_OK = 0,
     CBINFER_EINVAL = -1,       /* bad argument or inconsistent network description */
-    CBINFER_EUNSUPPORTED = -2, /* valid but not implemented (size limits, dtype) */
+    CBINFER_EUNSUPPORTED = -2, /* valid but not implemented (size limits, layer combinations) */
     CBINFER_ENOMEM = -3,       /* device allocation failed or caller workspace too small */
     CBINFER_EDEVICE = -4,      /* a HIP call failed; the state must be destroyed */
     CBINFER_ESTATE = -5        /* call not valid in the current state (e.g. no frame yet) */
@@ -60,6 +60,9 @@ typedef struct {
     int32_t relu;      /* CONV: apply max(0, .) in the output update (Section 3.1, "Output Updating") */
     int32_t dense;     /* CONV: 1 = recompute every position every frame (the paper kept its two
                           pixel-classification layers dense, Section 4.2) */
+    int32_t propagate; /* CONV behind the first: 1 = no change detection of its own; every input position the
+                          op before it recomputed counts as changed (the worst-case change propagation that
+                          Section 5.3 compares per-layer detection with).  Not together with dense */
     float threshold;   /* CONV: change-detection threshold tau of this layer (Section 3.3);
                           negative = use the global threshold given to cbinfer_create */
     const void *weight; /* HOST, [cout][cin][kh][kw] float32, read during cbinfer_create only */
@@ -72,8 +75,9 @@ typedef struct {
     int32_t in_c, in_h, in_w;    /* frame shape per stream */
     int32_t n_streams;           /* >= 1 independent cameras processed together; each has its own
                                     state; index lists are concatenated in stream order */
-    int32_t dtype;               /* storage type of the library's internal maps and weights:
-                                    CBINFER_F32 (frames, outputs and thresholds are float32 either way) */
+    int32_t dtype;               /* storage type of the library's internal maps and filter matrices:
+                                    CBINFER_F32, or CBINFER_BF16 (values rounded to nearest even, float32
+                                    accumulation); frames, outputs, bias and thresholds are float32 either way */
     uint32_t flags;              /* CBINFER_FLAG_* */
     void *stream;                /* hipStream_t all work is enqueued on (NULL = default stream) */
     void *workspace;             /* DEVICE memory for all state and scratch, 256-byte aligned, or

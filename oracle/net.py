@@ -41,13 +41,15 @@ class OracleCBNet:
     ref_mode: 0 = the stored previous input is the previous frame's input everywhere
               (the x^(t-1) of the detection formula); 1 = it is only refreshed where a
               change was flagged.
+    propagate_layers: conv layers (not the first) that run no change detection and take every
+              input position recomputed by the layer before them as changed (Section 5.3).
     After process_frame(), self.trace[l] holds, per conv layer: 'x' (its input), 'flags',
     'C' (changed input positions), 'upd' (map), 'U' (outputs recomputed), 'out' (stored
     output after the update); per pooling layer: 'P' (pooled positions touched) and 'out'.
     """
 
     def __init__(self, layers, params, tau, ref_mode: int = 0, bf16: bool = False,
-                 dense_layers: Sequence[int] = ()):
+                 dense_layers: Sequence[int] = (), propagate_layers: Sequence[int] = ()):
         self.layers = list(layers)
         self.params = []
         for L, P in zip(self.layers, params):
@@ -61,6 +63,8 @@ class OracleCBNet:
         self.ref_mode = int(ref_mode)
         self.bf16 = bool(bf16)
         self.dense_layers = set(dense_layers)
+        self.propagate_layers = set(propagate_layers)
+        assert 0 not in self.propagate_layers and not (self.propagate_layers & self.dense_layers)
         self.reset()
 
     def reset(self):
@@ -80,6 +84,11 @@ class OracleCBNet:
                 Cc, H, W = x.shape
                 if not self.initialised or l in self.dense_layers:
                     flags = np.ones((H, W), np.uint8)
+                elif l in self.propagate_layers:
+                    # worst-case propagation (Section 5.3): no detection; every position the layer
+                    # before recomputed (carried through pooling) counts as changed
+                    flags = np.array(prev_upd, dtype=np.uint8, copy=True)
+                    assert flags.shape == (H, W)
                 else:
                     flags = steps.detect(x, self.ref[l], self.tau[l])
                 if self.ref[l] is None:

@@ -27,7 +27,7 @@ EXPORTS = [
 class cbinfer_layer(C.Structure):
     _fields_ = [("kind", C.c_int32), ("cin", C.c_int32), ("cout", C.c_int32), ("kh", C.c_int32),
                 ("kw", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32), ("relu", C.c_int32),
-                ("dense", C.c_int32), ("threshold", C.c_float), ("weight", C.c_void_p),
+                ("dense", C.c_int32), ("propagate", C.c_int32), ("threshold", C.c_float), ("weight", C.c_void_p),
                 ("bias", C.POINTER(C.c_float))]
 
 
@@ -97,7 +97,8 @@ def _last_error(lib) -> str:
     return (lib.cbinfer_last_error() or b"").decode("utf-8", "replace")
 
 
-def _describe(layers, params, in_shape, n_streams, flags, tau_per_layer, dense_layers, keep, dtype=F32):
+def _describe(layers, params, in_shape, n_streams, flags, tau_per_layer, dense_layers, keep, dtype=F32,
+              propagate_layers=()):
     """Build the C network description.  `keep` collects every numpy array the pointers refer to."""
     arr = (cbinfer_layer * len(layers))()
     for l, L in enumerate(layers):
@@ -110,6 +111,7 @@ def _describe(layers, params, in_shape, n_streams, flags, tau_per_layer, dense_l
             d.kind, d.cin, d.cout, d.kh, d.kw = OP_CONV, L.cin, L.cout, L.kh, L.kw
             d.stride, d.pad, d.relu = L.stride, L.pad, int(L.relu)
             d.dense = int(l in dense_layers)
+            d.propagate = int(l in propagate_layers)
             d.threshold = -1.0 if tau_per_layer is None else float(tau_per_layer[l])
             d.weight = w.ctypes.data_as(C.c_void_p)
             if b is not None:
@@ -145,7 +147,8 @@ class CBInfer:
     all work is enqueued on the torch stream that was current at construction."""
 
     def __init__(self, layers, params, in_shape, tau, *, n_streams: int = 1, hold_reference: bool = False,
-                 dense_layers: Sequence[int] = (), caller_workspace: bool = True, dtype: int = F32):
+                 dense_layers: Sequence[int] = (), caller_workspace: bool = True, dtype: int = F32,
+                 propagate_layers: Sequence[int] = ()):
         import torch
         self._torch = torch
         self.lib = load_library()
@@ -160,7 +163,7 @@ class CBInfer:
         flags = FLAG_HOLD_REFERENCE if hold_reference else 0
         self.dtype = int(dtype)
         net = _describe(self.layers, params, self.in_shape, n_streams, flags, per_layer, set(dense_layers), keep,
-                        self.dtype)
+                        self.dtype, set(propagate_layers))
         self.stream = torch.cuda.current_stream()
         net.stream = C.c_void_p(self.stream.cuda_stream)
         self.workspace = None

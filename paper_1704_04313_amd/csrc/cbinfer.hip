@@ -58,7 +58,7 @@ struct Op {
     int C = 0, Cs = 0, H = 0, W = 0;
     // output map
     int M = 0, Ms = 0, Ho = 0, Wo = 0;
-    int kh = 1, kw = 1, stride = 1, pad = 0, relu = 0, dense = 0;
+    int kh = 1, kw = 1, stride = 1, pad = 0, relu = 0, dense = 0, propagate = 0;
     float tau = 0.f;
     int K = 0, Kpad = 0, Mpad = 0;
     int gemm_grid = 0;
@@ -149,6 +149,9 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
             op.pad = L.pad;
             op.relu = L.relu != 0;
             op.dense = L.dense != 0;
+            op.propagate = L.propagate != 0;
+            if (op.propagate && l == 0) return fail(CBINFER_EINVAL, "layer 0: the first layer has no op before it to propagate changes from");
+            if (op.propagate && op.dense) return fail(CBINFER_EINVAL, "layer %d: propagate and dense exclude each other", l);
             op.tau = L.threshold >= 0.0f ? L.threshold : threshold;
             op.M = L.cout;
             op.Ms = round_up(op.M, eu);
@@ -195,7 +198,7 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
         if (op.kind == CBINFER_OP_CONV) {
             // Layers behind the first keep no copy of their previous input unless asked to hold it
             // or to run densely: their previous input is the stored output of the op before them.
-            if (l == 0 || P.hold || op.dense) op.o_ref = cv.take(in_px * op.Cs * esz + 16);
+            if (l == 0 || ((P.hold || op.dense) && !op.propagate)) op.o_ref = cv.take(in_px * op.Cs * esz + 16);
             if (l == 0 && P.hold) op.o_cur = cv.take(in_px * op.Cs * esz + 16);
             op.o_wt = cv.take((size_t)op.Mpad * op.Kpad * esz);
             op.o_bias = cv.take((size_t)op.Mpad * 4);
@@ -364,8 +367,11 @@ void build_taps(const Op &op, int dtype, std::vector<int2> &taps)
 // Whether conv op l takes its change bitmap from the op that produces its input.
 bool fuses_detection(const Plan &P, int l, bool force_dense)
 {
-    return l > 0 && !P.hold && !P.ops[l].dense && !force_dense;
+    return l > 0 && !P.hold && !P.ops[l].dense && !P.ops[l].propagate && !force_dense;
 }
+
+// Whether conv op l runs no detection and takes the positions recomputed by the op before it as changed.
+bool propagates(const Plan &P, int l, bool force_dense) { return l > 0 && P.ops[l].propagate && !force_dense; }
 
 // The maps of convolution op l in a change-based frame.
 struct LayerMaps {
@@ -384,6 +390,14 @@ LayerMaps layer_maps(const cbinfer_state *s, int l)
     LayerMaps m;
     m.chg = s->at<uint64_t>(op.o_chg);
     m.chg_bytes = fuses_detection(P, l, s->force_dense) ? 1 : 0;
+    if (propagates(P, l, s->force_dense)) {
+        // the update map of the convolution before, carried through the pooling in between if any
+        const Op &before = P.ops[l - 1];
+        const int cl = before.kind == CBINFER_OP_CONV ? l - 1 : before.conv_before;
+        const LayerMaps pm = layer_maps(s, cl);
+        m.chg = before.kind == CBINFER_OP_CONV ? pm.upd : pm.pool;
+        m.chg_bytes = before.kind == CBINFER_OP_CONV ? pm.upd_bytes : 0;
+    }
     m.pool = op.pool_after >= 0 ? s->at<uint64_t>(op.o_pool) : nullptr;
     m.identity = op.kh == 1 && op.kw == 1 && op.stride == 1 && op.pad == 0 && !m.pool;
     m.upd = m.identity ? m.chg : s->at<uint64_t>(op.o_upd);
@@ -436,7 +450,7 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             // A layer fed by a stored map finds its changes while that map is updated (the op
             // before it compares each new value with the one it replaces), unless it holds its
             // reference or runs densely.
-            const bool fused_in = l > 0 && !P.hold && !op.dense && !s->force_dense;
+            const bool fused_in = fuses_detection(P, l, s->force_dense);
             // --- change detection (also turns the planar frame into a map for layer 0)
             if (l == 0) {
                 StepTimer t(s, l, CBINFER_STEP_DETECT);
@@ -448,7 +462,7 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                 x = hold ? s->at<void>(op.o_cur) : ref;
             } else {
                 x = s->at<void>(P.ops[l - 1].o_out);
-                if (!s->force_dense && !fused_in) {
+                if (!s->force_dense && !fused_in && !op.propagate) {
                     StepTimer t(s, l, CBINFER_STEP_DETECT);
                     HIP_TRY(cbk::detect_map(st, x, ref, s->at<uint64_t>(op.o_chg), op.Cs / eu, S * N, op.tau,
                                             P.hold ? 1 : 0, all ? 1 : 0, P.dtype));

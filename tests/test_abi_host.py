@@ -52,6 +52,8 @@ def _net_for(layers, params, shape, **kw):
     ("pool_first", "pooling must directly follow"),
     ("dtype", "dtype must be"),
     ("flags", "flag"),
+    ("propagate_first", "no op before it"),
+    ("propagate_dense", "exclude each other"),
     ("shape", "frame shape"),
 ])
 def test_invalid_descriptions_are_rejected(case, msg):
@@ -74,6 +76,11 @@ def test_invalid_descriptions_are_rejected(case, msg):
     net, keep = _net_for(layers, params, shape, **kw)
     if case == "pad":
         net.layers[0].pad = 3
+    if case == "propagate_first":
+        net.layers[0].propagate = 1
+    if case == "propagate_dense":
+        net.layers[2].propagate = 1
+        net.layers[2].dense = 1
     if case == "dtype":
         net.dtype = 7
     assert lib.cbinfer_workspace_bytes(C.byref(net)) == 0

@@ -382,3 +382,52 @@ def test_integer_network_reset_and_dense_switch_keep_lists_exact():
             np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), orc.trace[l]["U"])
         np.testing.assert_array_equal(got, want)
     net.destroy()
+
+
+# ------------------------------------------------------------------ worst-case change propagation
+@pytest.mark.parametrize("prop", [(2,), (3,), (2, 3, 5), (5,)])
+def test_integer_network_with_propagating_layers_bit_exact(prop):
+    """Layers that run no detection and take the positions recomputed before them as changed
+    (Section 5.3), behind a pooling layer, behind a convolution, behind a 1x1 layer."""
+    layers = [conv(3, 8, 3), pool(), conv(8, 20, 3), conv(20, 12, 1), pool(), conv(12, 5, 3, relu=False)]
+    params = _integer_params(layers, 31)
+    H, W = 24, 36
+    frames = _integer_video(H, W, 3, 6, 77)
+    taus = [0.5, None, 1.5, 2.5, None, 3.5]
+    net = cb.CBInfer(layers, params, (3, H, W), taus, propagate_layers=prop)
+    orc = oracle.OracleCBNet(layers, params, [0.0 if t is None else t for t in taus], propagate_layers=prop)
+    for t, f in enumerate(frames):
+        want = orc.process_frame(f)
+        got = net.process_frame(to_dev(f)).cpu().numpy()[0]
+        for l, L in enumerate(layers):
+            what = "layer %d frame %d" % (l, t)
+            if L.kind == "conv":
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_CHANGED), orc.trace[l]["C"], err_msg=what)
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), orc.trace[l]["U"], err_msg=what)
+            else:
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), orc.trace[l]["P"], err_msg=what)
+            np.testing.assert_array_equal(net.read_map(l, cb.MAP_OUTPUT)[0], orc.out[l], err_msg=what)
+        np.testing.assert_array_equal(got, want)
+    net.destroy()
+
+
+def test_scene_network_all_layers_propagating_lists_exact():
+    """With propagation in every layer behind the first, no list depends on a floating-point
+    comparison of computed values, so all lists of the whole network must match exactly."""
+    layers = scene_labeling_net()
+    params = make_weights(layers, 2001)
+    H, W, tau = 80, 96, 0.02
+    v = _video(H, W, sigma=0.005, n_objects=3, seed=40)
+    conv_ids = [l for l, L in enumerate(layers) if L.kind == "conv"]
+    net = cb.CBInfer(layers, params, (3, H, W), tau, propagate_layers=conv_ids[1:])
+    orc = oracle.OracleCBNet(layers, params, tau, propagate_layers=conv_ids[1:])
+    for t in range(4):
+        f = v.frame(t)
+        want = orc.process_frame(f)
+        got = net.process_frame(to_dev(f)).cpu().numpy()[0]
+        for l in conv_ids:
+            np.testing.assert_array_equal(net.read_list(l, cb.LIST_CHANGED), orc.trace[l]["C"])
+            np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), orc.trace[l]["U"])
+            assert net.layer_counts(l) == (orc.trace[l]["C"].size, orc.trace[l]["U"].size)
+        assert_features_close(got, want, "network output frame %d" % t)
+    net.destroy()

@@ -329,3 +329,51 @@ def test_recompute_uses_current_input_everywhere_in_the_support():
     y = net.process_frame(b)
     assert y[0, 2, 2] == 1.25 and y[0, 2, 4] == 0.0     # (2,4) not recomputed: stale by 0.25
     assert net.trace[0]["U"].size == 9
+
+
+# ---------------------------------------------------------------- worst-case change propagation
+def test_propagation_printed_counts_without_detection(golden_dir):
+    """Section 3 / Section 5.3: one changed pixel reaches 7x7 outputs of the first 7x7 layer and,
+    if every one of them is taken as changed (no detection in the second layer), 13x13 outputs
+    of the second: the counts the paper prints, here produced by the propagating mode itself."""
+    vals = {}
+    with open(os.path.join(golden_dir, "propagation_counts.txt")) as fh:
+        for line in fh:
+            if line.strip() and not line.startswith("#"):
+                k, _, v = line.split()[:3]
+                vals[k] = int(v)
+    layers = [conv(1, 2, 7, relu=False), conv(2, 1, 7, relu=False)]
+    params = make_weights(layers, 5)
+    net = oracle.OracleCBNet(layers, params, tau=0.5, propagate_layers=[1])
+    a = np.zeros((1, 31, 31), np.float32)
+    net.process_frame(a)
+    b = a.copy()
+    b[0, 15, 15] = 1.0
+    net.process_frame(b)
+    assert net.trace[0]["U"].size == vals["one_pixel_after_first_7x7"]
+    assert net.trace[1]["C"].size == vals["one_pixel_after_first_7x7"]
+    assert net.trace[1]["U"].size == vals["one_pixel_after_second_7x7"]
+
+
+def test_propagation_is_a_superset_of_detection_and_exact_at_threshold_zero():
+    """Every position whose input value changed at all was recomputed by the layer before, so the
+    propagated set contains the detected set for any threshold; with threshold zero in the first
+    layer the propagating network equals per-frame dense inference bit for bit."""
+    layers, params = _small_net()
+    v = _video(sigma=0.01)
+    det = oracle.OracleCBNet(layers, params, tau=0.02)
+    conv_ids = [l for l, L in enumerate(layers) if L.kind == "conv"]
+    prop = oracle.OracleCBNet(layers, params, tau=0.02, propagate_layers=conv_ids[1:])
+    exact = oracle.OracleCBNet(layers, params, tau=0.0, propagate_layers=conv_ids[1:])
+    for t in range(5):
+        f = v.frame(t)
+        det.process_frame(f)
+        prop.process_frame(f)
+        y = exact.process_frame(f)
+        np.testing.assert_array_equal(y, oracle.dense_forward(layers, params, f)[-1])
+        # both see the same first-layer input, hence the same first-layer sets
+        np.testing.assert_array_equal(det.trace[0]["U"], prop.trace[0]["U"])
+        l1 = conv_ids[1]
+        assert np.isin(det.trace[l1]["C"], prop.trace[l1]["C"]).all()
+        if t:
+            assert prop.trace[l1]["C"].size >= det.trace[l1]["C"].size
