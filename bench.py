@@ -105,6 +105,10 @@ def parse_args(argv=None):
     ap.add_argument("--dtype", choices=["f32", "bf16"], default=None,
                     help="storage type of maps and weights (default: the workload's)")
     ap.add_argument("--sigma", type=float, default=None, help="override sensor noise")
+    ap.add_argument("--hold", action="store_true",
+                    help="refresh the stored previous input only where a change was flagged")
+    ap.add_argument("--propagate", action="store_true",
+                    help="no change detection behind the first layer (worst-case propagation)")
     ap.add_argument("--frames", type=int, default=0, help="frames generated (default: the workload's)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg (0: skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel timing pass")
@@ -150,8 +154,10 @@ def run(args) -> dict:
     bf16 = cfg.dtype == "bf16"
     esz = 2.0 if bf16 else 4.0         # bytes per stored map element
     mfma_peak = MI355X_BF16_MFMA_TFLOPS if bf16 else MI355X_FP32_MFMA_TFLOPS
+    conv_ids = [l for l, L in enumerate(cfg.layers) if L.kind == "conv"]
     net = cb.CBInfer(cfg.layers, params, in_shape, cfg.tau, n_streams=cfg.n_streams,
-                     dtype=cb.BF16 if bf16 else cb.F32)
+                     dtype=cb.BF16 if bf16 else cb.F32, hold_reference=args.hold,
+                     propagate_layers=conv_ids[1:] if args.propagate else ())
     out = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
 
     W, K = args.warmup, args.steps
@@ -174,7 +180,8 @@ def run(args) -> dict:
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "frame": "%dx%dx%d" % (cfg.width, cfg.height, cfg.channels),
                    "tau": cfg.tau, "sigma": cfg.sigma, "n_frames": cfg.n_frames, "n_streams": cfg.n_streams,
-                   "reference_update": "previous frame"},
+                   "reference_update": "where flagged" if args.hold else "previous frame",
+                   "detection": "first layer only, changes propagated" if args.propagate else "every layer"},
         "dense_hip_frames_per_s": cfg.n_streams * K / sec_dense,
         "speedup_vs_dense_hip": sec_dense / sec_cb,
         "paper_context": "8.6x (Tegra X1) / 7.6x (GTX 1080) over cuDNN, 327.6 GOp/s/W; other hardware, other data",
@@ -183,7 +190,6 @@ def run(args) -> dict:
     # ---- per-kernel timing pass (HIP events around every launch, on the library's stream)
     if not args.no_profile:
         n_ops = len(cfg.layers)
-        conv_ids = [l for l, L in enumerate(cfg.layers) if L.kind == "conv"]
         net.reset()
         for t in frame_order(cfg.n_frames, W):
             net.process_frame(frames_dev[t], out)
