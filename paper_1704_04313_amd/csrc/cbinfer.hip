@@ -284,10 +284,11 @@ namespace {
         }                                                                                          \
     } while (0)
 
+// Hands the launch(es) of one step a pair of events that receive the kernel's own start and end
+// time stamps (profiling on), or nothing.
 struct StepTimer {
-    cbinfer_state *s;
     EventPair *ep = nullptr;
-    StepTimer(cbinfer_state *s_, int layer, int step) : s(s_)
+    StepTimer(cbinfer_state *s, int layer, int step)
     {
         if (!s->profiling) return;
         if (s->events_used == s->events.size()) {
@@ -298,12 +299,8 @@ struct StepTimer {
         ep = &s->events[s->events_used++];
         ep->layer = layer;
         ep->step = step;
-        (void)hipEventRecord(ep->a, s->stream);
     }
-    ~StepTimer()
-    {
-        if (ep) (void)hipEventRecord(ep->b, s->stream);
-    }
+    cbk::Timing timing() const { return ep ? cbk::Timing{ep->a, ep->b} : cbk::Timing{}; }
 };
 
 int collect_profile(cbinfer_state *s)
@@ -406,7 +403,7 @@ LayerMaps layer_maps(const cbinfer_state *s, int l)
 }
 
 // Change-index extraction for op l (and the pooling op behind it): maps -> ascending lists and counts.
-hipError_t extract_lists(const cbinfer_state *s, int l, const LayerMaps &m)
+hipError_t extract_lists(const cbinfer_state *s, int l, const LayerMaps &m, const cbk::Timing &tm = cbk::Timing())
 {
     const Plan &P = s->plan;
     const Op &op = P.ops[l];
@@ -423,7 +420,7 @@ hipError_t extract_lists(const cbinfer_state *s, int l, const LayerMaps &m)
         jobs[nj++] = {m.pool, 0, words_for((long long)P.S * pp.Ho * pp.Wo), s->at<int>(pp.o_ulist),
                       s->at<int>(pp.o_counts) + 1, groups + 2 * gstride};
     }
-    return cbk::compact(s->stream, jobs, nj);
+    return cbk::compact(s->stream, jobs, nj, tm);
 }
 
 
@@ -458,14 +455,15 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                 // the same launch zeroes the byte change maps that this frame's kernels fill in
                 uint64_t *flags = s->force_dense ? nullptr : reinterpret_cast<uint64_t *>(s->ws + P.o_flags);
                 HIP_TRY(cbk::detect_frame(st, frame, ref, s->at<void>(op.o_cur), s->at<uint64_t>(op.o_chg), op.C,
-                                          op.Cs / eu, N, S, op.tau, hold, all ? 1 : 0, P.dtype, flags, P.flag_words));
+                                          op.Cs / eu, N, S, op.tau, hold, all ? 1 : 0, P.dtype, flags, P.flag_words,
+                                          t.timing()));
                 x = hold ? s->at<void>(op.o_cur) : ref;
             } else {
                 x = s->at<void>(P.ops[l - 1].o_out);
                 if (!s->force_dense && !fused_in && !op.propagate) {
                     StepTimer t(s, l, CBINFER_STEP_DETECT);
                     HIP_TRY(cbk::detect_map(st, x, ref, s->at<uint64_t>(op.o_chg), op.Cs / eu, S * N, op.tau,
-                                            P.hold ? 1 : 0, all ? 1 : 0, P.dtype));
+                                            P.hold ? 1 : 0, all ? 1 : 0, P.dtype, t.timing()));
                 }
             }
             const int *ulist = iota;
@@ -485,7 +483,7 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                         g.pool_k = pp.kh; g.Hp = pp.Ho; g.Wp = pp.Wo;
                     }
                     StepTimer t(s, l, CBINFER_STEP_DILATE);
-                    HIP_TRY(cbk::dilate(st, m.chg, m.upd, m.pool, g));
+                    HIP_TRY(cbk::dilate(st, m.chg, m.upd, m.pool, g, t.timing()));
                 }
                 if (op.select) {
                     sel_map = m.upd;
@@ -495,7 +493,7 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                     s->lists_stale = true;
                 } else {
                     StepTimer t(s, l, CBINFER_STEP_COMPACT);
-                    HIP_TRY(extract_lists(s, l, m));
+                    HIP_TRY(extract_lists(s, l, m, t.timing()));
                     ulist = s->at<int>(op.o_ulist);
                     ucount = counts + 1;
                 }
@@ -533,7 +531,7 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
 #endif
             {
                 StepTimer t(s, l, CBINFER_STEP_GEMM);
-                HIP_TRY(cbk::gemm_gather(st, a));
+                HIP_TRY(cbk::gemm_gather(st, a, t.timing()));
             }
         } else {
             const Op &cv = P.ops[op.conv_before];
@@ -550,18 +548,18 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             if (cv.select && !s->force_dense)
                 HIP_TRY(cbk::pool_masked(st, s->at<uint64_t>(cv.o_pool), S * Np, s->at<void>(cv.o_out),
                                          s->at<void>(op.o_out), op.Ms / cbk::elems_per_unit(P.dtype), op.kh, cv.Wo,
-                                         cv.Ho * cv.Wo, op.Wo, Np, next_flags, next_tau, first ? 1 : 0, P.dtype));
+                                         cv.Ho * cv.Wo, op.Wo, Np, next_flags, next_tau, first ? 1 : 0, P.dtype, t.timing()));
             else
                 HIP_TRY(cbk::pool_sparse(st, plist, pcount, S * Np, s->at<void>(cv.o_out), s->at<void>(op.o_out),
                                          op.Ms / cbk::elems_per_unit(P.dtype), op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np,
-                                         next_flags, next_tau, first ? 1 : 0, P.dtype));
+                                         next_flags, next_tau, first ? 1 : 0, P.dtype, t.timing()));
         }
     }
     const Op &last = P.ops.back();
     {
         StepTimer t(s, nops - 1, CBINFER_STEP_OUTPUT);
         HIP_TRY(cbk::map_to_planar(st, s->at<void>(last.o_out), out, last.M, last.Ms / cbk::elems_per_unit(P.dtype),
-                                   last.Ho * last.Wo, S, P.dtype));
+                                   last.Ho * last.Wo, S, P.dtype, t.timing()));
     }
     s->initialised = true;
     s->have_frame = true;

@@ -10,9 +10,26 @@
 //   lists     int32 pixel indices g, ascending, with their length in an int32 counter.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace cbk {
+
+// Optional pair of events that receive a launch's own start and end time stamps (the kernel's
+// execution interval as the device records it, without the gaps before and after that events
+// recorded on the stream around a launch would include).  Both null: an ordinary launch.
+struct Timing {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+
+template <typename F, typename... Args>
+inline void launch_kernel(const Timing &tm, F kernel, dim3 grid, dim3 block, unsigned smem, hipStream_t st, Args... args)
+{
+    if (tm.start || tm.stop)
+        hipExtLaunchKernelGGL(kernel, grid, block, smem, st, tm.start, tm.stop, 0u, args...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, smem, st, args...);
+}
 
 enum { kF32 = 0, kBF16 = 1 }; // storage type of maps and filter matrices (accumulation is float32)
 inline int elems_per_unit(int dt) { return dt == kBF16 ? 8 : 4; }
@@ -90,11 +107,11 @@ __device__ __forceinline__ uint4 unit_max(const uint4 &a, const uint4 &b)
 // that later kernels of the frame fill in); they must not overlap bits.
 hipError_t detect_frame(hipStream_t st, const float *frame, void *ref, void *cur, uint64_t *bits, int C, int V,
                         int N, int S, float tau, int hold, int force, int dtype, uint64_t *clear,
-                        long long clear_words);
+                        long long clear_words, const Timing &tm = Timing());
 
 // Map against map (layers fed by a stored output map).  x and ref are [S*N][V units].
 hipError_t detect_map(hipStream_t st, const void *x, void *ref, uint64_t *bits, int V, int total, float tau,
-                      int hold, int force, int dtype);
+                      int hold, int force, int dtype, const Timing &tm = Timing());
 
 // ---- dilation by the filter support (Section 3.1, second formula) -------------------------
 // upd bit (stream, qy, qx) = OR of the change bits inside that output's receptive field.
@@ -106,7 +123,7 @@ struct DilateGeom {
     int chg_bytes;                            // the change map has one byte per pixel instead of one bit
 };
 hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, uint64_t *pool_bits,
-                  const DilateGeom &g);
+                  const DilateGeom &g, const Timing &tm = Timing());
 
 // ---- change-index extraction (Section 3.1) -------------------------------------------------
 // Up to three bitmaps -> ascending index lists and counts in one launch.
@@ -121,7 +138,7 @@ struct CompactJob {
 };
 bool compact_two_level(int nwords);
 size_t compact_group_count_bytes(int nwords);
-hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs);
+hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, const Timing &tm = Timing());
 
 // ---- gathered matrix generation + multiplication + output update (Section 3.1) -------------
 struct GemmArgs {
@@ -172,7 +189,7 @@ size_t gemm_partial_bytes(int M, int grid);
 size_t gemm_ticket_bytes(int grid);
 hipError_t gemm_prepare(void);  // one-time function attributes (dynamic LDS size)
 // Matrix generation, multiplication and output update (bias, activation, scatter) in one launch.
-hipError_t gemm_gather(hipStream_t st, const GemmArgs &a);
+hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm = Timing());
 
 // ---- max-pooling at listed pooled positions -----------------------------------------------
 // next_flags != nullptr: the pooled map feeds a convolution layer whose stored previous input is
@@ -181,14 +198,15 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a);
 // next_force != 0: flag every recomputed position (first frame).
 hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const void *in,
                        void *pooled, int V, int k, int Wo, int No, int Wp, int Np, unsigned char *next_flags,
-                       float next_tau, int next_force, int dtype);
+                       float next_tau, int next_force, int dtype, const Timing &tm = Timing());
 // The same at the positions whose bit is set in a bitmap over the total pooled positions (no list).
 hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int total, const void *in, void *pooled, int V, int k,
                        int Wo, int No, int Wp, int Np, unsigned char *next_flags, float next_tau, int next_force,
-                       int dtype);
+                       int dtype, const Timing &tm = Timing());
 
 // ---- stored map -> caller's planar output --------------------------------------------------
-hipError_t map_to_planar(hipStream_t st, const void *map, float *planar, int M, int V, int No, int S, int dtype);
+hipError_t map_to_planar(hipStream_t st, const void *map, float *planar, int M, int V, int No, int S, int dtype,
+                         const Timing &tm = Timing());
 
 // helpers
 hipError_t fill_iota(hipStream_t st, int *list, int n);

@@ -808,17 +808,19 @@ hipError_t gemm_prepare(void)
 }
 
 template <int BM, int BNB, int WMB, int WNB, int BNS, int WMS, int WNS>
-static hipError_t launch(hipStream_t st, const GemmArgs &a)
+static hipError_t launch(hipStream_t st, const GemmArgs &a, const Timing &tm)
 {
     constexpr int smem_bytes = TileSmem<BM, BNB>::bytes;
     if (a.dtype == kBF16)
-        gemm_gather_kernel<kBF16, BM, BNB, WMB, WNB, BNS, WMS, WNS><<<dim3(a.grid), dim3(NT), smem_bytes, st>>>(a);
+        launch_kernel(tm, gemm_gather_kernel<kBF16, BM, BNB, WMB, WNB, BNS, WMS, WNS>, dim3(a.grid), dim3(NT), smem_bytes,
+                      st, a);
     else
-        gemm_gather_kernel<kF32, BM, BNB, WMB, WNB, BNS, WMS, WNS><<<dim3(a.grid), dim3(NT), smem_bytes, st>>>(a);
+        launch_kernel(tm, gemm_gather_kernel<kF32, BM, BNB, WMB, WNB, BNS, WMS, WNS>, dim3(a.grid), dim3(NT), smem_bytes,
+                      st, a);
     return hipGetLastError();
 }
 
-hipError_t gemm_gather(hipStream_t st, const GemmArgs &a)
+hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm)
 {
     const int bm = gemm_channel_tile(a.M);
     const int eu = elems_per_unit(a.dtype);
@@ -829,10 +831,10 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a)
         (a.sel_words == 0 && (!a.list || !a.count)) || (long long)a.sel_words * 64 < a.max_pixels * (a.sel_words > 0))
         return hipErrorInvalidValue;
     switch (bm) {
-    case 16: return launch<16, 256, 1, 4, 64, 1, 4>(st, a);
-    case 32: return launch<32, 256, 1, 4, 64, 1, 4>(st, a);
-    case 64: return launch<64, 256, 1, 4, 64, 1, 4>(st, a);
-    default: return launch<128, 128, 2, 2, 64, 2, 2>(st, a);
+    case 16: return launch<16, 256, 1, 4, 64, 1, 4>(st, a, tm);
+    case 32: return launch<32, 256, 1, 4, 64, 1, 4>(st, a, tm);
+    case 64: return launch<64, 256, 1, 4, 64, 1, 4>(st, a, tm);
+    default: return launch<128, 128, 2, 2, 64, 2, 2>(st, a, tm);
     }
 }
 

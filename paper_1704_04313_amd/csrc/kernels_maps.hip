@@ -8,10 +8,14 @@ namespace cbk {
 static constexpr int kBlock = 256;
 
 // ------------------------------------------------------------------------------------------
-// Change detection on a planar frame: one thread per pixel, channels in 16-byte units.
-// Frame reads are coalesced per channel plane; the stored map is read and written as one
-// unit per lane and step.  Each wave emits one 64-bit word of the change bitmap.
+// Change detection on a planar frame.  A wave takes kDetectPix * 64 consecutive pixels, lane l
+// the pixels l, l + 64, ...: every access is a full-wave coalesced transaction (one channel
+// plane of the frame, or one 16-byte unit per lane of the stored map), and the loads of all
+// of a lane's pixels are issued before the first is used, which is what keeps enough bytes in
+// flight to approach the HBM rate.  Each group of 64 pixels yields one word of the change bitmap.
 // ------------------------------------------------------------------------------------------
+static constexpr int kDetectPix = 4;
+
 template <int DT, int HOLD>
 __global__ __launch_bounds__(kBlock) void detect_frame_kernel(const float *__restrict__ frame,
                                                               uint4 *__restrict__ ref, uint4 *__restrict__ cur,
@@ -20,47 +24,67 @@ __global__ __launch_bounds__(kBlock) void detect_frame_kernel(const float *__res
                                                               uint64_t *__restrict__ clear, long long clear_words)
 {
     constexpr int E = Unit<DT>::N;
-    const int g = blockIdx.x * kBlock + threadIdx.x;
-    for (long long i = g; i < clear_words; i += (long long)gridDim.x * kBlock) clear[i] = 0ull;
-    bool flag = false;
-    if (g < total) {
-        const int st = g / N;
-        const int p = g - st * N;
-        const float *fp = frame + (size_t)st * C * N + p;
-        uint4 *rp = ref + (size_t)g * V;
-        uint4 *cp = HOLD ? cur + (size_t)g * V : nullptr;
-        for (int u = 0; u < V; ++u) {
-            uint4 xv = make_uint4(0u, 0u, 0u, 0u);
+    constexpr int P = kDetectPix;
+    const int tid = blockIdx.x * kBlock + threadIdx.x;
+    for (long long i = tid; i < clear_words; i += (long long)gridDim.x * kBlock) clear[i] = 0ull;
+    const int lane = threadIdx.x & 63;
+    const int g0 = (tid >> 6) * (64 * P) + lane; // this lane's first pixel
+    bool ok[P], flag[P];
+    const float *fp[P];
 #pragma unroll
-            for (int i = 0; i < E; ++i) {
-                const int c = u * E + i;
-                if (c < C) Unit<DT>::set(xv, i, fp[(size_t)c * N]);
-            }
-            if (!force) flag |= unit_exceeds<DT>(xv, rp[u], tau);
-            if (HOLD)
-                cp[u] = xv;
-            else
-                rp[u] = xv;
-        }
-        if (force) flag = true;
-        if (HOLD && flag)
-            for (int u = 0; u < V; ++u) rp[u] = cp[u];
+    for (int k = 0; k < P; ++k) {
+        const int g = g0 + 64 * k;
+        ok[k] = g < total;
+        flag[k] = false;
+        const int st = ok[k] ? g / N : 0;
+        fp[k] = frame + (size_t)st * C * N + (ok[k] ? g - st * N : 0);
     }
-    const uint64_t word = __ballot(flag);
-    const int g0 = g & ~63;
-    if ((threadIdx.x & 63) == 0 && g0 < total) bits[g0 >> 6] = word;
+    for (int u = 0; u < V; ++u) {
+        uint4 xv[P], rv[P];
+#pragma unroll
+        for (int k = 0; k < P; ++k) {
+            xv[k] = make_uint4(0u, 0u, 0u, 0u);
+            rv[k] = xv[k];
+            if (ok[k]) {
+#pragma unroll
+                for (int i = 0; i < E; ++i) {
+                    const int c = u * E + i;
+                    if (c < C) Unit<DT>::set(xv[k], i, fp[k][(size_t)c * N]);
+                }
+                if (!force) rv[k] = ref[(size_t)(g0 + 64 * k) * V + u];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < P; ++k) {
+            if (!ok[k]) continue;
+            if (!force) flag[k] |= unit_exceeds<DT>(xv[k], rv[k], tau);
+            if (HOLD)
+                cur[(size_t)(g0 + 64 * k) * V + u] = xv[k];
+            else
+                ref[(size_t)(g0 + 64 * k) * V + u] = xv[k];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < P; ++k) {
+        const int g = g0 + 64 * k;
+        if (force) flag[k] = ok[k];
+        if (HOLD && flag[k])
+            for (int u = 0; u < V; ++u) ref[(size_t)g * V + u] = cur[(size_t)g * V + u];
+        const uint64_t word = __ballot(flag[k]);
+        if (lane == 0 && g < total) bits[g >> 6] = word;
+    }
 }
 
 hipError_t detect_frame(hipStream_t st, const float *frame, void *ref, void *cur, uint64_t *bits, int C, int V,
                         int N, int S, float tau, int hold, int force, int dtype, uint64_t *clear,
-                        long long clear_words)
+                        long long clear_words, const Timing &tm)
 {
     if (!clear) clear_words = 0;
     const int total = S * N;
-    const int grid = (total + kBlock - 1) / kBlock;
+    const int grid = (total + kBlock * kDetectPix - 1) / (kBlock * kDetectPix);
     uint4 *r = static_cast<uint4 *>(ref), *c = static_cast<uint4 *>(cur);
 #define CBK_LAUNCH(DT_, HOLD_)                                                                                  \
-    hipLaunchKernelGGL((detect_frame_kernel<DT_, HOLD_>), dim3(grid), dim3(kBlock), 0, st, frame, r, c, bits, C, \
+    launch_kernel(tm, detect_frame_kernel<DT_, HOLD_>, dim3(grid), dim3(kBlock), 0, st, frame, r, c, bits, C, \
                        V, N, total, tau, force, clear, clear_words)
     if (dtype == kBF16) {
         if (hold) CBK_LAUNCH(kBF16, 1); else CBK_LAUNCH(kBF16, 0);
@@ -130,7 +154,7 @@ __global__ __launch_bounds__(1024) void detect_map_kernel(const uint4 *__restric
 }
 
 hipError_t detect_map(hipStream_t st, const void *x, void *ref, uint64_t *bits, int V, int total, float tau,
-                      int hold, int force, int dtype)
+                      int hold, int force, int dtype, const Timing &tm)
 {
     const int words = (total + 63) / 64;
     int nw = V < 16 ? V : 16;
@@ -138,7 +162,7 @@ hipError_t detect_map(hipStream_t st, const void *x, void *ref, uint64_t *bits, 
     const uint4 *x4 = static_cast<const uint4 *>(x);
     uint4 *r4 = static_cast<uint4 *>(ref);
 #define CBK_LAUNCH(DT_, HOLD_)                                                                                  \
-    hipLaunchKernelGGL((detect_map_kernel<DT_, HOLD_>), dim3(words), dim3(nw * 64), 0, st, x4, r4, bits, V, total, \
+    launch_kernel(tm, detect_map_kernel<DT_, HOLD_>, dim3(words), dim3(nw * 64), 0, st, x4, r4, bits, V, total, \
                        tau, force)
     if (dtype == kBF16) {
         if (hold) CBK_LAUNCH(kBF16, 1); else CBK_LAUNCH(kBF16, 0);
@@ -252,15 +276,15 @@ __global__ __launch_bounds__(kBlock) void dilate_kernel(const uint64_t *__restri
 }
 
 hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, uint64_t *pool_bits,
-                  const DilateGeom &g)
+                  const DilateGeom &g, const Timing &tm)
 {
     const int ub = (g.S * g.Ho * g.Wo + kBlock - 1) / kBlock;
     const int pb = (pool_bits && g.pool_k > 0) ? (g.S * g.Hp * g.Wp + kBlock - 1) / kBlock : 0;
     if (g.chg_bytes)
-        hipLaunchKernelGGL(dilate_kernel<true>, dim3(ub + pb), dim3(kBlock), 0, st, chg_bits, upd_bits, pool_bits, g,
+        launch_kernel(tm, dilate_kernel<true>, dim3(ub + pb), dim3(kBlock), 0, st, chg_bits, upd_bits, pool_bits, g,
                            ub);
     else
-        hipLaunchKernelGGL(dilate_kernel<false>, dim3(ub + pb), dim3(kBlock), 0, st, chg_bits, upd_bits, pool_bits, g,
+        launch_kernel(tm, dilate_kernel<false>, dim3(ub + pb), dim3(kBlock), 0, st, chg_bits, upd_bits, pool_bits, g,
                            ub);
     return hipGetLastError();
 }
@@ -369,7 +393,7 @@ bool compact_two_level(int nwords) { return nwords > kCompactWords * 48; }
 
 size_t compact_group_count_bytes(int nwords) { return ((size_t)nwords / kCompactWords + 2) * sizeof(int); }
 
-hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs)
+hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, const Timing &tm)
 {
     if (njobs < 1 || njobs > 3) return hipErrorInvalidValue;
     CompactJobs js;
@@ -382,10 +406,10 @@ hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs)
     if (compact_two_level(maxw)) {
         for (int i = 0; i < njobs; ++i)
             if (!jobs[i].group_counts) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(compact_count_kernel, dim3(gx, njobs), dim3(kBlock), 0, st, js);
-        hipLaunchKernelGGL(compact_kernel<true>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+        launch_kernel(Timing{tm.start, nullptr}, compact_count_kernel, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+        launch_kernel(Timing{nullptr, tm.stop}, compact_kernel<true>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
     } else {
-        hipLaunchKernelGGL(compact_kernel<false>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+        launch_kernel(tm, compact_kernel<false>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
     }
     return hipGetLastError();
 }
@@ -475,7 +499,7 @@ __global__ __launch_bounds__(kBlock) void pool_masked_kernel(const uint64_t *__r
 
 hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const void *in,
                        void *pooled, int V, int k, int Wo, int No, int Wp, int Np, unsigned char *next_flags,
-                       float next_tau, int next_force, int dtype)
+                       float next_tau, int next_force, int dtype, const Timing &tm)
 {
     long long work = (long long)max_count * V;
     long long grid = (work + kBlock - 1) / kBlock;
@@ -484,17 +508,17 @@ hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int ma
     const uint4 *i4 = static_cast<const uint4 *>(in);
     uint4 *p4 = static_cast<uint4 *>(pooled);
     if (dtype == kBF16)
-        hipLaunchKernelGGL(pool_sparse_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, list, count, i4, p4, V, k,
+        launch_kernel(tm, pool_sparse_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, list, count, i4, p4, V, k,
                            Wo, No, Wp, Np, next_flags, next_tau, next_force);
     else
-        hipLaunchKernelGGL(pool_sparse_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, list, count, i4, p4, V, k,
+        launch_kernel(tm, pool_sparse_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, list, count, i4, p4, V, k,
                            Wo, No, Wp, Np, next_flags, next_tau, next_force);
     return hipGetLastError();
 }
 
 hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int total, const void *in, void *pooled, int V, int k,
                        int Wo, int No, int Wp, int Np, unsigned char *next_flags, float next_tau, int next_force,
-                       int dtype)
+                       int dtype, const Timing &tm)
 {
     long long work = (long long)total * V;
     long long grid = (work + kBlock - 1) / kBlock;
@@ -503,10 +527,10 @@ hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int total, const vo
     const uint4 *i4 = static_cast<const uint4 *>(in);
     uint4 *p4 = static_cast<uint4 *>(pooled);
     if (dtype == kBF16)
-        hipLaunchKernelGGL(pool_masked_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, bits, total, i4, p4, V, k,
+        launch_kernel(tm, pool_masked_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, bits, total, i4, p4, V, k,
                            Wo, No, Wp, Np, next_flags, next_tau, next_force);
     else
-        hipLaunchKernelGGL(pool_masked_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, bits, total, i4, p4, V, k,
+        launch_kernel(tm, pool_masked_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, bits, total, i4, p4, V, k,
                            Wo, No, Wp, Np, next_flags, next_tau, next_force);
     return hipGetLastError();
 }
@@ -535,7 +559,8 @@ __global__ __launch_bounds__(kBlock) void map_to_planar_kernel(const uint4 *__re
     }
 }
 
-hipError_t map_to_planar(hipStream_t st, const void *map, float *planar, int M, int V, int No, int S, int dtype)
+hipError_t map_to_planar(hipStream_t st, const void *map, float *planar, int M, int V, int No, int S, int dtype,
+                         const Timing &tm)
 {
     const long long total = (long long)S * V * No;
     long long grid = (total + kBlock - 1) / kBlock;
@@ -543,10 +568,10 @@ hipError_t map_to_planar(hipStream_t st, const void *map, float *planar, int M, 
     if (grid < 1) grid = 1;
     const uint4 *m4 = static_cast<const uint4 *>(map);
     if (dtype == kBF16)
-        hipLaunchKernelGGL(map_to_planar_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, m4, planar, M, V, No,
+        launch_kernel(tm, map_to_planar_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, m4, planar, M, V, No,
                            total);
     else
-        hipLaunchKernelGGL(map_to_planar_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, m4, planar, M, V, No,
+        launch_kernel(tm, map_to_planar_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, m4, planar, M, V, No,
                            total);
     return hipGetLastError();
 }
@@ -561,7 +586,7 @@ hipError_t fill_iota(hipStream_t st, int *list, int n)
     int grid = (n + 255) / 256;
     if (grid > 1024) grid = 1024;
     if (grid < 1) grid = 1;
-    hipLaunchKernelGGL(iota_kernel, dim3(grid), dim3(256), 0, st, list, n);
+    launch_kernel(Timing(), iota_kernel, dim3(grid), dim3(256), 0, st, list, n);
     return hipGetLastError();
 }
 
