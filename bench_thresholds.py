@@ -8,7 +8,7 @@ Base thresholds: the workload's threshold for the first layer; for every deeper 
 value scaled by the ratio of that layer's mean absolute input to the frame's, measured once on
 frame 0 (thresholds that grow with the depth of the layer, as the values selected in Section 4.3
 do).  Optionally every layer behind the first takes its changes from the layer before it without
-a detection of its own (worst-case propagation, Section 5.3), and the reference-update variant
+a detection of its own (worst-case propagation, Section 4.7), and the reference-update variant
 can be selected.  The dense result and the error are computed on the GPU (dense mode of the same
 library; torch reductions over the two outputs).  Prints a markdown table.
 

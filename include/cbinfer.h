@@ -62,7 +62,7 @@ typedef struct {
                           pixel-classification layers dense, Section 4.2) */
     int32_t propagate; /* CONV behind the first: 1 = no change detection of its own; every input position the
                           op before it recomputed counts as changed (the worst-case change propagation that
-                          Section 5.3 compares per-layer detection with).  Not together with dense */
+                          Section 4.7 compares per-layer detection with).  Not together with dense */
     float threshold;   /* CONV: change-detection threshold tau of this layer (Section 3.3);
                           negative = use the global threshold given to cbinfer_create */
     const void *weight; /* HOST, [cout][cin][kh][kw] float32, read during cbinfer_create only */

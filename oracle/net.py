@@ -42,7 +42,7 @@ class OracleCBNet:
               (the x^(t-1) of the detection formula); 1 = it is only refreshed where a
               change was flagged.
     propagate_layers: conv layers (not the first) that run no change detection and take every
-              input position recomputed by the layer before them as changed (Section 5.3).
+              input position recomputed by the layer before them as changed (Section 4.7).
     After process_frame(), self.trace[l] holds, per conv layer: 'x' (its input), 'flags',
     'C' (changed input positions), 'upd' (map), 'U' (outputs recomputed), 'out' (stored
     output after the update); per pooling layer: 'P' (pooled positions touched) and 'out'.
@@ -85,7 +85,7 @@ class OracleCBNet:
                 if not self.initialised or l in self.dense_layers:
                     flags = np.ones((H, W), np.uint8)
                 elif l in self.propagate_layers:
-                    # worst-case propagation (Section 5.3): no detection; every position the layer
+                    # worst-case propagation (Section 4.7): no detection; every position the layer
                     # before recomputed (carried through pooling) counts as changed
                     flags = np.array(prev_upd, dtype=np.uint8, copy=True)
                     assert flags.shape == (H, W)

@@ -388,7 +388,7 @@ def test_integer_network_reset_and_dense_switch_keep_lists_exact():
 @pytest.mark.parametrize("prop", [(2,), (3,), (2, 3, 5), (5,)])
 def test_integer_network_with_propagating_layers_bit_exact(prop):
     """Layers that run no detection and take the positions recomputed before them as changed
-    (Section 5.3), behind a pooling layer, behind a convolution, behind a 1x1 layer."""
+    (Section 4.7), behind a pooling layer, behind a convolution, behind a 1x1 layer."""
     layers = [conv(3, 8, 3), pool(), conv(8, 20, 3), conv(20, 12, 1), pool(), conv(12, 5, 3, relu=False)]
     params = _integer_params(layers, 31)
     H, W = 24, 36

@@ -333,7 +333,7 @@ def test_recompute_uses_current_input_everywhere_in_the_support():
 
 # ---------------------------------------------------------------- worst-case change propagation
 def test_propagation_printed_counts_without_detection(golden_dir):
-    """Section 3 / Section 5.3: one changed pixel reaches 7x7 outputs of the first 7x7 layer and,
+    """Section 3 / Section 4.7: one changed pixel reaches 7x7 outputs of the first 7x7 layer and,
     if every one of them is taken as changed (no detection in the second layer), 13x13 outputs
     of the second: the counts the paper prints, here produced by the propagating mode itself."""
     vals = {}
