@@ -59,12 +59,6 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const float *p, 
 #define CBK_CYCLES(slot) do { } while (0)
 #endif
 
-#ifdef CBK_EXP_NOBARRIER
-#define CBK_LOOP_BARRIER() do { } while (0)
-#else
-#define CBK_LOOP_BARRIER() __syncthreads()
-#endif
-#define CBK_LOOP_BARRIER0() __syncthreads()
 
 static constexpr int BK = 32;       // K slice per pipeline stage: 128 bytes = 32 floats or 64 bfloat16,
                                     // i.e. 8 units of 16 bytes
@@ -282,10 +276,6 @@ __device__ __forceinline__ void gather_rows(const GemmArgs &a, const int2 tp, co
 template <int BM, int PB>
 __device__ __forceinline__ void load_filter_rows(const floatx4 *wrow, int krow, int kc, int r0, floatx4 (&rb)[PB])
 {
-#ifdef CBK_EXP_NOFILTER
-    for (int ps = 0; ps < PB; ++ps) rb[ps] = (floatx4){(float)kc, 0.f, 0.f, 0.f};
-    return;
-#endif
     if constexpr (BM >= 32) {
 #pragma unroll
         for (int ps = 0; ps < PB; ++ps) rb[ps] = wrow[(size_t)(32 * ps) * krow + kc * KU];
@@ -302,15 +292,6 @@ template <int BM, int PA, int PB>
 __device__ __forceinline__ void stage_rows(float *A, float *B, int r0, int v, const floatx4 (&ra)[PA],
                                            const floatx4 (&rb)[PB])
 {
-#ifdef CBK_EXP_NOSTAGE
-    if (r0 >= 0) {
-        float t = 0.f;
-        for (int ps = 0; ps < PA; ++ps) t += ra[ps][0];
-        for (int ps = 0; ps < PB; ++ps) t += rb[ps][0];
-        if (t == 12345.678f) A[0] = t;
-        return;
-    }
-#endif
 #pragma unroll
     for (int ps = 0; ps < PA; ++ps) *reinterpret_cast<floatx4 *>(A + (r0 + 32 * ps) * LDK + v * 4) = ra[ps];
     if constexpr (BM >= 32) {
@@ -420,12 +401,6 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             for (int i = 0; i < TP; ++i) acc[j][i] = (floatx4){0.f, 0.f, 0.f, 0.f};
 
         // Both roles execute the same number of barriers: one after the prologue, one per slice.
-#ifdef CBK_EXP_IDLEPROD
-        if (producer) {
-            CBK_LOOP_BARRIER0();
-            for (int kc = kc0; kc < kc1; ++kc) CBK_LOOP_BARRIER();
-        } else
-#endif
         if (producer) {
             const int ptid = tid & (NPROD - 1);
             const int v = ptid & 7;   // 16-byte unit column inside the K slice
@@ -489,7 +464,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                     }
                 }
                 slot = slot == kStages - 1 ? 0 : slot + 1;
-                CBK_LOOP_BARRIER();
+                __syncthreads();
                 if (kc + 1 < kc1) {
                     if (kc + 3 < kc1) {
                         stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, vs, raB, rbB);
@@ -500,7 +475,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                         }
                     }
                     slot = slot == kStages - 1 ? 0 : slot + 1;
-                    CBK_LOOP_BARRIER();
+                    __syncthreads();
                 }
             }
         } else {
@@ -514,13 +489,6 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             // i.e. four consecutive channels of one pixel per accumulator.
             floatx4 af[2][TP], bf[2][TC];
             auto read_frags = [&](int set, int slot, int kk) {
-#ifdef CBK_EXP_NOREADS
-                if (kc0 >= 0) {
-                    for (int i = 0; i < TP; ++i) af[set][i] = (floatx4){(float)slot, 1.f, 2.f, (float)kk};
-                    for (int j = 0; j < TC; ++j) bf[set][j] = (floatx4){(float)slot, 1.f, 2.f, (float)kk};
-                    return;
-                }
-#endif
                 const float *A = A0 + slot * ASZ + (u0 ^ (kk * 16));
                 const float *B = B0 + slot * BSZ + (u0 ^ (kk * 16));
 #pragma unroll
@@ -529,11 +497,6 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                 for (int j = 0; j < TC; ++j) bf[set][j] = *reinterpret_cast<const floatx4 *>(B + j * 16 * LDK);
             };
             auto multiply = [&](int set) {
-#ifdef CBK_EXP_NOMFMA
-                for (int j = 0; j < TC; ++j)
-                    for (int i = 0; i < TP; ++i) acc[j][i] += bf[set][j] + af[set][i];
-                return;
-#endif
                 if constexpr (DT == kBF16) {
                     // one 16-byte fragment = 8 consecutive k: v_mfma_f32_16x16x32_bf16 takes it whole
 #pragma unroll
@@ -575,7 +538,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                 multiply(1);
                 __builtin_amdgcn_sched_barrier(0);
                 slot = nslot;
-                CBK_LOOP_BARRIER();
+                __syncthreads();
             }
             __builtin_amdgcn_s_setprio(0);
             CBK_CYCLES(15);
@@ -654,8 +617,34 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             for (int j = 0; j < TC; ++j) {
                 const int ch = mt * BM + wch0 + j * 16 + lk * 4;
                 const float4 bv = *reinterpret_cast<const float4 *>(a.bias + ch);
+                // The values about to be replaced are loaded a few positions at a time before the
+                // stores of those positions (the compiler cannot move a load across a store to the
+                // same map, and one round trip to memory per accumulator would line up at the very
+                // end of the kernel).
+                constexpr int CH = TP < 2 ? 1 : 2;
 #pragma unroll
-                for (int i = 0; i < TP; ++i) {
+                for (int i0 = 0; i0 < TP; i0 += CH) {
+                uintx4 replaced[CH];
+                if (detect) {
+#pragma unroll
+                    for (int ii = 0; ii < CH; ++ii) {
+                        const int g = sU[wpx0 + (i0 + ii) * 16 + lrow];
+                        replaced[ii] = (uintx4){0u, 0u, 0u, 0u};
+                        if (g >= 0 && ch < a.Ms) {
+                            if constexpr (DT == kBF16) {
+                                const uint2 v = *reinterpret_cast<const uint2 *>(static_cast<const unsigned short *>(a.out) +
+                                                                                 (size_t)g * a.Ms + ch);
+                                replaced[ii][0] = v.x;
+                                replaced[ii][1] = v.y;
+                            } else {
+                                replaced[ii] = *reinterpret_cast<const uintx4 *>(static_cast<const float *>(a.out) +
+                                                                                 (size_t)g * a.Ms + ch);
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int i = i0; i < i0 + CH; ++i) {
                     const int g = sU[wpx0 + i * 16 + lrow];
                     if (g >= 0 && ch < a.Ms) {
                         float4 o;
@@ -677,7 +666,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                             nv.x = (unsigned)bf16_bits(o.x) | ((unsigned)bf16_bits(o.y) << 16);
                             nv.y = (unsigned)bf16_bits(o.z) | ((unsigned)bf16_bits(o.w) << 16);
                             if (detect) {
-                                const uint2 ov = *dst;
+                                const uint2 ov = make_uint2(replaced[i - i0][0], replaced[i - i0][1]);
                                 changed[i] |= fabsf(bf16_value(nv.x & 0xffff) - bf16_value(ov.x & 0xffff)) > a.next_tau ||
                                               fabsf(bf16_value(nv.x >> 16) - bf16_value(ov.x >> 16)) > a.next_tau ||
                                               fabsf(bf16_value(nv.y & 0xffff) - bf16_value(ov.y & 0xffff)) > a.next_tau ||
@@ -687,13 +676,15 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                         } else {
                             float4 *dst = reinterpret_cast<float4 *>(static_cast<float *>(a.out) + (size_t)g * a.Ms + ch);
                             if (detect) {
-                                const float4 ov = *dst;
+                                const float4 ov = make_float4(__uint_as_float(replaced[i - i0][0]), __uint_as_float(replaced[i - i0][1]),
+                                                              __uint_as_float(replaced[i - i0][2]), __uint_as_float(replaced[i - i0][3]));
                                 changed[i] |= fabsf(o.x - ov.x) > a.next_tau || fabsf(o.y - ov.y) > a.next_tau ||
                                               fabsf(o.z - ov.z) > a.next_tau || fabsf(o.w - ov.w) > a.next_tau;
                             }
                             *dst = o;
                         }
                     }
+                }
                 }
             }
             if (a.next_flags) {
