@@ -385,8 +385,9 @@ def test_integer_network_reset_and_dense_switch_keep_lists_exact():
 
 
 # ------------------------------------------------------------------ worst-case change propagation
-@pytest.mark.parametrize("prop", [(2,), (3,), (2, 3, 5), (5,)])
-def test_integer_network_with_propagating_layers_bit_exact(prop):
+@pytest.mark.parametrize("prop,hold", [((2,), False), ((3,), False), ((2, 3, 5), False), ((5,), False),
+                                       ((2, 3, 5), True), ((3,), True)])
+def test_integer_network_with_propagating_layers_bit_exact(prop, hold):
     """Layers that run no detection and take the positions recomputed before them as changed
     (Section 4.7), behind a pooling layer, behind a convolution, behind a 1x1 layer."""
     layers = [conv(3, 8, 3), pool(), conv(8, 20, 3), conv(20, 12, 1), pool(), conv(12, 5, 3, relu=False)]
@@ -394,8 +395,9 @@ def test_integer_network_with_propagating_layers_bit_exact(prop):
     H, W = 24, 36
     frames = _integer_video(H, W, 3, 6, 77)
     taus = [0.5, None, 1.5, 2.5, None, 3.5]
-    net = cb.CBInfer(layers, params, (3, H, W), taus, propagate_layers=prop)
-    orc = oracle.OracleCBNet(layers, params, [0.0 if t is None else t for t in taus], propagate_layers=prop)
+    net = cb.CBInfer(layers, params, (3, H, W), taus, propagate_layers=prop, hold_reference=hold)
+    orc = oracle.OracleCBNet(layers, params, [0.0 if t is None else t for t in taus], propagate_layers=prop,
+                             ref_mode=1 if hold else 0)
     for t, f in enumerate(frames):
         want = orc.process_frame(f)
         got = net.process_frame(to_dev(f)).cpu().numpy()[0]
@@ -431,3 +433,36 @@ def test_scene_network_all_layers_propagating_lists_exact():
             assert net.layer_counts(l) == (orc.trace[l]["C"].size, orc.trace[l]["U"].size)
         assert_features_close(got, want, "network output frame %d" % t)
     net.destroy()
+
+
+# ------------------------------------------------------------------ index extraction inside / outside the consumers
+@pytest.mark.parametrize("W", [512, 516])
+def test_selection_map_size_boundary(W):
+    """Maps of up to 131072 positions are ranked inside the multiplication kernel, larger ones go
+    through the extraction kernel: 256 x 512 is the largest of the first kind, 256 x 516 the
+    first multiple of four columns of the second.  Both must give the oracle's lists and values."""
+    layers = [conv(3, 4, 3), pool()]
+    params = make_weights(layers, 17)
+    v = _video(256, W, sigma=0.003, n_objects=4, seed=300 + W, size_range=(6, 20))
+    frames = [v.frame(t) for t in range(3)]
+    stats = compare_sequence(layers, params, frames, 0.02, label="256x%d" % W)
+    assert 0 < stats[-1][0] < 256 * W // 4
+
+
+@pytest.mark.parametrize("hold", [False, True])
+def test_sparse_changes_far_apart(hold):
+    """A handful of single changed pixels spread over a map of many bitmap words: the wanted ranks
+    of a tile then lie in words that are far apart."""
+    layers = [conv(2, 5, 3, relu=False)]
+    params = make_weights(layers, 23)
+    r = np.random.default_rng(5)
+    base = r.random((2, 96, 200)).astype(np.float32)
+    frames = [base]
+    for t in range(1, 5):
+        f = frames[-1].copy()
+        for _ in range(t):      # t isolated pixels
+            y, x = int(r.integers(0, 96)), int(r.integers(0, 200))
+            f[:, y, x] += 0.5
+        frames.append(f)
+    stats = compare_sequence(layers, params, frames, 0.1, hold=hold, label="sparse")
+    assert [c for c, _ in stats[1:]] == [1, 2, 3, 4]
