@@ -378,6 +378,8 @@ struct LayerMaps {
     int upd_bytes;
     uint64_t *pool;  // pooled positions to recompute, nullptr without pooling
     bool identity;   // upd == chg: no dilation launch
+    bool in_gemm;    // the multiplication kernel dilates chg itself and writes upd: no dilation launch,
+                     // and the pooled bitmap is not filled in during the frame
 };
 
 LayerMaps layer_maps(const cbinfer_state *s, int l)
@@ -399,7 +401,29 @@ LayerMaps layer_maps(const cbinfer_state *s, int l)
     m.identity = op.kh == 1 && op.kw == 1 && op.stride == 1 && op.pad == 0 && !m.pool;
     m.upd = m.identity ? m.chg : s->at<uint64_t>(op.o_upd);
     m.upd_bytes = m.identity ? m.chg_bytes : 0;
+    // a propagating layer behind this layer's pooling reads the pooled bitmap during the frame
+    const bool pool_map_wanted = op.pool_after >= 0 && op.pool_after + 1 < (int)P.ops.size() &&
+                                 propagates(P, op.pool_after + 1, s->force_dense);
+    m.in_gemm = !m.identity && op.select && op.stride == 1 && op.kw <= 16 && !s->force_dense && !pool_map_wanted &&
+                words_for((long long)P.S * op.H * op.Wo) <= cbk::gemm_select_max_words();
     return m;
+}
+
+// Dilation launch for op l: change map -> map of outputs to recompute (+ pooled positions).
+hipError_t dilate_maps(const cbinfer_state *s, int l, const LayerMaps &m, const cbk::Timing &tm = cbk::Timing())
+{
+    const Plan &P = s->plan;
+    const Op &op = P.ops[l];
+    cbk::DilateGeom g;
+    g.S = P.S; g.H = op.H; g.W = op.W; g.Ho = op.Ho; g.Wo = op.Wo;
+    g.kh = op.kh; g.kw = op.kw; g.stride = op.stride; g.pad = op.pad;
+    g.pool_k = 0; g.Hp = 0; g.Wp = 0;
+    g.chg_bytes = m.chg_bytes;
+    if (op.pool_after >= 0) {
+        const Op &pp = P.ops[op.pool_after];
+        g.pool_k = pp.kh; g.Hp = pp.Ho; g.Wp = pp.Wo;
+    }
+    return cbk::dilate(s->stream, m.chg, m.upd, m.pool, g, tm);
 }
 
 // Change-index extraction for op l (and the pooling op behind it): maps -> ascending lists and counts.
@@ -469,25 +493,17 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             const int *ulist = iota;
             const int *ucount = consts + 2 * l;
             const uint64_t *sel_map = nullptr;
-            int sel_bytes = 0;
+            int sel_bytes = 0, sel_dilate = 0;
             if (!s->force_dense) {
                 const LayerMaps m = layer_maps(s, l);
-                if (!m.identity) {
-                    cbk::DilateGeom g;
-                    g.S = S; g.H = op.H; g.W = op.W; g.Ho = op.Ho; g.Wo = op.Wo;
-                    g.kh = op.kh; g.kw = op.kw; g.stride = op.stride; g.pad = op.pad;
-                    g.pool_k = 0; g.Hp = 0; g.Wp = 0;
-                    g.chg_bytes = m.chg_bytes;
-                    if (op.pool_after >= 0) {
-                        const Op &pp = P.ops[op.pool_after];
-                        g.pool_k = pp.kh; g.Hp = pp.Ho; g.Wp = pp.Wo;
-                    }
+                if (!m.identity && !m.in_gemm) {
                     StepTimer t(s, l, CBINFER_STEP_DILATE);
-                    HIP_TRY(cbk::dilate(st, m.chg, m.upd, m.pool, g, t.timing()));
+                    HIP_TRY(dilate_maps(s, l, m, t.timing()));
                 }
                 if (op.select) {
-                    sel_map = m.upd;
-                    sel_bytes = m.upd_bytes;
+                    sel_map = m.in_gemm ? m.chg : m.upd;
+                    sel_bytes = m.in_gemm ? m.chg_bytes : m.upd_bytes;
+                    sel_dilate = m.in_gemm ? 1 : 0;
                     ulist = nullptr;
                     ucount = nullptr;
                     s->lists_stale = true;
@@ -510,6 +526,10 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             a.sel_map = sel_map;
             a.sel_bytes = sel_bytes;
             a.sel_words = sel_map ? words_for((long long)S * No) : 0;
+            a.sel_dilate = sel_dilate;
+            a.sel_in_words = words_for((long long)S * N);
+            a.upd_out = s->at<uint64_t>(op.o_upd);
+            a.kh = op.kh; a.kw = op.kw; a.S = S;
             a.out = s->at<void>(op.o_out);
             a.N = N; a.H = op.H; a.W = op.W; a.No = No; a.Wo = op.Wo;
             a.stride = op.stride; a.pad = op.pad; a.V = op.Cs / eu; a.Kpad = op.Kpad;
@@ -545,10 +565,15 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                 next_tau = P.ops[l + 1].tau;
             }
             StepTimer t(s, l, CBINFER_STEP_POOL);
-            if (cv.select && !s->force_dense)
-                HIP_TRY(cbk::pool_masked(st, s->at<uint64_t>(cv.o_pool), S * Np, s->at<void>(cv.o_out),
-                                         s->at<void>(op.o_out), op.Ms / cbk::elems_per_unit(P.dtype), op.kh, cv.Wo,
-                                         cv.Ho * cv.Wo, op.Wo, Np, next_flags, next_tau, first ? 1 : 0, P.dtype, t.timing()));
+            if (cv.select && !s->force_dense) {
+                // the pooled bitmap, or (when the multiplication kernel derived the update map itself)
+                // the update bitmap of the convolution, tested window by window
+                const LayerMaps cm = layer_maps(s, op.conv_before);
+                HIP_TRY(cbk::pool_masked(st, cm.in_gemm ? cm.upd : cm.pool, cm.in_gemm ? 1 : 0, S * Np,
+                                         s->at<void>(cv.o_out), s->at<void>(op.o_out),
+                                         op.Ms / cbk::elems_per_unit(P.dtype), op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np,
+                                         next_flags, next_tau, first ? 1 : 0, P.dtype, t.timing()));
+            }
             else
                 HIP_TRY(cbk::pool_sparse(st, plist, pcount, S * Np, s->at<void>(cv.o_out), s->at<void>(op.o_out),
                                          op.Ms / cbk::elems_per_unit(P.dtype), op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np,
@@ -701,7 +726,11 @@ static int refresh_lists(cbinfer_state *s)
     if (!s->lists_stale) return CBINFER_OK;
     for (int l = 0; l < (int)s->plan.ops.size(); ++l) {
         const Op &op = s->plan.ops[l];
-        if (op.kind == CBINFER_OP_CONV && op.select) HIP_TRY(extract_lists(s, l, layer_maps(s, l)));
+        if (op.kind != CBINFER_OP_CONV || !op.select) continue;
+        const LayerMaps m = layer_maps(s, l);
+        // the frame skipped the dilation kernel: the pooled bitmap has not been filled in yet
+        if (m.in_gemm && m.pool) HIP_TRY(dilate_maps(s, l, m));
+        HIP_TRY(extract_lists(s, l, m));
     }
     s->lists_stale = false;
     return CBINFER_OK;

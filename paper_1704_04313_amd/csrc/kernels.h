@@ -158,6 +158,15 @@ struct GemmArgs {
     const uint64_t *sel_map;
     int sel_bytes;
     int sel_words;
+    // sel_dilate != 0 (stride 1, kw <= 16, change map and the S*H*Wo intermediate map of at most
+    // gemm_select_max_words() words each): sel_map is the layer's *change* map over its
+    // sel_in_words * 64 input positions, and the kernel derives the outputs to recompute itself
+    // by dilating it with the kh x kw filter support (Section 3.1, second formula); workgroup 0
+    // writes the resulting bitmap (sel_words words) to upd_out.
+    int sel_dilate;
+    int sel_in_words;
+    uint64_t *upd_out;
+    int kh, kw, S;      // filter size and number of streams (used by sel_dilate only)
     void *out;          // stored output map [S*No][Ms]
     int N, H, W, No, Wo, stride, pad;
     int V;              // units per input pixel
@@ -199,10 +208,12 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm = Tim
 hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int max_count, const void *in,
                        void *pooled, int V, int k, int Wo, int No, int Wp, int Np, unsigned char *next_flags,
                        float next_tau, int next_force, int dtype, const Timing &tm = Timing());
-// The same at the positions whose bit is set in a bitmap over the total pooled positions (no list).
-hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int total, const void *in, void *pooled, int V, int k,
-                       int Wo, int No, int Wp, int Np, unsigned char *next_flags, float next_tau, int next_force,
-                       int dtype, const Timing &tm = Timing());
+// The same at the positions whose bit is set in a bitmap over the total pooled positions (no list);
+// from_outputs != 0: the bitmap is over the convolution outputs instead, and a pooled position is
+// recomputed if any output in its k x k window is set.
+hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int from_outputs, int total, const void *in,
+                       void *pooled, int V, int k, int Wo, int No, int Wp, int Np, unsigned char *next_flags,
+                       float next_tau, int next_force, int dtype, const Timing &tm = Timing());
 
 // ---- stored map -> caller's planar output --------------------------------------------------
 hipError_t map_to_planar(hipStream_t st, const void *map, float *planar, int M, int V, int No, int S, int dtype,

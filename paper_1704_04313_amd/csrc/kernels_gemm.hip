@@ -102,26 +102,22 @@ struct Selection {
     int nwords;
 };
 
-// Loads the selection map into LDS (sW) and ranks it: sRank[i] = number of selected pixels in
-// the words before word i.  Returns the number of selected pixels.  All NT threads take part;
-// thread t ranks the kSelWordsPerThread consecutive words starting at kSelWordsPerThread * t.
-__device__ __forceinline__ int rank_selection(const GemmArgs &a, uint64_t *sW, int *sRank, int *sTot)
+// A map of nw words (64 positions each) from global memory into LDS as a bitmap.  bytes != 0: the
+// map has one byte per position and is packed on the way -- for eight of them in a 64-bit value x
+// the high bits of (x | (x & 0x7f..7f) + 0x7f..7f) mark the nonzero bytes and the multiplication
+// gathers the eight marks into one byte, which is byte i of the bitmap.  The caller synchronises.
+__device__ __forceinline__ void load_bitmap(const uint64_t *__restrict__ map, int bytes, int nw, uint64_t *sM)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nw = a.sel_words;
-    uint64_t w[kSelWordsPerThread];
-    if (a.sel_bytes) {
-        // One byte per pixel: eight pixels per 64-bit load.  The high bit of
-        // (x | (x & 0x7f..7f) + 0x7f..7f) marks the nonzero bytes and the multiplication gathers
-        // the eight marks into one byte, which is byte i of the bitmap in LDS.
-        unsigned char *sB = reinterpret_cast<unsigned char *>(sW);
+    const int tid = threadIdx.x;
+    if (bytes) {
+        unsigned char *sB = reinterpret_cast<unsigned char *>(sM);
         const int n8 = nw * 8;
         for (int i0 = 0; i0 < n8; i0 += 4 * NT) {
             uint64_t x[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int i = i0 + j * NT + tid;
-                x[j] = i < n8 ? a.sel_map[i] : 0ull;
+                x[j] = i < n8 ? map[i] : 0ull;
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -131,23 +127,145 @@ __device__ __forceinline__ int rank_selection(const GemmArgs &a, uint64_t *sW, i
                 if (i < n8) sB[i] = (unsigned char)((nz * 0x0102040810204080ull) >> 56);
             }
         }
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < kSelWordsPerThread; ++j) {
-            const int i = kSelWordsPerThread * tid + j;
-            w[j] = i < nw ? sW[i] : 0ull;
-        }
-#pragma unroll
-        for (int j = 0; j < kSelWordsPerThread; ++j) sW[kSelWordsPerThread * tid + j] = w[j]; // zero beyond the map
     } else {
+        for (int i0 = 0; i0 < nw; i0 += 4 * NT) {
+            uint64_t x[4];
 #pragma unroll
-        for (int j = 0; j < kSelWordsPerThread; ++j) {
-            const int i = kSelWordsPerThread * tid + j;
-            w[j] = i < nw ? a.sel_map[i] : 0ull;
+            for (int j = 0; j < 4; ++j) {
+                const int i = i0 + j * NT + tid;
+                x[j] = i < nw ? map[i] : 0ull;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = i0 + j * NT + tid;
+                if (i < nw) sM[i] = x[j];
+            }
         }
-#pragma unroll
-        for (int j = 0; j < kSelWordsPerThread; ++j) sW[kSelWordsPerThread * tid + j] = w[j];
     }
+}
+
+// Bits [a, a + len) of an LDS bitmap as the low bits of the result; 1 <= len <= 64, a >= 0, and
+// the word behind the last one read must exist (the maps are followed by a zero word).
+__device__ __forceinline__ uint64_t lds_bit_run(const uint64_t *m, int a, int len)
+{
+    const int w = a >> 6, o = a & 63;
+    uint64_t v = m[w] >> o;
+    if (o + len > 64) v |= m[w + 1] << (64 - o);
+    if (len < 64) v &= (1ull << len) - 1ull;
+    return v;
+}
+
+// Dilation by the filter support for a stride-1 layer (Section 3.1, second formula), in two
+// separable steps on bitmaps in LDS.  sC: change bitmap over the input positions
+// [(st*H + iy)*W + ix].  Step 1 writes sH over [(st*H + iy)*Wo + qx]: is any changed pixel in row
+// iy under the kw taps of output column qx.  Step 2 (dilated_word) ORs the kh rows of sH that an
+// output row reads.  All bitmaps are followed by a zero word.
+__device__ __forceinline__ uint64_t row_dilated_word(const GemmArgs &a, const uint64_t *sC, int v, int total)
+{
+    const int p0 = v * 64, p1 = p0 + 64 < total ? p0 + 64 : total;
+    uint64_t res = 0;
+    int pos = p0;
+    int row = pos / a.Wo, x = pos - row * a.Wo; // row = st*H + iy
+    while (pos < p1) {
+        const int len = a.Wo - x < p1 - pos ? a.Wo - x : p1 - pos;
+        // window of input columns xs .. xs + L - 1 of that row; output column x + t reads t .. t + kw - 1
+        const int xs = x - a.pad, L = len + a.kw - 1;
+        const int k0 = xs < 0 ? -xs : 0, k1 = L < a.W - xs ? L : a.W - xs;
+        uint64_t lo = 0, hi = 0;
+        if (k1 > k0) {
+            const int base = row * a.W + xs;
+            if (k0 < 64) lo = lds_bit_run(sC, base + k0, (k1 < 64 ? k1 : 64) - k0) << k0;
+            if (k1 > 64) {
+                const int s0 = k0 > 64 ? k0 : 64;
+                hi = lds_bit_run(sC, base + s0, k1 - s0) << (s0 - 64);
+            }
+        }
+        // OR of the kw shifted copies of the (up to 79-bit) window, by doubling
+        int cover = 1;
+        while (cover * 2 <= a.kw) {
+            lo |= (lo >> cover) | (hi << (64 - cover));
+            hi |= hi >> cover;
+            cover *= 2;
+        }
+        if (cover < a.kw) {
+            const int sft = a.kw - cover;
+            lo |= (lo >> sft) | (hi << (64 - sft));
+        }
+        if (len < 64) lo &= (1ull << len) - 1ull;
+        res |= lo << (pos - p0);
+        pos += len;
+        x = 0; // a segment ends at the end of its row or of the word
+        ++row;
+    }
+    return res;
+}
+
+__device__ __forceinline__ uint64_t dilated_word(const GemmArgs &a, const uint64_t *sH, int w, int total)
+{
+    const int p0 = w * 64, p1 = p0 + 64 < total ? p0 + 64 : total;
+    const int Ho = a.No / a.Wo;
+    uint64_t res = 0;
+    int pos = p0;
+    const int orow = pos / a.Wo;
+    int x = pos - orow * a.Wo, st = orow / Ho, qy = orow - st * Ho;
+    while (pos < p1) {
+        const int len = a.Wo - x < p1 - pos ? a.Wo - x : p1 - pos;
+        uint64_t r = 0;
+        for (int j = 0; j < a.kh; ++j) {
+            const int iy = qy - a.pad + j;
+            if ((unsigned)iy < (unsigned)a.H) r |= lds_bit_run(sH, (st * a.H + iy) * a.Wo + x, len);
+        }
+        res |= r << (pos - p0);
+        pos += len;
+        x = 0;
+        if (++qy == Ho) {
+            qy = 0;
+            ++st;
+        }
+    }
+    return res;
+}
+
+// Brings the map of positions to recompute into LDS (sW) and ranks it: sRank[i] = number of
+// selected positions in the words before word i.  Returns the number of selected positions.
+// The map is either given (bits or bytes) or, sel_dilate != 0, derived here from the layer's
+// change map by dilation (scratch: LDS that the tile ring will use later); workgroup 0 then also
+// writes it to a.upd_out for the kernels that follow.  All NT threads take part; thread t ranks
+// the kSelWordsPerThread consecutive words starting at kSelWordsPerThread * t.
+__device__ __forceinline__ int rank_selection(const GemmArgs &a, uint64_t *sW, int *sRank, int *sTot,
+                                              uint64_t *scratch)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nw = a.sel_words;
+    uint64_t w[kSelWordsPerThread];
+    if (a.sel_dilate) {
+        const int in_words = a.sel_in_words;
+        const int hd_total = a.S * a.H * a.Wo, hd_words = (hd_total + 63) >> 6;
+        uint64_t *sC = scratch, *sH = scratch + in_words + 2;
+        load_bitmap(a.sel_map, a.sel_bytes, in_words, sC);
+        if (tid < 2) sC[in_words + tid] = 0ull;
+        __syncthreads();
+        for (int v = tid; v < hd_words; v += NT) sH[v] = row_dilated_word(a, sC, v, hd_total);
+        if (tid < 2) sH[hd_words + tid] = 0ull;
+        __syncthreads();
+        const int out_total = a.S * a.No;
+        for (int i = tid; i < nw; i += NT) { // one word per thread and round: all lanes busy
+            const uint64_t d = dilated_word(a, sH, i, out_total);
+            sW[i] = d;
+            if (blockIdx.x == 0) a.upd_out[i] = d;
+        }
+    } else {
+        load_bitmap(a.sel_map, a.sel_bytes, nw, sW);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kSelWordsPerThread; ++j) {
+        const int i = kSelWordsPerThread * tid + j;
+        w[j] = i < nw ? sW[i] : 0ull;
+    }
+    __syncthreads(); // every thread has read its words before they are rewritten below
+#pragma unroll
+    for (int j = 0; j < kSelWordsPerThread; ++j) sW[kSelWordsPerThread * tid + j] = w[j]; // zero beyond the map
     int c[kSelWordsPerThread], sum = 0;
 #pragma unroll
     for (int j = 0; j < kSelWordsPerThread; ++j) {
@@ -722,7 +840,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         char *base = reinterpret_cast<char *>(smem) + TileSmem<BM, BNB>::sel_offset;
         uint64_t *sW = reinterpret_cast<uint64_t *>(base);
         int *sRank = reinterpret_cast<int *>(base + kSelMaxWords * 8);
-        n = rank_selection(a, sW, sRank, sRank + kSelMaxWords);
+        n = rank_selection(a, sW, sRank, sRank + kSelMaxWords, reinterpret_cast<uint64_t *>(smem));
         sel.words = sW;
         sel.rank = sRank;
         sel.nwords = a.sel_words;
@@ -817,6 +935,11 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm)
     const int eu = elems_per_unit(a.dtype);
     if (a.Mpad % bm != 0 || a.Kpad % gemm_k_multiple(a.dtype) != 0 || a.Ms % eu != 0 || a.V < 1 || !a.partial ||
         !a.tickets || a.grid < 8 || (a.grid & 7))
+        return hipErrorInvalidValue;
+    if (a.sel_words > 0 && a.sel_dilate &&
+        (a.stride != 1 || a.kw > 16 || a.kw < 1 || a.kh < 1 || !a.upd_out || a.S < 1 || a.sel_in_words < 1 ||
+         a.sel_in_words > kSelMaxWords || ((long long)a.S * a.H * a.Wo + 63) / 64 > kSelMaxWords ||
+         (long long)a.sel_in_words * 64 < (long long)a.S * a.N || a.No % a.Wo != 0))
         return hipErrorInvalidValue;
     if (a.sel_words < 0 || a.sel_words > kSelMaxWords || (a.sel_words > 0 && !a.sel_map) ||
         (a.sel_words == 0 && (!a.list || !a.count)) || (long long)a.sel_words * 64 < a.max_pixels * (a.sel_words > 0))

@@ -479,7 +479,8 @@ __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restri
 }
 
 template <int DT>
-__global__ __launch_bounds__(kBlock) void pool_masked_kernel(const uint64_t *__restrict__ bits, int total_px,
+__global__ __launch_bounds__(kBlock) void pool_masked_kernel(const uint64_t *__restrict__ bits, int from_outputs,
+                                                             int total_px,
                                                              const uint4 *__restrict__ in,
                                                              uint4 *__restrict__ pooled, int V, int k, int Wo,
                                                              int No, int Wp, int Np,
@@ -492,7 +493,20 @@ __global__ __launch_bounds__(kBlock) void pool_masked_kernel(const uint64_t *__r
         const long long idx = i0 + threadIdx.x;
         bool active = idx < total;
         const int g = active ? (int)(idx / V) : 0, v = active ? (int)(idx - (long long)g * V) : 0;
-        if (active) active = ((bits[g >> 6] >> (g & 63)) & 1ull) != 0ull;
+        if (active) {
+            if (from_outputs) {
+                const int st = g / Np, pp = g - st * Np;
+                const int py = pp / Wp, px = pp - py * Wp;
+                bool any = false;
+                for (int j = 0; j < k; ++j) {
+                    const long long q0 = (long long)st * No + (long long)(py * k + j) * Wo + px * k;
+                    for (int i = 0; i < k; ++i) any |= ((bits[(q0 + i) >> 6] >> ((q0 + i) & 63)) & 1ull) != 0ull;
+                }
+                active = any;
+            } else {
+                active = ((bits[g >> 6] >> (g & 63)) & 1ull) != 0ull;
+            }
+        }
         pool_unit<DT>(active, g, v, in, pooled, V, k, Wo, No, Wp, Np, next_flags, next_tau, next_force);
     }
 }
@@ -516,9 +530,9 @@ hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int ma
     return hipGetLastError();
 }
 
-hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int total, const void *in, void *pooled, int V, int k,
-                       int Wo, int No, int Wp, int Np, unsigned char *next_flags, float next_tau, int next_force,
-                       int dtype, const Timing &tm)
+hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int from_outputs, int total, const void *in,
+                       void *pooled, int V, int k, int Wo, int No, int Wp, int Np, unsigned char *next_flags,
+                       float next_tau, int next_force, int dtype, const Timing &tm)
 {
     long long work = (long long)total * V;
     long long grid = (work + kBlock - 1) / kBlock;
@@ -527,10 +541,10 @@ hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int total, const vo
     const uint4 *i4 = static_cast<const uint4 *>(in);
     uint4 *p4 = static_cast<uint4 *>(pooled);
     if (dtype == kBF16)
-        launch_kernel(tm, pool_masked_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, bits, total, i4, p4, V, k,
+        launch_kernel(tm, pool_masked_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, bits, from_outputs, total, i4, p4, V, k,
                            Wo, No, Wp, Np, next_flags, next_tau, next_force);
     else
-        launch_kernel(tm, pool_masked_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, bits, total, i4, p4, V, k,
+        launch_kernel(tm, pool_masked_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, bits, from_outputs, total, i4, p4, V, k,
                            Wo, No, Wp, Np, next_flags, next_tau, next_force);
     return hipGetLastError();
 }
