@@ -3,22 +3,28 @@
 // Section 3.1 of the paper assembles only the columns of the image matrix X that belong to
 // output positions needing an update, multiplies them with the unchanged filter matrix K and
 // writes the result (with the activation) over the stored output.  Here the three steps are one
-// kernel: a workgroup owns BN listed output positions x BM output channels, builds the BN x 32
-// slices of the reduced X directly in LDS by gathering 16-byte channel groups from the
-// channel-contiguous input map, multiplies on the matrix cores and scatters bias + ReLU results
-// straight into the stored map.  The reduced X never exists in HBM.
+// kernel: a workgroup owns BN output positions to recompute x BM output channels, builds the
+// BN x 128-byte slices of the reduced X directly in LDS by gathering 16-byte channel units from
+// the channel-contiguous input map, multiplies on the matrix cores and scatters bias + ReLU
+// results straight into the stored map.  The reduced X never exists in HBM.
+//
+// Which positions: from an index list, or -- for maps small enough to be held in LDS -- from the
+// map itself.  Every workgroup then loads the map of positions to recompute (or the layer's
+// change map, which it first dilates by the filter support), ranks it with popcounts and a scan,
+// and picks the positions whose rank falls into its tile: the index extraction and the dilation
+// of Section 3.1 without launches of their own.
 //
 // The workgroup has eight waves with two roles.  Waves 4-7 ("producers") compute gather
-// addresses, load the next K slice of both operands from global memory and store it to LDS;
-// waves 0-3 ("consumers") only read LDS fragments and issue v_mfma_f32_16x16x4_f32 (fp32 in,
-// fp32 accumulate).  One producer and one consumer wave share each SIMD, so address
-// arithmetic, global-load latency and LDS stores overlap the matrix pipeline instead of
-// draining it once per slice.
+// addresses, load the next K slices of both operands from global memory and store them to LDS;
+// waves 0-3 ("consumers") only read LDS fragments and issue MFMAs (v_mfma_f32_16x16x4_f32 for
+// float32 storage, v_mfma_f32_16x16x32_bf16 for bfloat16; float32 accumulation either way).  One
+// producer and one consumer wave share each SIMD, so address arithmetic, global-load latency and
+// LDS stores overlap the matrix pipeline instead of draining it once per slice.
 //
 // Work distribution: one workgroup per compute unit.  Output tiles are dealt out whole as long
 // as every workgroup gets one; the (tiles mod workgroups) left over are cut along K into
 // equal iteration ranges, one per workgroup, so that all compute units finish together whatever
-// the list length is.  A workgroup that computed only part of a tile's K range stores its
+// the number of positions is.  A workgroup that computed only part of a tile's K range stores its
 // partial accumulators; the last workgroup to finish a tile (an atomic ticket, nobody waits)
 // adds all parts in ascending K order, which keeps results deterministic, and performs the
 // output update.
