@@ -14,12 +14,14 @@
 // and picks the positions whose rank falls into its tile: the index extraction and the dilation
 // of Section 3.1 without launches of their own.
 //
-// The workgroup has eight waves with two roles.  Waves 4-7 ("producers") compute gather
+// The workgroup has twelve waves with two roles.  The last four ("producers") compute gather
 // addresses, load the next K slices of both operands from global memory and store them to LDS;
-// waves 0-3 ("consumers") only read LDS fragments and issue MFMAs (v_mfma_f32_16x16x4_f32 for
-// float32 storage, v_mfma_f32_16x16x32_bf16 for bfloat16; float32 accumulation either way).  One
-// producer and one consumer wave share each SIMD, so address arithmetic, global-load latency and
-// LDS stores overlap the matrix pipeline instead of draining it once per slice.
+// the first eight ("consumers") only read LDS fragments and issue MFMAs (v_mfma_f32_16x16x4_f32
+// for float32 storage, v_mfma_f32_16x16x32_bf16 for bfloat16; float32 accumulation either way).
+// One producer and two consumer waves share each SIMD, so address arithmetic, global-load latency
+// and LDS stores overlap the matrix pipeline instead of draining it once per slice, and while one
+// consumer wave waits for its fragments the other keeps the pipeline fed (measured +2.5 % over
+// one consumer wave per SIMD).
 //
 // Work distribution: one workgroup per compute unit.  Output tiles are dealt out whole as long
 // as every workgroup gets one; the (tiles mod workgroups) left over are cut along K into
@@ -52,13 +54,13 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const float *p, 
 // timing study builds only: lane 0 of wave 0 (consumer) and of wave 4 (producer) stamp events
 #define CBK_STAMP(slot)                                                                         \
     do {                                                                                        \
-        if (lane == 0 && (wave == 0 || wave == 4) && (slot) < 16)                               \
-            a.trace[((size_t)blockIdx.x * 2 + (wave >> 2)) * 16 + (slot)] = wall_clock64();      \
+        if (lane == 0 && (wave == 0 || wave == kConsWaves) && (slot) < 16)                               \
+            a.trace[((size_t)blockIdx.x * 2 + (wave != 0)) * 16 + (slot)] = wall_clock64();      \
     } while (0)
 #define CBK_CYCLES(slot)                                                                        \
     do {                                                                                        \
-        if (lane == 0 && (wave == 0 || wave == 4) && seg == 0)                                  \
-            a.trace[((size_t)blockIdx.x * 2 + (wave >> 2)) * 16 + (slot)] = clock64();          \
+        if (lane == 0 && (wave == 0 || wave == kConsWaves) && seg == 0)                                  \
+            a.trace[((size_t)blockIdx.x * 2 + (wave != 0)) * 16 + (slot)] = clock64();          \
     } while (0)
 #else
 #define CBK_STAMP(slot) do { } while (0)
@@ -74,9 +76,13 @@ static constexpr int LDK = BK;      // LDS row pitch in 4-byte words: 128 bytes,
                                     // u ^ lds_swizzle(r)) so that the 16-lane groups of a ds_read_b128
                                     // (16 rows, one or two neighbouring units) and of a ds_write_b128 (two rows,
                                     // all units) each cover all 64 banks once
-static constexpr int NT = 512;      // threads per workgroup: 4 consumer + 4 producer waves
-static constexpr int NPROD = 256;   // producer threads
-static constexpr int NCONS = 256;   // consumer threads
+#ifndef CBK_CONS_WAVES
+#define CBK_CONS_WAVES 8
+#endif
+static constexpr int kConsWaves = CBK_CONS_WAVES; // consumer waves per workgroup (one or two per SIMD)
+static constexpr int NPROD = 256;                 // producer threads (one wave per SIMD)
+static constexpr int NCONS = 64 * kConsWaves;     // consumer threads: waves 0 .. kConsWaves-1
+static constexpr int NT = NCONS + NPROD;          // threads per workgroup
 static constexpr int kStages = 3;   // K slices resident in LDS
 #ifndef CBK_MIN_ITERS
 #define CBK_MIN_ITERS 8
@@ -88,8 +94,9 @@ static constexpr int kMinIters = CBK_MIN_ITERS; // shortest K range worth giving
 static constexpr int kMaxGrid = 1024;
 static constexpr int kSmallTileFactor = CBK_SMALL_FACTOR; // big tiles are used from (workgroups / this) big tiles on
 
-static constexpr int kSelWordsPerThread = 4;
-static constexpr int kSelMaxWords = kSelWordsPerThread * NT; // largest selection map ranked in-kernel (131072 pixels)
+static constexpr int kSelMaxWords = 2048; // largest selection map ranked in-kernel (131072 pixels)
+static constexpr int kSelWordsPerThread = (kSelMaxWords + NT - 1) / NT;
+static constexpr int kSelSlots = kSelWordsPerThread * NT; // LDS words per ranking array (>= kSelMaxWords)
 
 template <int BM, int BN>
 struct TileSmem {
@@ -98,7 +105,7 @@ struct TileSmem {
     static constexpr int tile_bytes = kStages * (a_floats + b_floats) * 4 + BN * 4 + 16; // + list, ticket, range
     // behind the tile: the selection map's words, their exclusive ranks, and the wave totals of the scan
     static constexpr int sel_offset = (tile_bytes + 15) / 16 * 16;
-    static constexpr int bytes = sel_offset + kSelMaxWords * 12 + 64;
+    static constexpr int bytes = sel_offset + kSelSlots * 12 + 64;
 };
 
 // Selection-map mode: the words of the map and the rank of each word's first set bit, in LDS.
@@ -435,7 +442,7 @@ __device__ __forceinline__ void stage_rows(float *A, float *B, int r0, int v, co
 template <int DT, int BM, int BN, int WM, int WN>
 __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n, float *smem, const Selection sel)
 {
-    static_assert(WM * WN == 4, "four consumer waves");
+    static_assert(WM * WN == kConsWaves, "one sub-tile per consumer wave");
     constexpr int TP = BN / WN / 16; // 16-pixel MFMA tiles per consumer wave
     constexpr int TC = BM / WM / 16; // 16-channel MFMA tiles per consumer wave
     constexpr int PA = BN / 32;      // image-matrix rows staged per producer thread and slice
@@ -454,7 +461,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const bool producer = wave >= 4;
+    const bool producer = wave >= kConsWaves;
 
     const int mtiles = a.Mpad / BM;
     const int krow = a.Kpad / Unit<DT>::N; // units per filter-matrix row
@@ -513,7 +520,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
         __syncthreads();
 
         // consumer coordinates (used again after the role-specific loops)
-        const int cw = wave & 3;
+        const int cw = producer ? 0 : wave;
         const int wpx0 = (cw % WN) * (BN / WN);
         const int wch0 = (cw / WN) * (BM / WM);
         const int lrow = lane & 15; // row of the 16-row operand tiles this lane feeds
@@ -526,7 +533,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
 
         // Both roles execute the same number of barriers: one after the prologue, one per slice.
         if (producer) {
-            const int ptid = tid & (NPROD - 1);
+            const int ptid = tid - NCONS;
             const int v = ptid & 7;   // 16-byte unit column inside the K slice
             const int r0 = ptid >> 3; // first row this thread stages
             const int vs = v ^ lds_swizzle(r0); // slot of that unit in those rows
@@ -677,7 +684,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             const long long t0 = (long long)shared_j * nk;
             const int w_first = share_owner(sch, t0);
             const int w_last = share_owner(sch, t0 + nk - 1);
-            const int ctid = tid & (NCONS - 1);
+            const int ctid = producer ? 0 : tid;
             if (!producer) {
                 // slab 2*wsh + (0: first tile this workgroup touches, 1: a later one), register layout:
                 // one float4 per lane and accumulator, consecutive lanes consecutive addresses
@@ -833,7 +840,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
 // split of the big tiles would leave compute units idle (short lists): small tiles then need no
 // or fewer shared tiles, whose partial sums and reduction are pure overhead.
 template <int DT, int BM, int BNB, int WMB, int WNB, int BNS, int WMS, int WNS>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_gather_kernel(GemmArgs a)
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT / 256, NT / 256))) void gemm_gather_kernel(GemmArgs a)
 {
     extern __shared__ __align__(16) float smem[];
 #ifdef CBK_TRACE
@@ -845,8 +852,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     if (a.sel_words > 0) {
         char *base = reinterpret_cast<char *>(smem) + TileSmem<BM, BNB>::sel_offset;
         uint64_t *sW = reinterpret_cast<uint64_t *>(base);
-        int *sRank = reinterpret_cast<int *>(base + kSelMaxWords * 8);
-        n = rank_selection(a, sW, sRank, sRank + kSelMaxWords, reinterpret_cast<uint64_t *>(smem));
+        int *sRank = reinterpret_cast<int *>(base + kSelSlots * 8);
+        n = rank_selection(a, sW, sRank, sRank + kSelSlots, reinterpret_cast<uint64_t *>(smem));
         sel.words = sW;
         sel.rank = sRank;
         sel.nwords = a.sel_words;
@@ -903,7 +910,11 @@ int gemm_grid(const GemmArgs &a, int compute_units)
 }
 
 // BM, big tile (BN, WM, WN), small tile (BN, WM, WN)
+#if CBK_CONS_WAVES == 8
+#define CBK_VARIANTS(X) X(16, 256, 1, 8, 128, 1, 8) X(32, 256, 1, 8, 64, 2, 4) X(64, 256, 2, 4, 64, 2, 4) X(128, 128, 2, 4, 64, 4, 2)
+#else
 #define CBK_VARIANTS(X) X(16, 256, 1, 4, 64, 1, 4) X(32, 256, 1, 4, 64, 1, 4) X(64, 256, 1, 4, 64, 1, 4) X(128, 128, 2, 2, 64, 2, 2)
+#endif
 
 hipError_t gemm_prepare(void)
 {
@@ -950,12 +961,11 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm)
     if (a.sel_words < 0 || a.sel_words > kSelMaxWords || (a.sel_words > 0 && !a.sel_map) ||
         (a.sel_words == 0 && (!a.list || !a.count)) || (long long)a.sel_words * 64 < a.max_pixels * (a.sel_words > 0))
         return hipErrorInvalidValue;
-    switch (bm) {
-    case 16: return launch<16, 256, 1, 4, 64, 1, 4>(st, a, tm);
-    case 32: return launch<32, 256, 1, 4, 64, 1, 4>(st, a, tm);
-    case 64: return launch<64, 256, 1, 4, 64, 1, 4>(st, a, tm);
-    default: return launch<128, 128, 2, 2, 64, 2, 2>(st, a, tm);
-    }
+#define X(BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_) \
+    if (bm == BM_) return launch<BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_>(st, a, tm);
+    CBK_VARIANTS(X)
+#undef X
+    return hipErrorInvalidValue;
 }
 
 } // namespace cbk
