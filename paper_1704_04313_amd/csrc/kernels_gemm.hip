@@ -80,7 +80,11 @@ static constexpr int LDK = BK;      // LDS row pitch in 4-byte words: 128 bytes,
 #define CBK_CONS_WAVES 8
 #endif
 static constexpr int kConsWaves = CBK_CONS_WAVES; // consumer waves per workgroup (one or two per SIMD)
-static constexpr int NPROD = 256;                 // producer threads (one wave per SIMD)
+#ifndef CBK_PROD_WAVES
+#define CBK_PROD_WAVES 4
+#endif
+static constexpr int NPROD = 64 * CBK_PROD_WAVES; // producer threads (one or two waves per SIMD)
+static constexpr int kRP = NPROD / 8;             // tile rows staged per pass: eight threads (units) per row
 static constexpr int NCONS = 64 * kConsWaves;     // consumer threads: waves 0 .. kConsWaves-1
 static constexpr int NT = NCONS + NPROD;          // threads per workgroup
 static constexpr int kStages = 3;   // K slices resident in LDS
@@ -407,9 +411,9 @@ __device__ __forceinline__ void gather_rows(const GemmArgs &a, const int2 tp, co
 template <int BM, int PB>
 __device__ __forceinline__ void load_filter_rows(const floatx4 *wrow, int krow, int kc, int r0, floatx4 (&rb)[PB])
 {
-    if constexpr (BM >= 32) {
+    if constexpr (BM >= kRP) {
 #pragma unroll
-        for (int ps = 0; ps < PB; ++ps) rb[ps] = wrow[(size_t)(32 * ps) * krow + kc * KU];
+        for (int ps = 0; ps < PB; ++ps) rb[ps] = wrow[(size_t)(kRP * ps) * krow + kc * KU];
     } else {
         if (r0 < BM) rb[0] = wrow[kc * KU];
     }
@@ -424,10 +428,10 @@ __device__ __forceinline__ void stage_rows(float *A, float *B, int r0, int v, co
                                            const floatx4 (&rb)[PB])
 {
 #pragma unroll
-    for (int ps = 0; ps < PA; ++ps) *reinterpret_cast<floatx4 *>(A + (r0 + 32 * ps) * LDK + v * 4) = ra[ps];
-    if constexpr (BM >= 32) {
+    for (int ps = 0; ps < PA; ++ps) *reinterpret_cast<floatx4 *>(A + (r0 + kRP * ps) * LDK + v * 4) = ra[ps];
+    if constexpr (BM >= kRP) {
 #pragma unroll
-        for (int ps = 0; ps < PB; ++ps) *reinterpret_cast<floatx4 *>(B + (r0 + 32 * ps) * LDK + v * 4) = rb[ps];
+        for (int ps = 0; ps < PB; ++ps) *reinterpret_cast<floatx4 *>(B + (r0 + kRP * ps) * LDK + v * 4) = rb[ps];
     } else {
         if (r0 < BM) *reinterpret_cast<floatx4 *>(B + r0 * LDK + v * 4) = rb[0];
     }
@@ -445,8 +449,9 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
     static_assert(WM * WN == kConsWaves, "one sub-tile per consumer wave");
     constexpr int TP = BN / WN / 16; // 16-pixel MFMA tiles per consumer wave
     constexpr int TC = BM / WM / 16; // 16-channel MFMA tiles per consumer wave
-    constexpr int PA = BN / 32;      // image-matrix rows staged per producer thread and slice
-    constexpr int PB = (BM + 31) / 32;
+    constexpr int PA = BN / kRP;     // image-matrix rows staged per producer thread and slice
+    constexpr int PB = (BM + kRP - 1) / kRP;
+    static_assert(BN % kRP == 0, "whole passes over the pixel rows");
     constexpr int ASZ = BN * LDK, BSZ = BM * LDK;
     constexpr int SLAB = BM * BN; // floats of one partial-accumulator slab
     static_assert(TP >= 1 && TC >= 1, "tile too small");
@@ -540,7 +545,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             int iy0[PA], ix0[PA], base[PA];
 #pragma unroll
             for (int ps = 0; ps < PA; ++ps) {
-                const int g = sU[r0 + 32 * ps];
+                const int g = sU[r0 + kRP * ps];
                 if (g >= 0) {
                     const int st = g / a.No, q = g - st * a.No;
                     const int qy = q / a.Wo, qx = q - qy * a.Wo;
@@ -840,7 +845,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
 // split of the big tiles would leave compute units idle (short lists): small tiles then need no
 // or fewer shared tiles, whose partial sums and reduction are pure overhead.
 template <int DT, int BM, int BNB, int WMB, int WNB, int BNS, int WMS, int WNS>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT / 256, NT / 256))) void gemm_gather_kernel(GemmArgs a)
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT + 255) / 256, (NT + 255) / 256))) void gemm_gather_kernel(GemmArgs a)
 {
     extern __shared__ __align__(16) float smem[];
 #ifdef CBK_TRACE
