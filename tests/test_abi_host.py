@@ -116,3 +116,26 @@ def test_negative_global_threshold_needs_per_layer_values():
     net, keep = _net_for(layers, make_weights(layers, 0), (3, 8, 8))
     assert not lib.cbinfer_create(C.byref(net), C.c_float(float("nan")))
     assert b"threshold" in lib.cbinfer_last_error()
+
+
+def test_oversize_maps_are_refused_not_truncated():
+    """Pixel indices and element offsets are 32-bit inside the kernels: a map beyond 2^31 - 1
+    elements must be refused when the network is described, whatever the device could hold."""
+    lib = cb.load_library()
+    layers = [conv(3, 8, 3)]
+    net, keep = _net_for(layers, make_weights(layers, 0), (3, 40000, 40000))
+    assert lib.cbinfer_workspace_bytes(C.byref(net)) == 0
+    assert "2^31-1" in lib.cbinfer_last_error().decode()
+    # many streams of an ordinary frame overflow the same limit
+    net, keep = _net_for(layers, make_weights(layers, 0), (3, 1080, 1920), n_streams=400)
+    assert lib.cbinfer_workspace_bytes(C.byref(net)) == 0
+
+
+def test_workspace_grows_with_streams_and_shrinks_with_bfloat16():
+    layers = [conv(3, 16, 7), pool(), conv(16, 32, 3)]
+    params = make_weights(layers, 1)
+    one = cb.cbinfer_workspace_bytes(layers, params, (3, 240, 320))
+    four = cb.cbinfer_workspace_bytes(layers, params, (3, 240, 320), n_streams=4)
+    half = cb.cbinfer_workspace_bytes(layers, params, (3, 240, 320), dtype=cb.BF16)
+    assert four > 2 * one > 0
+    assert half < one
