@@ -160,6 +160,8 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
             op.K = L.kh * L.kw * op.Cs;
             op.Kpad = round_up(op.K, cbk::gemm_k_multiple(P.dtype));
             op.Mpad = round_up(op.M, cbk::gemm_channel_tile(op.M));
+            if (op.Kpad / cbk::gemm_k_multiple(P.dtype) >= (1 << 20))
+                return fail(CBINFER_EUNSUPPORTED, "layer %d: more than 2^20 slices of 128 bytes per filter-matrix row", l);
             c = op.M;
         } else if (L.kind == CBINFER_OP_MAXPOOL) {
             if (L.kh != L.kw || L.kh < 1) return fail(CBINFER_EINVAL, "layer %d: pooling window must be square", l);
@@ -549,6 +551,7 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
 #ifdef CBK_TRACE
             a.trace = cbk_trace_buffer();
 #endif
+            cbk::gemm_set_divisors(a);
             {
                 StepTimer t(s, l, CBINFER_STEP_GEMM);
                 HIP_TRY(cbk::gemm_gather(st, a, t.timing()));

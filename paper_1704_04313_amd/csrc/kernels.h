@@ -140,6 +140,30 @@ bool compact_two_level(int nwords);
 size_t compact_group_count_bytes(int nwords);
 hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, const Timing &tm = Timing());
 
+// Division of a non-negative 32-bit number by an invariant divisor through one 64-bit
+// multiplication (integer division is emulated with dozens of instructions on this hardware).
+// Exact for 0 <= n < 2^31 and 1 <= d < 2^31: with l = ceil(log2 d) and m = floor(2^(31+l) / d) + 1,
+// m*d - 2^(31+l) lies in (0, d], which keeps floor(n*m / 2^(31+l)) equal to floor(n / d).
+struct FastDiv {
+    unsigned m;
+    int shift;
+    int d;
+};
+inline FastDiv make_fastdiv(int d)
+{
+    int l = 0;
+    while ((1ll << l) < d) ++l;
+    FastDiv f;
+    f.d = d;
+    f.shift = 31 + l;
+    f.m = (unsigned)(((1ull << (31 + l)) / (unsigned long long)d) + 1ull);
+    return f;
+}
+__host__ __device__ inline int fast_div(int n, const FastDiv &f)
+{
+    return (int)(((unsigned long long)(unsigned)n * f.m) >> f.shift);
+}
+
 // ---- gathered matrix generation + multiplication + output update (Section 3.1) -------------
 struct GemmArgs {
     int dtype;          // kF32 or kBF16: storage of x, wt and out
@@ -169,6 +193,7 @@ struct GemmArgs {
     int kh, kw, S;      // filter size and number of streams (used by sel_dilate only)
     void *out;          // stored output map [S*No][Ms]
     int N, H, W, No, Wo, stride, pad;
+    FastDiv dNo, dWo, dHo, dNk, dGrid; // by No, Wo, No / Wo, Kpad / gemm_k_multiple(dtype) and grid (gemm_set_divisors)
     int V;              // units per input pixel
     int zero_unit;      // index of a 16-byte unit of zeros relative to x (gathers outside the image read it)
     int Kpad;           // filter-matrix row length in elements, a multiple of gemm_k_multiple(dtype)
@@ -197,6 +222,7 @@ int gemm_select_max_words(void);
 size_t gemm_partial_bytes(int M, int grid);
 size_t gemm_ticket_bytes(int grid);
 hipError_t gemm_prepare(void);  // one-time function attributes (dynamic LDS size)
+void gemm_set_divisors(GemmArgs &a); // fills dNo ... dGrid from No, Wo, Kpad, dtype and grid
 // Matrix generation, multiplication and output update (bias, activation, scatter) in one launch.
 hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm = Timing());
 

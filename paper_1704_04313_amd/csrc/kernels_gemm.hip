@@ -182,7 +182,7 @@ __device__ __forceinline__ uint64_t row_dilated_word(const GemmArgs &a, const ui
     const int p0 = v * 64, p1 = p0 + 64 < total ? p0 + 64 : total;
     uint64_t res = 0;
     int pos = p0;
-    int row = pos / a.Wo, x = pos - row * a.Wo; // row = st*H + iy
+    int row = fast_div(pos, a.dWo), x = pos - row * a.Wo; // row = st*H + iy
     while (pos < p1) {
         const int len = a.Wo - x < p1 - pos ? a.Wo - x : p1 - pos;
         // window of input columns xs .. xs + L - 1 of that row; output column x + t reads t .. t + kw - 1
@@ -220,11 +220,11 @@ __device__ __forceinline__ uint64_t row_dilated_word(const GemmArgs &a, const ui
 __device__ __forceinline__ uint64_t dilated_word(const GemmArgs &a, const uint64_t *sH, int w, int total)
 {
     const int p0 = w * 64, p1 = p0 + 64 < total ? p0 + 64 : total;
-    const int Ho = a.No / a.Wo;
+    const int Ho = a.dHo.d;
     uint64_t res = 0;
     int pos = p0;
-    const int orow = pos / a.Wo;
-    int x = pos - orow * a.Wo, st = orow / Ho, qy = orow - st * Ho;
+    const int orow = fast_div(pos, a.dWo);
+    int x = pos - orow * a.Wo, st = fast_div(orow, a.dHo), qy = orow - st * Ho;
     while (pos < p1) {
         const int len = a.Wo - x < p1 - pos ? a.Wo - x : p1 - pos;
         uint64_t r = 0;
@@ -343,22 +343,26 @@ __device__ __forceinline__ void select_tile(const Selection &sel, int n, int r0,
     }
 }
 
-// The split of one launch's work over W workgroups; a pure function of its arguments.
+// The split of one launch's work over W workgroups; a pure function of its arguments.  32-bit
+// arithmetic: W <= 1024 and the host refuses filter matrices of 2^20 slices or more, so
+// rem * nk stays below 2^30.
 struct Schedule {
-    int tiles;       // output tiles: pixel tiles x channel tiles (channel tile fastest)
-    int whole;       // rounds in which every workgroup takes one whole tile
-    int rem;         // tiles left over, shared along K
-    int wr;          // workgroups sharing the left-over tiles
-    long long iters; // rem * nk: K-slice iterations of the left-over tiles
+    int tiles; // output tiles: pixel tiles x channel tiles (channel tile fastest)
+    int whole; // rounds in which every workgroup takes one whole tile
+    int rem;   // tiles left over, shared along K
+    int wr;    // workgroups sharing the left-over tiles
+    int iters; // rem * nk: K-slice iterations of the left-over tiles
+    int q, r;  // iters = q * wr + r
 };
 
-__device__ __forceinline__ Schedule make_schedule(int n, int bn, int mtiles, int nk, int W)
+__device__ __forceinline__ Schedule make_schedule(int n, int bn, int mtiles, int nk, const FastDiv &dW)
 {
+    const int W = dW.d;
     Schedule s;
     s.tiles = ((n + bn - 1) / bn) * mtiles;
-    s.whole = s.tiles / W;
+    s.whole = fast_div(s.tiles, dW);
     s.rem = s.tiles - s.whole * W;
-    s.iters = (long long)s.rem * nk;
+    s.iters = s.rem * nk;
     // Cut every left-over tile into the same number of parts if that occupies at least 7/8 of
     // the workgroups (ranges then start on tile boundaries: one segment per workgroup); otherwise
     // deal the iterations out evenly over all workgroups.  Never make parts shorter than
@@ -370,19 +374,24 @@ __device__ __forceinline__ Schedule make_schedule(int n, int bn, int mtiles, int
         if (p > max_parts) p = max_parts;
         if (p < 1) p = 1;
         wr = s.rem * p;
-        if (wr * 8 < W * 7 && (long long)s.rem * max_parts >= W) wr = W;
+        if (wr * 8 < W * 7 && s.rem * max_parts >= W) wr = W;
         if (wr > W) wr = W;
     }
     s.wr = wr;
+    s.q = s.iters / wr;
+    s.r = s.iters - s.q * wr;
     return s;
 }
 
-// First iteration of workgroup w's share, and the workgroup owning an iteration.
-__device__ __forceinline__ long long share_begin(const Schedule &s, int w) { return s.iters * w / s.wr; }
+// First iteration of workgroup w's share: floor(iters * w / wr), and the workgroup owning an iteration.
+__device__ __forceinline__ int share_begin(const Schedule &s, int w) { return s.q * w + s.r * w / s.wr; }
 
-__device__ __forceinline__ int share_owner(const Schedule &s, long long it)
+__device__ __forceinline__ int share_owner(const Schedule &s, int it)
 {
-    int w = (int)(it * s.wr / s.iters);
+    // estimate in float (off by one at most for these magnitudes), then settle exactly
+    int w = (int)((float)it * (float)s.wr / (float)s.iters);
+    if (w > s.wr - 1) w = s.wr - 1;
+    if (w < 0) w = 0;
     while (w + 1 < s.wr && share_begin(s, w + 1) <= it) ++w;
     while (w > 0 && share_begin(s, w) > it) --w;
     return w;
@@ -472,7 +481,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
     const int krow = a.Kpad / Unit<DT>::N; // units per filter-matrix row
     const int nk = krow / KU;
     const int W = gridDim.x;
-    const Schedule sch = make_schedule(n, BN, mtiles, nk, W);
+    const Schedule sch = make_schedule(n, BN, mtiles, nk, a.dGrid);
     if (sch.tiles == 0) return;
     // Workgroups are dealt round-robin over the 8 XCDs.  Number them so that each XCD works on a
     // contiguous range of tiles / iterations: neighbours share gathered pixels (channel tiles of
@@ -483,11 +492,11 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                                : (int)blockIdx.x; // number inside the K-sharing group
     const bool sharing =
         sch.rem > 0 && (xcd_ranges ? (int)(blockIdx.x >> 3) < (sch.wr >> 3) : (int)blockIdx.x < sch.wr);
-    const long long it_begin = sharing ? share_begin(sch, wsh) : 0;
-    const long long it_end = sharing ? share_begin(sch, wsh + 1) : 0;
+    const int it_begin = sharing ? share_begin(sch, wsh) : 0;
+    const int it_end = sharing ? share_begin(sch, wsh + 1) : 0;
 
     int round = 0;
-    long long it = it_begin;
+    int it = it_begin;
     [[maybe_unused]] int seg = 0; // numbers the time stamps of timing-study builds
     CBK_STAMP(1);
     while (true) {
@@ -499,10 +508,10 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             kc1 = nk;
             ++round;
         } else if (it < it_end) {
-            shared_j = (int)(it / nk);
-            kc0 = (int)(it - (long long)shared_j * nk);
-            const long long left = it_end - it;
-            kc1 = (left < nk - kc0) ? kc0 + (int)left : nk;
+            shared_j = fast_div(it, a.dNk);
+            kc0 = it - shared_j * nk;
+            const int left = it_end - it;
+            kc1 = (left < nk - kc0) ? kc0 + left : nk;
             tile = sch.whole * W + shared_j;
             it += kc1 - kc0;
         } else {
@@ -547,8 +556,8 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             for (int ps = 0; ps < PA; ++ps) {
                 const int g = sU[r0 + kRP * ps];
                 if (g >= 0) {
-                    const int st = g / a.No, q = g - st * a.No;
-                    const int qy = q / a.Wo, qx = q - qy * a.Wo;
+                    const int st = fast_div(g, a.dNo), q = g - st * a.No;
+                    const int qy = fast_div(q, a.dWo), qx = q - qy * a.Wo;
                     iy0[ps] = qy * a.stride - a.pad;
                     ix0[ps] = qx * a.stride - a.pad;
                     base[ps] = ((st * a.H + iy0[ps]) * a.W + ix0[ps]) * a.V;
@@ -686,14 +695,14 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
         CBK_STAMP(4 + 6 * seg);
         bool finish = true;
         if (partial) {
-            const long long t0 = (long long)shared_j * nk;
+            const int t0 = shared_j * nk;
             const int w_first = share_owner(sch, t0);
             const int w_last = share_owner(sch, t0 + nk - 1);
             const int ctid = producer ? 0 : tid;
             if (!producer) {
                 // slab 2*wsh + (0: first tile this workgroup touches, 1: a later one), register layout:
                 // one float4 per lane and accumulator, consecutive lanes consecutive addresses
-                const int first_j = (int)(it_begin / nk);
+                const int first_j = fast_div(it_begin, a.dNk);
                 const __amdgpu_buffer_rsrc_t slab = slab_resource(
                     a.partial + (size_t)(2 * wsh + (shared_j == first_j ? 0 : 1)) * SLAB, SLAB * 4);
 #pragma unroll
@@ -721,7 +730,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
 #pragma unroll
                         for (int i = 0; i < TP; ++i) acc[j][i] = (floatx4){0.f, 0.f, 0.f, 0.f};
                     for (int ww = w_first; ww <= w_last; ++ww) {
-                        const int fj = (int)(share_begin(sch, ww) / nk);
+                        const int fj = fast_div(share_begin(sch, ww), a.dNk);
                         const __amdgpu_buffer_rsrc_t slab = slab_resource(
                             a.partial + (size_t)(2 * ww + (shared_j == fj ? 0 : 1)) * SLAB, SLAB * 4);
                         floatx4 part[TC][TP];
@@ -875,6 +884,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT + 255) /
 // ---- host side --------------------------------------------------------------------------
 int gemm_k_multiple(int dtype) { return BK * 4 / elem_bytes(dtype); }
 
+void gemm_set_divisors(GemmArgs &a)
+{
+    a.dNo = make_fastdiv(a.No > 0 ? a.No : 1);
+    a.dWo = make_fastdiv(a.Wo > 0 ? a.Wo : 1);
+    a.dHo = make_fastdiv(a.Wo > 0 && a.No >= a.Wo ? a.No / a.Wo : 1);
+    const int nk = a.Kpad / gemm_k_multiple(a.dtype);
+    a.dNk = make_fastdiv(nk > 0 ? nk : 1);
+    a.dGrid = make_fastdiv(a.grid > 0 ? a.grid : 1);
+}
+
 int gemm_select_max_words(void) { return kSelMaxWords; }
 
 int gemm_channel_tile(int M)
@@ -956,7 +975,11 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm)
     const int bm = gemm_channel_tile(a.M);
     const int eu = elems_per_unit(a.dtype);
     if (a.Mpad % bm != 0 || a.Kpad % gemm_k_multiple(a.dtype) != 0 || a.Ms % eu != 0 || a.V < 1 || !a.partial ||
-        !a.tickets || a.grid < 8 || (a.grid & 7))
+        !a.tickets || a.grid < 8 || (a.grid & 7) || a.grid > kMaxGrid)
+        return hipErrorInvalidValue;
+    // the divisors must belong to these arguments, and the schedule's 32-bit arithmetic must hold
+    if (a.dNo.d != a.No || a.dWo.d != a.Wo || a.dHo.d * a.Wo != a.No || a.dGrid.d != a.grid ||
+        a.dNk.d != a.Kpad / gemm_k_multiple(a.dtype) || a.dNk.d >= (1 << 20))
         return hipErrorInvalidValue;
     if (a.sel_words > 0 && a.sel_dilate &&
         (a.stride != 1 || a.kw > 16 || a.kw < 1 || a.kh < 1 || !a.upd_out || a.S < 1 || a.sel_in_words < 1 ||
