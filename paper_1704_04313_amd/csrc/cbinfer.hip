@@ -406,7 +406,7 @@ LayerMaps layer_maps(const cbinfer_state *s, int l)
     // a propagating layer behind this layer's pooling reads the pooled bitmap during the frame
     const bool pool_map_wanted = op.pool_after >= 0 && op.pool_after + 1 < (int)P.ops.size() &&
                                  propagates(P, op.pool_after + 1, s->force_dense);
-    m.in_gemm = !m.identity && op.select && op.stride == 1 && op.kw <= 16 && !s->force_dense && !pool_map_wanted &&
+    m.in_gemm = !m.identity && op.select && op.stride == 1 && op.kw <= 16 && op.kh <= 16 && !s->force_dense && !pool_map_wanted &&
                 words_for((long long)P.S * op.H * op.Wo) <= cbk::gemm_select_max_words();
     return m;
 }

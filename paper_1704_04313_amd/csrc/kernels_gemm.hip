@@ -51,10 +51,21 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const float *p, 
 }
 
 #ifdef CBK_TRACE
+#ifdef CBK_TRACE_FRONT // slots 8-11 stamp the phases of the map ranking instead of a second segment
+#define CBK_STAMP_SLOTS 8
+#define CBK_FRONT(slot)                                                                         \
+    do {                                                                                        \
+        if (lane == 0 && (wave == 0 || wave == kConsWaves))                                      \
+            a.trace[((size_t)blockIdx.x * 2 + (wave != 0)) * 16 + (slot)] = wall_clock64();      \
+    } while (0)
+#else
+#define CBK_STAMP_SLOTS 16
+#define CBK_FRONT(slot) do { } while (0)
+#endif
 // timing study builds only: lane 0 of wave 0 (consumer) and of wave 4 (producer) stamp events
 #define CBK_STAMP(slot)                                                                         \
     do {                                                                                        \
-        if (lane == 0 && (wave == 0 || wave == kConsWaves) && (slot) < 16)                               \
+        if (lane == 0 && (wave == 0 || wave == kConsWaves) && (slot) < CBK_STAMP_SLOTS)                  \
             a.trace[((size_t)blockIdx.x * 2 + (wave != 0)) * 16 + (slot)] = wall_clock64();      \
     } while (0)
 #define CBK_CYCLES(slot)                                                                        \
@@ -65,6 +76,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const float *p, 
 #else
 #define CBK_STAMP(slot) do { } while (0)
 #define CBK_CYCLES(slot) do { } while (0)
+#define CBK_FRONT(slot) do { } while (0)
 #endif
 
 
@@ -161,21 +173,20 @@ __device__ __forceinline__ void load_bitmap(const uint64_t *__restrict__ map, in
     }
 }
 
-// Bits [a, a + len) of an LDS bitmap as the low bits of the result; 1 <= len <= 64, a >= 0, and
-// the word behind the last one read must exist (the maps are followed by a zero word).
+// Bits [a, a + len) of an LDS bitmap as the low bits of the result; 1 <= len <= 64, a >= 0.  Reads
+// the word holding bit a and the one behind it, so a zero word must follow the map; no branches.
 __device__ __forceinline__ uint64_t lds_bit_run(const uint64_t *m, int a, int len)
 {
     const int w = a >> 6, o = a & 63;
-    uint64_t v = m[w] >> o;
-    if (o + len > 64) v |= m[w + 1] << (64 - o);
-    if (len < 64) v &= (1ull << len) - 1ull;
-    return v;
+    const uint64_t lo = m[w], hi = m[w + 1];
+    const uint64_t v = (lo >> o) | ((hi << 1) << (63 - o));
+    return v & (~0ull >> (64 - len));
 }
 
 // Dilation by the filter support for a stride-1 layer (Section 3.1, second formula), in two
 // separable steps on bitmaps in LDS.  sC: change bitmap over the input positions
 // [(st*H + iy)*W + ix].  Step 1 writes sH over [(st*H + iy)*Wo + qx]: is any changed pixel in row
-// iy under the kw taps of output column qx.  Step 2 (dilated_word) ORs the kh rows of sH that an
+// iy under the kw taps of output column qx.  Step 2 (dilated_word_rows) ORs the kh rows of sH that an
 // output row reads.  All bitmaps are followed by a zero word.
 __device__ __forceinline__ uint64_t row_dilated_word(const GemmArgs &a, const uint64_t *sC, int v, int total)
 {
@@ -217,7 +228,10 @@ __device__ __forceinline__ uint64_t row_dilated_word(const GemmArgs &a, const ui
     return res;
 }
 
-__device__ __forceinline__ uint64_t dilated_word(const GemmArgs &a, const uint64_t *sH, int w, int total)
+// The share of tap rows j0, j0 + dj, j0 + 2 dj, ... in word w of the update map: for each output row
+// the word touches, the bits of the sH rows qy - pad + j (nothing for rows outside the image).
+__device__ __forceinline__ uint64_t dilated_word_rows(const GemmArgs &a, const uint64_t *sH, int w, int j0, int dj,
+                                                      int total)
 {
     const int p0 = w * 64, p1 = p0 + 64 < total ? p0 + 64 : total;
     const int Ho = a.dHo.d;
@@ -228,9 +242,11 @@ __device__ __forceinline__ uint64_t dilated_word(const GemmArgs &a, const uint64
     while (pos < p1) {
         const int len = a.Wo - x < p1 - pos ? a.Wo - x : p1 - pos;
         uint64_t r = 0;
-        for (int j = 0; j < a.kh; ++j) {
+        for (int j = j0; j < a.kh; j += dj) {
             const int iy = qy - a.pad + j;
-            if ((unsigned)iy < (unsigned)a.H) r |= lds_bit_run(sH, (st * a.H + iy) * a.Wo + x, len);
+            const bool in = (unsigned)iy < (unsigned)a.H;
+            const uint64_t b = lds_bit_run(sH, in ? (st * a.H + iy) * a.Wo + x : 0, len);
+            r |= in ? b : 0ull;
         }
         res |= r << (pos - p0);
         pos += len;
@@ -241,6 +257,20 @@ __device__ __forceinline__ uint64_t dilated_word(const GemmArgs &a, const uint64
         }
     }
     return res;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves: shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes, then lane 15 of a row into the next row (rows 1 and 3)
+// and lane 31 into rows 2 and 3.  Lanes without a source add the zero given as the old value.
+__device__ __forceinline__ int wave_inclusive_sum(int x)
+{
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false); // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false); // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false); // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false); // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false); // row_bcast:15
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false); // row_bcast:31
+    return x;
 }
 
 // Brings the map of positions to recompute into LDS (sW) and ranks it: sRank[i] = number of
@@ -262,19 +292,31 @@ __device__ __forceinline__ int rank_selection(const GemmArgs &a, uint64_t *sW, i
         load_bitmap(a.sel_map, a.sel_bytes, in_words, sC);
         if (tid < 2) sC[in_words + tid] = 0ull;
         __syncthreads();
+        CBK_FRONT(8);
         for (int v = tid; v < hd_words; v += NT) sH[v] = row_dilated_word(a, sC, v, hd_total);
         if (tid < 2) sH[hd_words + tid] = 0ull;
+        for (int i = tid; i < nw; i += NT) sW[i] = 0ull;
         __syncthreads();
+        CBK_FRONT(9);
+        // 2^sh threads per word share its kh tap rows (as many as keeps all words in one round, at
+        // most one thread per row); their parts are OR-ed together in LDS
         const int out_total = a.S * a.No;
-        for (int i = tid; i < nw; i += NT) { // one word per thread and round: all lanes busy
-            const uint64_t d = dilated_word(a, sH, i, out_total);
-            sW[i] = d;
-            if (blockIdx.x == 0) a.upd_out[i] = d;
+        int sh = 0;
+        while ((1 << sh) < a.kh && (nw << (sh + 1)) <= NT) ++sh;
+        for (int t = tid; t < (nw << sh); t += NT) {
+            const int i = t >> sh, j0 = t & ((1 << sh) - 1);
+            const uint64_t d = dilated_word_rows(a, sH, i, j0, 1 << sh, out_total);
+            if (d) atomicOr(reinterpret_cast<unsigned long long *>(sW + i), (unsigned long long)d);
+        }
+        if (blockIdx.x == 0) {
+            __syncthreads();
+            for (int i = tid; i < nw; i += NT) a.upd_out[i] = sW[i];
         }
     } else {
         load_bitmap(a.sel_map, a.sel_bytes, nw, sW);
     }
     __syncthreads();
+    CBK_FRONT(10);
 #pragma unroll
     for (int j = 0; j < kSelWordsPerThread; ++j) {
         const int i = kSelWordsPerThread * tid + j;
@@ -289,12 +331,7 @@ __device__ __forceinline__ int rank_selection(const GemmArgs &a, uint64_t *sW, i
         c[j] = __popcll(w[j]);
         sum += c[j];
     }
-    int incl = sum;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int o = __shfl_up(incl, d, 64);
-        if (lane >= d) incl += o;
-    }
+    const int incl = wave_inclusive_sum(sum);
     if (lane == 63) sTot[wave] = incl;
     __syncthreads();
     int before = 0, total = 0;
@@ -311,6 +348,7 @@ __device__ __forceinline__ int rank_selection(const GemmArgs &a, uint64_t *sW, i
         e += c[j];
     }
     __syncthreads();
+    CBK_FRONT(11);
     return total;
 }
 
@@ -522,6 +560,24 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
         const bool partial = (kc1 - kc0) != nk;
 
         CBK_STAMP(2 + 6 * seg);
+        // Producers: the tap descriptors and the filter rows of the first two slices do not depend
+        // on the tile's pixel list, so their loads are in flight while the list is made.
+        const int ptid = producer ? tid - NCONS : 0;
+        const int v = ptid & 7;   // 16-byte unit column inside the K slice
+        const int r0 = ptid >> 3; // first row this thread stages
+        const floatx4 *wrow = static_cast<const floatx4 *>(a.wt) + (size_t)(mt * BM + r0) * krow + v;
+        const int2 *taps = a.taps + v;
+        auto tap = [&](int kc) { return taps[(kc < kc1 ? kc : kc0) * KU]; };
+        int2 tpA, tpB, t2, t3;
+        floatx4 rbA[PB], rbB[PB];
+        if (producer) {
+            tpA = tap(kc0);
+            tpB = tap(kc0 + 1);
+            t2 = tap(kc0 + 2);
+            t3 = tap(kc0 + 3);
+            load_filter_rows<BM, PB>(wrow, krow, kc0, r0, rbA);
+            if (kc0 + 1 < kc1) load_filter_rows<BM, PB>(wrow, krow, kc0 + 1, r0, rbB);
+        }
         __syncthreads(); // the previous segment's LDS reads are done
         if (sel.words) {
             select_tile<BN>(sel, n, pt * BN, sU, sFlag + 1);
@@ -547,9 +603,6 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
 
         // Both roles execute the same number of barriers: one after the prologue, one per slice.
         if (producer) {
-            const int ptid = tid - NCONS;
-            const int v = ptid & 7;   // 16-byte unit column inside the K slice
-            const int r0 = ptid >> 3; // first row this thread stages
             const int vs = v ^ lds_swizzle(r0); // slot of that unit in those rows
             int iy0[PA], ix0[PA], base[PA];
 #pragma unroll
@@ -567,23 +620,14 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                     base[ps] = 0;
                 }
             }
-            const floatx4 *wrow = static_cast<const floatx4 *>(a.wt) + (size_t)(mt * BM + r0) * krow + v;
-            const int2 *taps = a.taps + v;
             // Two register sets: while the slice loaded two iterations ago is stored to LDS, the
             // loads of the slice after next are already in flight (a slice of MFMA work is shorter
             // than a global-memory round trip for the small tiles).  The tap descriptor of a slice
             // is loaded before the operand loads that need it.
-            floatx4 raA[PA], rbA[PB], raB[PA], rbB[PB];
-            auto tap = [&](int kc) { return taps[(kc < kc1 ? kc : kc0) * KU]; };
-            int2 tpA = tap(kc0), tpB = tap(kc0 + 1);
-            const int2 t2 = tap(kc0 + 2), t3 = tap(kc0 + 3);
+            floatx4 raA[PA], raB[PA];
             // prologue: slices kc0 and kc0+1 into ring slots 0 and 1, slices kc0+2 and kc0+3 in flight
             gather_rows<PA>(a, tpA, iy0, ix0, base, raA);
-            load_filter_rows<BM, PB>(wrow, krow, kc0, r0, rbA);
-            if (kc0 + 1 < kc1) {
-                gather_rows<PA>(a, tpB, iy0, ix0, base, raB);
-                load_filter_rows<BM, PB>(wrow, krow, kc0 + 1, r0, rbB);
-            }
+            if (kc0 + 1 < kc1) gather_rows<PA>(a, tpB, iy0, ix0, base, raB);
             tpA = tap(kc0 + 4);
             tpB = tap(kc0 + 5);
             stage_rows<BM, PA, PB>(As, Bs, r0, vs, raA, rbA);
@@ -982,7 +1026,7 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm)
         a.dNk.d != a.Kpad / gemm_k_multiple(a.dtype) || a.dNk.d >= (1 << 20))
         return hipErrorInvalidValue;
     if (a.sel_words > 0 && a.sel_dilate &&
-        (a.stride != 1 || a.kw > 16 || a.kw < 1 || a.kh < 1 || !a.upd_out || a.S < 1 || a.sel_in_words < 1 ||
+        (a.stride != 1 || a.kw > 16 || a.kw < 1 || a.kh < 1 || a.kh > 16 || !a.upd_out || a.S < 1 || a.sel_in_words < 1 ||
          a.sel_in_words > kSelMaxWords || ((long long)a.S * a.H * a.Wo + 63) / 64 > kSelMaxWords ||
          (long long)a.sel_in_words * 64 < (long long)a.S * a.N || a.No % a.Wo != 0))
         return hipErrorInvalidValue;
