@@ -560,8 +560,8 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
         const bool partial = (kc1 - kc0) != nk;
 
         CBK_STAMP(2 + 6 * seg);
-        // Producers: the tap descriptors and the filter rows of the first two slices do not depend
-        // on the tile's pixel list, so their loads are in flight while the list is made.
+        // Producers: the tap descriptors of the first slices do not depend on the tile's pixel list,
+        // so their loads are in flight while the list is made.
         const int ptid = producer ? tid - NCONS : 0;
         const int v = ptid & 7;   // 16-byte unit column inside the K slice
         const int r0 = ptid >> 3; // first row this thread stages
@@ -569,14 +569,11 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
         const int2 *taps = a.taps + v;
         auto tap = [&](int kc) { return taps[(kc < kc1 ? kc : kc0) * KU]; };
         int2 tpA, tpB, t2, t3;
-        floatx4 rbA[PB], rbB[PB];
         if (producer) {
             tpA = tap(kc0);
             tpB = tap(kc0 + 1);
             t2 = tap(kc0 + 2);
             t3 = tap(kc0 + 3);
-            load_filter_rows<BM, PB>(wrow, krow, kc0, r0, rbA);
-            if (kc0 + 1 < kc1) load_filter_rows<BM, PB>(wrow, krow, kc0 + 1, r0, rbB);
         }
         __syncthreads(); // the previous segment's LDS reads are done
         if (sel.words) {
@@ -595,11 +592,9 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
         const int wch0 = (cw / WN) * (BM / WM);
         const int lrow = lane & 15; // row of the 16-row operand tiles this lane feeds
         const int lk = lane >> 4;   // k slot this lane feeds
+        // cleared inside the role branches, for the producers after their loop: registers that
+        // hold nothing while they stage slices
         floatx4 acc[TC][TP];
-#pragma unroll
-        for (int j = 0; j < TC; ++j)
-#pragma unroll
-            for (int i = 0; i < TP; ++i) acc[j][i] = (floatx4){0.f, 0.f, 0.f, 0.f};
 
         // Both roles execute the same number of barriers: one after the prologue, one per slice.
         if (producer) {
@@ -624,10 +619,14 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             // loads of the slice after next are already in flight (a slice of MFMA work is shorter
             // than a global-memory round trip for the small tiles).  The tap descriptor of a slice
             // is loaded before the operand loads that need it.
-            floatx4 raA[PA], raB[PA];
+            floatx4 raA[PA], rbA[PB], raB[PA], rbB[PB];
             // prologue: slices kc0 and kc0+1 into ring slots 0 and 1, slices kc0+2 and kc0+3 in flight
             gather_rows<PA>(a, tpA, iy0, ix0, base, raA);
-            if (kc0 + 1 < kc1) gather_rows<PA>(a, tpB, iy0, ix0, base, raB);
+            load_filter_rows<BM, PB>(wrow, krow, kc0, r0, rbA);
+            if (kc0 + 1 < kc1) {
+                gather_rows<PA>(a, tpB, iy0, ix0, base, raB);
+                load_filter_rows<BM, PB>(wrow, krow, kc0 + 1, r0, rbB);
+            }
             tpA = tap(kc0 + 4);
             tpB = tap(kc0 + 5);
             stage_rows<BM, PA, PB>(As, Bs, r0, vs, raA, rbA);
@@ -667,7 +666,15 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                     __syncthreads();
                 }
             }
+#pragma unroll
+            for (int j = 0; j < TC; ++j)
+#pragma unroll
+                for (int i = 0; i < TP; ++i) acc[j][i] = (floatx4){0.f, 0.f, 0.f, 0.f};
         } else {
+#pragma unroll
+            for (int j = 0; j < TC; ++j)
+#pragma unroll
+                for (int i = 0; i < TP; ++i) acc[j][i] = (floatx4){0.f, 0.f, 0.f, 0.f};
             // fragment group kk of this lane's row: unit 4*kk + lk, stored in slot (4*kk + lk) ^ swizzle
             const int u0 = (lk ^ lds_swizzle(lrow)) * 4;
             const float *A0 = As + (wpx0 + lrow) * LDK;
