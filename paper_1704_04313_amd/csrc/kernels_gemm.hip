@@ -100,6 +100,9 @@ static constexpr int kRP = NPROD / 8;             // tile rows staged per pass: 
 static constexpr int NCONS = 64 * kConsWaves;     // consumer threads: waves 0 .. kConsWaves-1
 static constexpr int NT = NCONS + NPROD;          // threads per workgroup
 static constexpr int kStages = 3;   // K slices resident in LDS
+#ifndef CBK_THREE_SETS_UNITS
+#define CBK_THREE_SETS_UNITS 6 // tiles whose producer threads load at most this many 16-byte units per slice
+#endif
 #ifndef CBK_MIN_ITERS
 #define CBK_MIN_ITERS 8
 #endif
@@ -498,6 +501,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
     constexpr int TC = BM / WM / 16; // 16-channel MFMA tiles per consumer wave
     constexpr int PA = BN / kRP;     // image-matrix rows staged per producer thread and slice
     constexpr int PB = (BM + kRP - 1) / kRP;
+    constexpr int NS = PA + PB <= CBK_THREE_SETS_UNITS ? 3 : 2; // register sets of loads in flight per producer thread
     static_assert(BN % kRP == 0, "whole passes over the pixel rows");
     constexpr int ASZ = BN * LDK, BSZ = BM * LDK;
     constexpr int SLAB = BM * BN; // floats of one partial-accumulator slab
@@ -568,12 +572,12 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
         const floatx4 *wrow = static_cast<const floatx4 *>(a.wt) + (size_t)(mt * BM + r0) * krow + v;
         const int2 *taps = a.taps + v;
         auto tap = [&](int kc) { return taps[(kc < kc1 ? kc : kc0) * KU]; };
-        int2 tpA, tpB, t2, t3;
+        int2 tp0, tp1, tp[NS];
         if (producer) {
-            tpA = tap(kc0);
-            tpB = tap(kc0 + 1);
-            t2 = tap(kc0 + 2);
-            t3 = tap(kc0 + 3);
+            tp0 = tap(kc0);
+            tp1 = tap(kc0 + 1);
+#pragma unroll
+            for (int u = 0; u < NS; ++u) tp[u] = tap(kc0 + 2 + u);
         }
         __syncthreads(); // the previous segment's LDS reads are done
         if (sel.words) {
@@ -615,55 +619,47 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                     base[ps] = 0;
                 }
             }
-            // Two register sets: while the slice loaded two iterations ago is stored to LDS, the
-            // loads of the slice after next are already in flight (a slice of MFMA work is shorter
-            // than a global-memory round trip for the small tiles).  The tap descriptor of a slice
-            // is loaded before the operand loads that need it.
-            floatx4 raA[PA], rbA[PB], raB[PA], rbB[PB];
-            // prologue: slices kc0 and kc0+1 into ring slots 0 and 1, slices kc0+2 and kc0+3 in flight
-            gather_rows<PA>(a, tpA, iy0, ix0, base, raA);
-            load_filter_rows<BM, PB>(wrow, krow, kc0, r0, rbA);
+            // NS register sets: in iteration kc the slice kc+2, loaded NS iterations ago, is stored to
+            // the LDS ring and the loads of slice kc+2+NS are issued into the same registers.  The
+            // loop runs at the pace of these loads when NS slices of MFMA work are shorter than a
+            // global-memory round trip, so the small tiles get a third set.  The tap descriptor of
+            // a slice is loaded a round before the operand loads that need it.
+            floatx4 ra[NS][PA], rb[NS][PB];
+            // prologue: slices kc0 and kc0+1 into ring slots 0 and 1, slices kc0+2 .. kc0+1+NS in flight
+            gather_rows<PA>(a, tp0, iy0, ix0, base, ra[0]);
+            load_filter_rows<BM, PB>(wrow, krow, kc0, r0, rb[0]);
             if (kc0 + 1 < kc1) {
-                gather_rows<PA>(a, tpB, iy0, ix0, base, raB);
-                load_filter_rows<BM, PB>(wrow, krow, kc0 + 1, r0, rbB);
+                gather_rows<PA>(a, tp1, iy0, ix0, base, ra[1]);
+                load_filter_rows<BM, PB>(wrow, krow, kc0 + 1, r0, rb[1]);
             }
-            tpA = tap(kc0 + 4);
-            tpB = tap(kc0 + 5);
-            stage_rows<BM, PA, PB>(As, Bs, r0, vs, raA, rbA);
-            if (kc0 + 1 < kc1) stage_rows<BM, PA, PB>(As + ASZ, Bs + BSZ, r0, vs, raB, rbB);
-            if (kc0 + 2 < kc1) {
-                gather_rows<PA>(a, t2, iy0, ix0, base, raA);
-                load_filter_rows<BM, PB>(wrow, krow, kc0 + 2, r0, rbA);
-            }
-            if (kc0 + 3 < kc1) {
-                gather_rows<PA>(a, t3, iy0, ix0, base, raB);
-                load_filter_rows<BM, PB>(wrow, krow, kc0 + 3, r0, rbB);
+            stage_rows<BM, PA, PB>(As, Bs, r0, vs, ra[0], rb[0]);
+            if (kc0 + 1 < kc1) stage_rows<BM, PA, PB>(As + ASZ, Bs + BSZ, r0, vs, ra[1], rb[1]);
+#pragma unroll
+            for (int u = 0; u < NS; ++u) {
+                if (kc0 + 2 + u < kc1) {
+                    gather_rows<PA>(a, tp[u], iy0, ix0, base, ra[u]);
+                    load_filter_rows<BM, PB>(wrow, krow, kc0 + 2 + u, r0, rb[u]);
+                }
+                tp[u] = tap(kc0 + 2 + NS + u);
             }
             __syncthreads();
             CBK_STAMP(3 + 6 * seg);
             int slot = 2; // ring slot of slice kc+2
-            for (int kc = kc0; kc < kc1; kc += 2) {
-                if (kc + 2 < kc1) {
-                    stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, vs, raA, rbA);
-                    if (kc + 4 < kc1) {
-                        gather_rows<PA>(a, tpA, iy0, ix0, base, raA);
-                        load_filter_rows<BM, PB>(wrow, krow, kc + 4, r0, rbA);
-                        tpA = tap(kc + 6);
-                    }
-                }
-                slot = slot == kStages - 1 ? 0 : slot + 1;
-                __syncthreads();
-                if (kc + 1 < kc1) {
-                    if (kc + 3 < kc1) {
-                        stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, vs, raB, rbB);
-                        if (kc + 5 < kc1) {
-                            gather_rows<PA>(a, tpB, iy0, ix0, base, raB);
-                            load_filter_rows<BM, PB>(wrow, krow, kc + 5, r0, rbB);
-                            tpB = tap(kc + 7);
+            for (int kc = kc0; kc < kc1; kc += NS) {
+#pragma unroll
+                for (int u = 0; u < NS; ++u) {
+                    if (kc + u < kc1) {
+                        if (kc + u + 2 < kc1) {
+                            stage_rows<BM, PA, PB>(As + slot * ASZ, Bs + slot * BSZ, r0, vs, ra[u], rb[u]);
+                            if (kc + u + 2 + NS < kc1) {
+                                gather_rows<PA>(a, tp[u], iy0, ix0, base, ra[u]);
+                                load_filter_rows<BM, PB>(wrow, krow, kc + u + 2 + NS, r0, rb[u]);
+                                tp[u] = tap(kc + u + 2 + 2 * NS);
+                            }
                         }
+                        slot = slot == kStages - 1 ? 0 : slot + 1;
+                        __syncthreads();
                     }
-                    slot = slot == kStages - 1 ? 0 : slot + 1;
-                    __syncthreads();
                 }
             }
 #pragma unroll
