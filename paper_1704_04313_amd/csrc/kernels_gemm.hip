@@ -725,7 +725,10 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                 __builtin_amdgcn_sched_barrier(0);
                 multiply(0);
                 __builtin_amdgcn_sched_barrier(0);
-                if (kc + 1 < kc1) read_frags(0, nslot, 0);
+                // Also in the last iteration, where the slot holds nothing of use: under a condition
+                // the compiler, which counts outstanding LDS reads per path, would make the MFMAs
+                // below wait for these reads too.
+                read_frags(0, nslot, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 multiply(1);
                 __builtin_amdgcn_sched_barrier(0);
