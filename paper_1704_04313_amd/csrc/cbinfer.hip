@@ -411,8 +411,24 @@ LayerMaps layer_maps(const cbinfer_state *s, int l)
     return m;
 }
 
+// The three group-count arrays of op l (update map, change map, pooled map), one behind the other.
+struct GroupCounts {
+    int *upd, *chg, *pool;
+};
+GroupCounts group_counts(const cbinfer_state *s, int l)
+{
+    const Plan &P = s->plan;
+    const Op &op = P.ops[l];
+    const long long N = (long long)P.S * op.H * op.W, No = (long long)P.S * op.Ho * op.Wo;
+    const size_t gstride = cbk::compact_group_count_bytes(words_for(std::max(N, No))) / sizeof(int);
+    int *groups = s->at<int>(op.o_groups);
+    return {groups, groups + gstride, groups + 2 * gstride};
+}
+
 // Dilation launch for op l: change map -> map of outputs to recompute (+ pooled positions).
-hipError_t dilate_maps(const cbinfer_state *s, int l, const LayerMaps &m, const cbk::Timing &tm = cbk::Timing())
+// counted (optional) is set if the launch also left the maps' group counts for extract_lists.
+hipError_t dilate_maps(const cbinfer_state *s, int l, const LayerMaps &m, bool *counted = nullptr,
+                       const cbk::Timing &tm = cbk::Timing())
 {
     const Plan &P = s->plan;
     const Op &op = P.ops[l];
@@ -425,28 +441,35 @@ hipError_t dilate_maps(const cbinfer_state *s, int l, const LayerMaps &m, const 
         const Op &pp = P.ops[op.pool_after];
         g.pool_k = pp.kh; g.Hp = pp.Ho; g.Wp = pp.Wo;
     }
-    return cbk::dilate(s->stream, m.chg, m.upd, m.pool, g, tm);
+    if (counted) {
+        const GroupCounts gc = group_counts(s, l);
+        const cbk::DilateGroups dg = {gc.upd, gc.pool, gc.chg};
+        *counted = cbk::dilate_counts(g) && (gc.pool != nullptr || !m.pool);
+        return cbk::dilate(s->stream, m.chg, m.upd, m.pool, g, &dg, tm);
+    }
+    return cbk::dilate(s->stream, m.chg, m.upd, m.pool, g, nullptr, tm);
 }
 
 // Change-index extraction for op l (and the pooling op behind it): maps -> ascending lists and counts.
-hipError_t extract_lists(const cbinfer_state *s, int l, const LayerMaps &m, const cbk::Timing &tm = cbk::Timing())
+// counted: the dilation launch of this frame has left the group counts of all three maps.
+hipError_t extract_lists(const cbinfer_state *s, int l, const LayerMaps &m, bool counted = false,
+                         const cbk::Timing &tm = cbk::Timing())
 {
     const Plan &P = s->plan;
     const Op &op = P.ops[l];
     const long long N = (long long)P.S * op.H * op.W, No = (long long)P.S * op.Ho * op.Wo;
     int *counts = s->at<int>(op.o_counts);
+    const GroupCounts gc = group_counts(s, l);
     cbk::CompactJob jobs[3];
     int nj = 0;
-    const size_t gstride = cbk::compact_group_count_bytes(words_for(std::max(N, No))) / sizeof(int);
-    int *groups = s->at<int>(op.o_groups);
-    jobs[nj++] = {m.upd, m.upd_bytes, words_for(No), s->at<int>(op.o_ulist), counts + 1, groups};
-    jobs[nj++] = {m.chg, m.chg_bytes, words_for(N), s->at<int>(op.o_clist), counts + 0, groups + gstride};
+    jobs[nj++] = {m.upd, m.upd_bytes, words_for(No), s->at<int>(op.o_ulist), counts + 1, gc.upd};
+    jobs[nj++] = {m.chg, m.chg_bytes, words_for(N), s->at<int>(op.o_clist), counts + 0, gc.chg};
     if (m.pool) {
         const Op &pp = P.ops[op.pool_after];
         jobs[nj++] = {m.pool, 0, words_for((long long)P.S * pp.Ho * pp.Wo), s->at<int>(pp.o_ulist),
-                      s->at<int>(pp.o_counts) + 1, groups + 2 * gstride};
+                      s->at<int>(pp.o_counts) + 1, gc.pool};
     }
-    return cbk::compact(s->stream, jobs, nj, tm);
+    return cbk::compact(s->stream, jobs, nj, counted, tm);
 }
 
 
@@ -498,9 +521,10 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             int sel_bytes = 0, sel_dilate = 0;
             if (!s->force_dense) {
                 const LayerMaps m = layer_maps(s, l);
+                bool counted = false;
                 if (!m.identity && !m.in_gemm) {
                     StepTimer t(s, l, CBINFER_STEP_DILATE);
-                    HIP_TRY(dilate_maps(s, l, m, t.timing()));
+                    HIP_TRY(dilate_maps(s, l, m, op.select ? nullptr : &counted, t.timing()));
                 }
                 if (op.select) {
                     sel_map = m.in_gemm ? m.chg : m.upd;
@@ -511,7 +535,7 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                     s->lists_stale = true;
                 } else {
                     StepTimer t(s, l, CBINFER_STEP_COMPACT);
-                    HIP_TRY(extract_lists(s, l, m, t.timing()));
+                    HIP_TRY(extract_lists(s, l, m, counted, t.timing()));
                     ulist = s->at<int>(op.o_ulist);
                     ucount = counts + 1;
                 }

@@ -113,33 +113,6 @@ hipError_t detect_frame(hipStream_t st, const float *frame, void *ref, void *cur
 hipError_t detect_map(hipStream_t st, const void *x, void *ref, uint64_t *bits, int V, int total, float tau,
                       int hold, int force, int dtype, const Timing &tm = Timing());
 
-// ---- dilation by the filter support (Section 3.1, second formula) -------------------------
-// upd bit (stream, qy, qx) = OR of the change bits inside that output's receptive field.
-// If pool_bits != nullptr also writes, for a k x k / stride k pooling that follows, the
-// bitmap of pooled positions whose window contains an updated output.
-struct DilateGeom {
-    int S, H, W, Ho, Wo, kh, kw, stride, pad; // convolution geometry
-    int pool_k, Hp, Wp;                       // pooling that follows (pool_k == 0: none)
-    int chg_bytes;                            // the change map has one byte per pixel instead of one bit
-};
-hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, uint64_t *pool_bits,
-                  const DilateGeom &g, const Timing &tm = Timing());
-
-// ---- change-index extraction (Section 3.1) -------------------------------------------------
-// Up to three bitmaps -> ascending index lists and counts in one launch.
-struct CompactJob {
-    const uint64_t *bits; // bitmap, or (bytes != 0) a map with one byte per pixel, padded to 64 pixels
-    int bytes;
-    int nwords;           // 64-pixel words
-    int *list;
-    int *count;
-    int *group_counts;    // scratch of compact_group_count_bytes(nwords) bytes; needed (non-null) when
-                          // compact_two_level(nwords), i.e. for maps of several hundred thousand pixels
-};
-bool compact_two_level(int nwords);
-size_t compact_group_count_bytes(int nwords);
-hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, const Timing &tm = Timing());
-
 // Division of a non-negative 32-bit number by an invariant divisor through one 64-bit
 // multiplication (integer division is emulated with dozens of instructions on this hardware).
 // Exact for 0 <= n < 2^31 and 1 <= d < 2^31: with l = ceil(log2 d) and m = floor(2^(31+l) / d) + 1,
@@ -163,6 +136,44 @@ __host__ __device__ inline int fast_div(int n, const FastDiv &f)
 {
     return (int)(((unsigned long long)(unsigned)n * f.m) >> f.shift);
 }
+
+// ---- dilation by the filter support (Section 3.1, second formula) -------------------------
+// upd bit (stream, qy, qx) = OR of the change bits inside that output's receptive field.
+// If pool_bits != nullptr also writes, for a k x k / stride k pooling that follows, the
+// bitmap of pooled positions whose window contains an updated output.
+struct DilateGeom {
+    int S, H, W, Ho, Wo, kh, kw, stride, pad; // convolution geometry
+    int pool_k, Hp, Wp;                       // pooling that follows (pool_k == 0: none)
+    int chg_bytes;                            // the change map has one byte per pixel instead of one bit
+};
+// groups: null, or one array of compact_group_count_bytes() bytes per map (update map, pooled map,
+// change map, in this order; the pooled one may be null without pooling).  When dilate_counts(g)
+// -- a geometry the word-at-a-time kernel handles -- the launch also fills them with the number of
+// set bits per group of words, which compact() then need not count (groups_ready).
+struct DilateGroups {
+    int *upd, *pool, *chg;
+};
+bool dilate_counts(const DilateGeom &g);
+hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, uint64_t *pool_bits,
+                  const DilateGeom &g, const DilateGroups *groups = nullptr, const Timing &tm = Timing());
+
+// ---- change-index extraction (Section 3.1) -------------------------------------------------
+// Up to three bitmaps -> ascending index lists and counts in one launch.
+struct CompactJob {
+    const uint64_t *bits; // bitmap, or (bytes != 0) a map with one byte per pixel, padded to 64 pixels
+    int bytes;
+    int nwords;           // 64-pixel words
+    int *list;
+    int *count;
+    int *group_counts;    // scratch of compact_group_count_bytes(nwords) bytes; needed (non-null) when
+                          // compact_two_level(nwords), i.e. for maps of several hundred thousand pixels
+};
+bool compact_two_level(int nwords);
+size_t compact_group_count_bytes(int nwords);
+// groups_ready: every job's group_counts already holds the set bits of its groups of words.
+hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, bool groups_ready = false,
+                   const Timing &tm = Timing());
+
 
 // ---- gathered matrix generation + multiplication + output update (Section 3.1) -------------
 struct GemmArgs {

@@ -275,11 +275,269 @@ __global__ __launch_bounds__(kBlock) void dilate_kernel(const uint64_t *__restri
     }
 }
 
-hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, uint64_t *pool_bits,
-                  const DilateGeom &g, const Timing &tm)
+// ------------------------------------------------------------------------------------------
+// Dilation a word at a time, for stride-1 layers with filters up to 16 wide (and a 2 x 2
+// pooling behind them, if any).  A workgroup produces kCountWords words of the update map or of
+// the pooled map, or counts as many of the change map.  It first brings the input rows its
+// outputs read -- a contiguous piece of the change map -- into LDS as bits (a byte map is packed
+// on the way): one round of coalesced loads, everything after that reads LDS.  Eight lanes then
+// share one 64-position word: lane r takes the input rows r, r + 8, ... of the receptive fields.
+// Dilation is separable and OR commutes, so each lane ORs the raw change bits of its rows (a
+// window of the outputs' columns plus the filter's reach), then the shifted copies of that
+// window by doubling, and the eight partial words are OR-ed across the lanes.  The fields of the
+// 2 x 2 outputs under a pooled position tile one (kh+1) x (kw+1) window, so the pooled map is a
+// dilation with that window at stride 2.  The workgroup also leaves the number of set bits of
+// its words, which is what the index extraction needs to place its output.
+// ------------------------------------------------------------------------------------------
+static constexpr int kCompactWords = 128; // words per workgroup of the index extraction
+static constexpr int kCountWords = 32;    // words per entry of the group-count arrays
+static constexpr int kWordLanes = 8;
+static constexpr int kRegionWords = 4096; // LDS bitmap of the input piece: 32 KiB
+static_assert(kCountWords * kWordLanes == kBlock, "one word per eight lanes");
+
+// Bits [a, a + len) of the LDS bitmap as the low bits of the result; 1 <= len <= 64; the word
+// behind the one holding bit a is read too (zero words follow the piece).
+__device__ __forceinline__ uint64_t lds_run(const uint64_t *m, int a, int len)
 {
+    const int w = a >> 6, o = a & 63;
+    const uint64_t lo = m[w], hi = m[w + 1];
+    const uint64_t v = (lo >> o) | ((hi << 1) << (63 - o));
+    return v & (~0ull >> (64 - len));
+}
+
+// A window of up to 192 columns, bit t = column xs + t.
+struct Window {
+    uint64_t w[3];
+};
+
+// OR over the input rows iy0 + j0, iy0 + j0 + dj, ... (j < nrows, inside the image) of stream st,
+// columns xs .. xs + L - 1 (zero outside the image); L <= 192.  sM holds the change bits from
+// position bit0 on.
+__device__ __forceinline__ Window rows_or(const uint64_t *sM, int bit0, const DilateGeom &g, int st, int iy0,
+                                          int nrows, int xs, int L, int j0, int dj)
+{
+    Window r = {{0ull, 0ull, 0ull}};
+    const int k0 = xs < 0 ? -xs : 0, k1 = L < g.W - xs ? L : g.W - xs; // window bits inside the image
+    for (int j = j0; j < nrows; j += dj) {
+        const int iy = iy0 + j;
+        if ((unsigned)iy >= (unsigned)g.H) continue;
+        const int base = (st * g.H + iy) * g.W + xs - bit0;
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            const int lo = k0 > 64 * c ? k0 : 64 * c, hi = k1 < 64 * c + 64 ? k1 : 64 * c + 64;
+            if (hi > lo) r.w[c] |= lds_run(sM, base + lo, hi - lo) << (lo - 64 * c);
+        }
+    }
+    return r;
+}
+
+// bit t := OR of bits t .. t + taps - 1, by doubling
+__device__ __forceinline__ void spread(Window &r, int taps)
+{
+    auto step = [&](int s) {
+        r.w[0] |= (r.w[0] >> s) | (r.w[1] << (64 - s));
+        r.w[1] |= (r.w[1] >> s) | (r.w[2] << (64 - s));
+        r.w[2] |= r.w[2] >> s;
+    };
+    int cover = 1;
+    while (cover * 2 <= taps) {
+        step(cover);
+        cover *= 2;
+    }
+    if (cover < taps) step(taps - cover);
+}
+
+// bits 0, 2, 4, ... of x moved to bits 0, 1, 2, ...
+__device__ __forceinline__ uint64_t even_bits(uint64_t x)
+{
+    x &= 0x5555555555555555ull;
+    x = (x | (x >> 1)) & 0x3333333333333333ull;
+    x = (x | (x >> 2)) & 0x0f0f0f0f0f0f0f0full;
+    x = (x | (x >> 4)) & 0x00ff00ff00ff00ffull;
+    x = (x | (x >> 8)) & 0x0000ffff0000ffffull;
+    x = (x | (x >> 16)) & 0x00000000ffffffffull;
+    return x;
+}
+
+// OR over the kWordLanes lanes that share a word
+__device__ __forceinline__ uint64_t word_lanes_or(uint64_t v)
+{
+    unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
+#pragma unroll
+    for (int d = 1; d < kWordLanes; d <<= 1) {
+        lo |= (unsigned)__shfl_xor((int)lo, d, 64);
+        hi |= (unsigned)__shfl_xor((int)hi, d, 64);
+    }
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// eight bytes of a byte map -> eight bits: the high bit of (x | (x & 0x7f..7f) + 0x7f..7f) marks
+// a nonzero byte and the multiplication gathers the eight marks
+__device__ __forceinline__ unsigned nonzero_bytes(uint64_t x)
+{
+    const uint64_t nz = ((x | ((x & 0x7f7f7f7f7f7f7f7full) + 0x7f7f7f7f7f7f7f7full)) & 0x8080808080808080ull) >> 7;
+    return (unsigned)((nz * 0x0102040810204080ull) >> 56);
+}
+
+struct DilateWords {
+    const uint64_t *chg;
+    uint64_t *upd, *pool;
+    int *upd_groups, *pool_groups, *chg_groups; // all null: no counting
+    DilateGeom g;
+    FastDiv dWo, dHo, dWp, dHp;
+    int upd_words, pool_words, chg_words;
+    int upd_blocks, pool_blocks; // workgroups per role, in this order; the rest count the change map
+};
+
+template <bool BYTES>
+__global__ __launch_bounds__(kBlock) void dilate_words_kernel(DilateWords a)
+{
+    __shared__ uint64_t sM[kRegionWords + 2];
+    __shared__ int swave[kBlock / 64];
+    const DilateGeom &g = a.g;
+    const int tid = threadIdx.x, r = tid & (kWordLanes - 1);
+    int b = blockIdx.x;
+    const int role = b < a.upd_blocks ? 0 : (b < a.upd_blocks + a.pool_blocks ? 1 : 2);
+    if (role >= 1) b -= a.upd_blocks;
+    if (role == 2) b -= a.pool_blocks;
+    const int nwords = role == 0 ? a.upd_words : (role == 1 ? a.pool_words : a.chg_words);
+    int *groups = role == 0 ? a.upd_groups : (role == 1 ? a.pool_groups : a.chg_groups);
+    const int i = b * kCountWords + (tid >> 3); // this lane's word (shared with seven neighbours)
+    uint64_t word = 0;
+
+    if (role < 2) {
+        // ---- the piece of the change map these words read, as bits in LDS
+        const int per = role == 0 ? g.Wo : g.Wp, rows = role == 0 ? g.Ho : g.Hp;
+        const FastDiv &dper = role == 0 ? a.dWo : a.dWp, &drows = role == 0 ? a.dHo : a.dHp;
+        const int total = g.S * rows * per;
+        const int q_lo = b * kCountWords * 64;
+        const int q_hi = (q_lo + kCountWords * 64 < total ? q_lo + kCountWords * 64 : total) - 1;
+        // first and last row (stream * rows + y) of those positions, then their first and last input row
+        const int r_lo = fast_div(q_lo, dper), r_hi = fast_div(q_hi, dper);
+        const int st_lo = fast_div(r_lo, drows), st_hi = fast_div(r_hi, drows);
+        const int y_lo = r_lo - st_lo * rows, y_hi = r_hi - st_hi * rows;
+        const int up = role == 0 ? 1 : 2; // output rows per row of this map
+        const int iy_lo = up * y_lo - g.pad > 0 ? up * y_lo - g.pad : 0;
+        int iy_hi = up * y_hi + (up - 1) - g.pad + g.kh - 1;
+        if (iy_hi > g.H - 1) iy_hi = g.H - 1;
+        const int w_lo = ((st_lo * g.H + iy_lo) * g.W) >> 6;
+        int w_hi = (((st_hi * g.H + iy_hi) * g.W + g.W - 1) >> 6) + 1; // one past the last word
+        if (w_hi > a.chg_words) w_hi = a.chg_words;
+        int nw = w_hi - w_lo;
+        if (nw > kRegionWords) nw = kRegionWords; // the host launches this kernel only if every piece fits
+        const int bit0 = w_lo * 64;
+        if (BYTES) {
+            unsigned char *sB = reinterpret_cast<unsigned char *>(sM);
+            for (int k = tid; k < nw * 8; k += kBlock) sB[k] = (unsigned char)nonzero_bytes(a.chg[(size_t)w_lo * 8 + k]);
+        } else {
+            for (int k = tid; k < nw; k += kBlock) sM[k] = a.chg[w_lo + k];
+        }
+        if (tid < 2) sM[nw + tid] = 0ull;
+        __syncthreads();
+
+        if (i < nwords) { // the same for the lanes that share the word
+            const int p0 = i * 64, p1 = p0 + 64 < total ? p0 + 64 : total;
+            int pos = p0;
+            const int row = fast_div(pos, dper);
+            int x = pos - row * per, st = fast_div(row, drows), y = row - st * rows;
+            while (pos < p1) { // one piece of a row at a time
+                const int len = per - x < p1 - pos ? per - x : p1 - pos;
+                uint64_t bits;
+                if (role == 0) {
+                    Window wd = rows_or(sM, bit0, g, st, y - g.pad, g.kh, x - g.pad, len + g.kw - 1, r, kWordLanes);
+                    spread(wd, g.kw);
+                    bits = wd.w[0];
+                } else {
+                    Window wd = rows_or(sM, bit0, g, st, 2 * y - g.pad, g.kh + 1, 2 * x - g.pad, 2 * len + g.kw - 1, r,
+                                        kWordLanes);
+                    spread(wd, g.kw + 1);
+                    bits = even_bits(wd.w[0]) | (even_bits(wd.w[1]) << 32);
+                }
+                if (len < 64) bits &= (1ull << len) - 1ull;
+                word |= bits << (pos - p0);
+                pos += len;
+                x = 0;
+                if (++y == rows) {
+                    y = 0;
+                    ++st;
+                }
+            }
+        }
+    } else if (i < nwords) {
+        if (BYTES) // lane r packs positions 8r .. 8r+7 (the byte maps are padded to whole words)
+            word = (uint64_t)nonzero_bytes(a.chg[(size_t)i * 8 + r]) << (8 * r);
+        else if (r == 0)
+            word = a.chg[i];
+    }
+    word = word_lanes_or(word);
+    int count = 0;
+    if (r == 0 && i < nwords) {
+        if (role == 0) a.upd[i] = word;
+        if (role == 1) a.pool[i] = word;
+        count = __popcll(word);
+    }
+    if (!groups) return;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) count += __shfl_xor(count, d, 64);
+    if ((tid & 63) == 0) swave[tid >> 6] = count;
+    __syncthreads();
+    if (tid == 0 && b * kCountWords < nwords) {
+        int c = 0;
+        for (int w = 0; w < kBlock / 64; ++w) c += swave[w];
+        groups[b] = c;
+    }
+}
+
+// Words of the change map that kCountWords output words (pooled: every pooled position stands
+// for two rows and columns of outputs) can need at most.
+static long long dilate_region_words(const DilateGeom &g, bool pooled)
+{
+    const long long per = pooled ? g.Wp : g.Wo, rows_per_stream = pooled ? g.Hp : g.Ho;
+    const long long out_rows = (long long)kCountWords * 64 / per + 2; // rows touched by that many positions
+    const long long streams = out_rows / rows_per_stream + 2;         // streams those rows can span
+    // outputs' own rows, the filter's reach at both ends, and per stream boundary crossed the
+    // rows by which a stream's input is taller than the output rows that count here; never more
+    // than all input rows of those streams
+    long long in_rows = (pooled ? 2 : 1) * out_rows + (g.kh + 1) * (streams + 1);
+    if (in_rows > (streams + 1) * g.H) in_rows = (streams + 1) * g.H;
+    return in_rows * g.W / 64 + 2;
+}
+
+bool dilate_counts(const DilateGeom &g)
+{
+    return g.stride == 1 && g.kw >= 1 && g.kw <= 16 && g.kh >= 1 && (g.pool_k == 0 || g.pool_k == 2) &&
+           (long long)g.S * g.H * g.W < (1ll << 31) && (long long)g.S * g.Ho * g.Wo < (1ll << 31) &&
+           dilate_region_words(g, false) <= kRegionWords && (g.pool_k == 0 || dilate_region_words(g, true) <= kRegionWords);
+}
+
+hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, uint64_t *pool_bits,
+                  const DilateGeom &g, const DilateGroups *groups, const Timing &tm)
+{
+    const bool pooled = pool_bits && g.pool_k > 0;
+    if (dilate_counts(g)) {
+        const bool count = groups && groups->upd && groups->chg && (!pooled || groups->pool);
+        DilateWords a;
+        a.chg = chg_bits; a.upd = upd_bits; a.pool = pooled ? pool_bits : nullptr;
+        a.upd_groups = count ? groups->upd : nullptr;
+        a.pool_groups = count ? groups->pool : nullptr;
+        a.chg_groups = count ? groups->chg : nullptr;
+        a.g = g;
+        a.dWo = make_fastdiv(g.Wo); a.dHo = make_fastdiv(g.Ho);
+        a.dWp = make_fastdiv(pooled ? g.Wp : 1); a.dHp = make_fastdiv(pooled ? g.Hp : 1);
+        a.upd_words = (int)(((long long)g.S * g.Ho * g.Wo + 63) / 64);
+        a.pool_words = pooled ? (int)(((long long)g.S * g.Hp * g.Wp + 63) / 64) : 0;
+        a.chg_words = (int)(((long long)g.S * g.H * g.W + 63) / 64);
+        a.upd_blocks = (a.upd_words + kCountWords - 1) / kCountWords;
+        a.pool_blocks = (a.pool_words + kCountWords - 1) / kCountWords;
+        const int grid = a.upd_blocks + a.pool_blocks + (count ? (a.chg_words + kCountWords - 1) / kCountWords : 0);
+        if (g.chg_bytes)
+            launch_kernel(tm, dilate_words_kernel<true>, dim3(grid), dim3(kBlock), 0, st, a);
+        else
+            launch_kernel(tm, dilate_words_kernel<false>, dim3(grid), dim3(kBlock), 0, st, a);
+        return hipGetLastError();
+    }
     const int ub = (g.S * g.Ho * g.Wo + kBlock - 1) / kBlock;
-    const int pb = (pool_bits && g.pool_k > 0) ? (g.S * g.Hp * g.Wp + kBlock - 1) / kBlock : 0;
+    const int pb = pooled ? (g.S * g.Hp * g.Wp + kBlock - 1) / kBlock : 0;
     if (g.chg_bytes)
         launch_kernel(tm, dilate_kernel<true>, dim3(ub + pb), dim3(kBlock), 0, st, chg_bits, upd_bits, pool_bits, g,
                            ub);
@@ -296,8 +554,6 @@ hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, 
 // launch or a cross-workgroup handshake, and it is deterministic), scans its own words'
 // popcounts, expands the bits into an LDS staging buffer and copies that out coalesced.
 // ------------------------------------------------------------------------------------------
-static constexpr int kCompactWords = 128;
-
 struct CompactJobs {
     CompactJob j[3];
 };
@@ -332,17 +588,16 @@ __device__ __forceinline__ uint64_t map_word(const CompactJob &job, int i)
 // workgroup recount all preceding words would dominate (see compact_kernel).
 __global__ __launch_bounds__(kBlock) void compact_count_kernel(CompactJobs jobs)
 {
-    __shared__ int swave[4];
     const CompactJob job = jobs.j[blockIdx.y];
     const int w0 = blockIdx.x * kCompactWords;
     if (w0 >= job.nwords) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int c = 0;
-    if (tid < kCompactWords && w0 + tid < job.nwords) c = __popcll(map_word(job, w0 + tid));
-    c = wave_incl_scan(c, lane);
-    if (lane == 63) swave[wave] = c;
-    __syncthreads();
-    if (tid == 0) job.group_counts[blockIdx.x] = swave[0] + swave[1] + swave[2] + swave[3];
+    const int tid = threadIdx.x;
+    if (tid >= kCompactWords) return;
+    int c = w0 + tid < job.nwords ? __popcll(map_word(job, w0 + tid)) : 0;
+    // one entry per kCountWords consecutive words
+#pragma unroll
+    for (int d = kCountWords / 2; d >= 1; d >>= 1) c += __shfl_xor(c, d, 64);
+    if ((tid & (kCountWords - 1)) == 0) job.group_counts[(w0 + tid) / kCountWords] = c;
 }
 
 template <bool TWO_LEVEL>
@@ -359,7 +614,7 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
     // set bits in all words before this workgroup's
     int before = 0;
     if (TWO_LEVEL) {
-        for (int i = tid; i < (int)blockIdx.x; i += kBlock) before += job.group_counts[i];
+        for (int i = tid; i < (int)blockIdx.x * (kCompactWords / kCountWords); i += kBlock) before += job.group_counts[i];
     } else {
         for (int i = tid; i < w0; i += kBlock) before += __popcll(map_word(job, i));
     }
@@ -391,9 +646,9 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
 
 bool compact_two_level(int nwords) { return nwords > kCompactWords * 48; }
 
-size_t compact_group_count_bytes(int nwords) { return ((size_t)nwords / kCompactWords + 2) * sizeof(int); }
+size_t compact_group_count_bytes(int nwords) { return ((size_t)nwords / kCountWords + 8) * sizeof(int); }
 
-hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, const Timing &tm)
+hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, bool groups_ready, const Timing &tm)
 {
     if (njobs < 1 || njobs > 3) return hipErrorInvalidValue;
     CompactJobs js;
@@ -403,11 +658,15 @@ hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, const Timi
         if (i < njobs && jobs[i].nwords > maxw) maxw = jobs[i].nwords;
     }
     const int gx = (maxw + kCompactWords - 1) / kCompactWords;
-    if (compact_two_level(maxw)) {
+    if (groups_ready || compact_two_level(maxw)) {
         for (int i = 0; i < njobs; ++i)
             if (!jobs[i].group_counts) return hipErrorInvalidValue;
-        launch_kernel(Timing{tm.start, nullptr}, compact_count_kernel, dim3(gx, njobs), dim3(kBlock), 0, st, js);
-        launch_kernel(Timing{nullptr, tm.stop}, compact_kernel<true>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+        if (groups_ready) {
+            launch_kernel(tm, compact_kernel<true>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+        } else {
+            launch_kernel(Timing{tm.start, nullptr}, compact_count_kernel, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+            launch_kernel(Timing{nullptr, tm.stop}, compact_kernel<true>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+        }
     } else {
         launch_kernel(tm, compact_kernel<false>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
     }

@@ -450,6 +450,35 @@ def test_selection_map_size_boundary(W):
 
 
 @pytest.mark.parametrize("hold", [False, True])
+def test_integer_network_large_maps_lists_exact(hold):
+    """Maps beyond 131072 positions at every layer (dilation a word at a time from bit maps and
+    from byte maps, with and without pooling behind, group counts handed to the extraction):
+    integer weights make every layer's lists and maps comparable bit for bit."""
+    layers = [conv(3, 4, 3), conv(4, 4, 5), pool(), conv(4, 4, 7), conv(4, 3, 1, relu=False)]
+    params = _integer_params(layers, 41)
+    H, W = 528, 1036   # 547008 positions, 8547 words: not a multiple of the extraction's group size
+    frames = _integer_video(H, W, 3, 3, 78)
+    taus = [0.5, 1.5, None, 2.5, 3.5]
+    net = cb.CBInfer(layers, params, (3, H, W), taus, hold_reference=hold)
+    orc = oracle.OracleCBNet(layers, params, [0.0 if t is None else t for t in taus], ref_mode=1 if hold else 0)
+    for t, f in enumerate(frames):
+        want = orc.process_frame(f)
+        got = net.process_frame(to_dev(f)).cpu().numpy()[0]
+        for l, L in enumerate(layers):
+            what = "layer %d frame %d" % (l, t)
+            if L.kind == "conv":
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_CHANGED), orc.trace[l]["C"], err_msg=what)
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), orc.trace[l]["U"], err_msg=what)
+            else:
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), orc.trace[l]["P"], err_msg=what)
+            np.testing.assert_array_equal(net.read_map(l, cb.MAP_OUTPUT)[0], orc.out[l], err_msg=what)
+        np.testing.assert_array_equal(got, want)
+        if t:
+            assert 0 < orc.trace[3]["U"].size < (H // 2) * (W // 2) // 10
+    net.destroy()
+
+
+@pytest.mark.parametrize("hold", [False, True])
 def test_sparse_changes_far_apart(hold):
     """A handful of single changed pixels spread over a map of many bitmap words: the wanted ranks
     of a tile then lie in words that are far apart."""
