@@ -487,12 +487,12 @@ __device__ __forceinline__ void stage_rows(float *A, float *B, int r0, int v, co
     }
 }
 
-// BM x BN workgroup tile; the four consumer waves are arranged WM (channels) x WN (pixels).
+// BM x BN workgroup tile; the consumer waves are arranged WM (channels) x WN (pixels).
 //
 // LDS holds a ring of three K slices.  In iteration kc the producers store slice kc+2 and issue
-// the global loads of slice kc+3, while the consumers multiply slice kc and already read the
-// first fragments of slice kc+1, so the matrix pipeline keeps running across the one barrier
-// per slice.
+// the global loads of a slice two or three further on (one per register set), while the consumers
+// multiply slice kc and already read the first fragments of slice kc+1, so the matrix pipeline
+// keeps running across the one barrier per slice.
 template <int DT, int BM, int BN, int WM, int WN>
 __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n, float *smem, const Selection sel)
 {
