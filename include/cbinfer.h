@@ -47,7 +47,14 @@ enum {
     /* Which value the stored "previous input" keeps at positions that were NOT flagged.
      * 0: the previous frame's layer input at every position, the x^(t-1) of the change
      *    detection formula (Section 3.1).  1: only flagged positions are refreshed. */
-    CBINFER_FLAG_HOLD_REFERENCE = 1u
+    CBINFER_FLAG_HOLD_REFERENCE = 1u,
+    /* Write the index lists of every layer (changed inputs, outputs to update, pooled positions
+     * -- the lists of Section 3.1) in every frame, with the dilation and extraction kernels, also
+     * for maps small enough for the multiplication kernel to pick its positions from the update
+     * map itself.  Results are the same; cbinfer_read_list / cbinfer_layer_counts then find the
+     * lists ready instead of extracting them on demand, at the price of two or three more
+     * launches per layer and frame. */
+    CBINFER_FLAG_LISTS_EVERY_FRAME = 2u
 };
 
 /* One operation of the network, in execution order. */

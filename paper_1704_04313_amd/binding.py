@@ -12,6 +12,7 @@ import numpy as np
 OP_CONV, OP_MAXPOOL = 0, 1
 F32, BF16 = 0, 1
 FLAG_HOLD_REFERENCE = 1
+FLAG_LISTS_EVERY_FRAME = 2
 LIST_CHANGED, LIST_UPDATE = 0, 1
 MAP_REFERENCE, MAP_OUTPUT = 0, 1
 STEP_NAMES = ["detect", "dilate", "compact", "gemm", "pool", "output"]
@@ -148,7 +149,7 @@ class CBInfer:
 
     def __init__(self, layers, params, in_shape, tau, *, n_streams: int = 1, hold_reference: bool = False,
                  dense_layers: Sequence[int] = (), caller_workspace: bool = True, dtype: int = F32,
-                 propagate_layers: Sequence[int] = ()):
+                 propagate_layers: Sequence[int] = (), lists_every_frame: bool = False):
         import torch
         self._torch = torch
         self.lib = load_library()
@@ -160,7 +161,7 @@ class CBInfer:
         per_layer = None if np.isscalar(tau) else [(-1.0 if t is None else float(t)) for t in tau]
         global_tau = float(tau) if np.isscalar(tau) else 0.0
         keep: list = []
-        flags = FLAG_HOLD_REFERENCE if hold_reference else 0
+        flags = (FLAG_HOLD_REFERENCE if hold_reference else 0) | (FLAG_LISTS_EVERY_FRAME if lists_every_frame else 0)
         self.dtype = int(dtype)
         net = _describe(self.layers, params, self.in_shape, n_streams, flags, per_layer, set(dense_layers), keep,
                         self.dtype, set(propagate_layers))

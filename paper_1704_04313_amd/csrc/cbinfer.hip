@@ -107,7 +107,8 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
     if (net->n_streams <= 0) return fail(CBINFER_EINVAL, "n_streams must be >= 1");
     if (net->dtype != CBINFER_F32 && net->dtype != CBINFER_BF16)
         return fail(CBINFER_EINVAL, "dtype must be CBINFER_F32 or CBINFER_BF16");
-    if (net->flags & ~(uint32_t)CBINFER_FLAG_HOLD_REFERENCE) return fail(CBINFER_EINVAL, "unknown flag bits");
+    if (net->flags & ~(uint32_t)(CBINFER_FLAG_HOLD_REFERENCE | CBINFER_FLAG_LISTS_EVERY_FRAME))
+        return fail(CBINFER_EINVAL, "unknown flag bits");
     if (need_threshold && !(threshold >= 0.0f && std::isfinite(threshold))) {
         bool all_own = true;
         for (int l = 0; l < net->n_layers; ++l)
@@ -228,7 +229,8 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
     P.flag_words = (long long)(cv.off - P.o_flags) / 8;
     for (Op &op : P.ops)
         if (op.kind == CBINFER_OP_CONV)
-            op.select = words_for((long long)P.S * op.Ho * op.Wo) <= cbk::gemm_select_max_words() &&
+            op.select = !(net->flags & CBINFER_FLAG_LISTS_EVERY_FRAME) &&
+                        words_for((long long)P.S * op.Ho * op.Wo) <= cbk::gemm_select_max_words() &&
                         words_for((long long)P.S * op.H * op.W) <= cbk::gemm_select_max_words();
     P.iota_len = (int)max_px;
     P.o_iota = cv.take((size_t)P.iota_len * 4);

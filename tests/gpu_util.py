@@ -34,7 +34,8 @@ def to_dev(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
 
-def compare_sequence(layers, params, inputs, tau, *, hold=False, dense_layers=(), label="", bf16=False):
+def compare_sequence(layers, params, inputs, tau, *, hold=False, dense_layers=(), label="", bf16=False,
+                     lists_every_frame=False):
     """Feed the same planar inputs (one array [C][H][W] per frame) to the HIP library and to the
     oracle.  Lists and the stored previous input must agree exactly on every frame; stored
     output maps within the float32 tolerance (bf16: both sides store bfloat16, tolerance one
@@ -46,7 +47,7 @@ def compare_sequence(layers, params, inputs, tau, *, hold=False, dense_layers=()
     assert n_conv == 1, "teacher-forced comparison is per convolution layer"
     in_shape = inputs[0].shape
     net = cb.CBInfer(layers, params, in_shape, tau, hold_reference=hold, dense_layers=dense_layers,
-                     dtype=cb.BF16 if bf16 else cb.F32)
+                     dtype=cb.BF16 if bf16 else cb.F32, lists_every_frame=lists_every_frame)
     orc = oracle.OracleCBNet(layers, params, tau, ref_mode=1 if hold else 0, dense_layers=dense_layers, bf16=bf16)
     stats = []
     try:

@@ -69,7 +69,7 @@ def test_invalid_descriptions_are_rejected(case, msg):
     elif case == "streams":
         kw["n_streams"] = 0
     elif case == "flags":
-        kw["flags"] = 6
+        kw["flags"] = 12
     elif case == "shape":
         shape = (3, 0, 8)
     params = make_weights(layers, 0)

@@ -91,12 +91,15 @@ CASES = [
     (16, 64, 3, 3, 3, 0, 31, 29, False),
     (1, 1, 3, 3, 1, 2, 8, 9, False),
     (12, 70, 3, 5, 1, 2, 17, 64, True),
+    (2, 6, 9, 16, 1, 7, 20, 40, False),
+    (3, 5, 6, 4, 1, 2, 23, 31, True),
 ]
 
 
 @pytest.mark.parametrize("case", CASES)
 @pytest.mark.parametrize("hold", [False, True])
-def test_random_geometry(case, hold):
+@pytest.mark.parametrize("lists", [False, True])
+def test_random_geometry(case, hold, lists):
     C, M, kh, kw, s, p, H, W, with_pool = case
     L = conv(C, M, kh, relu=True, stride=s, pad=p)
     L = type(L)("conv", C, M, kh, kw, s, p, True)
@@ -107,7 +110,8 @@ def test_random_geometry(case, hold):
     params = make_weights(layers, 7 + C + M)
     v = _video(H, W, C, sigma=0.004, n_objects=2, seed=C * 100 + M)
     frames = [v.frame(t) for t in range(4)]
-    compare_sequence(layers, params, frames, 0.015, hold=hold, label=str(case))
+    # lists: dilation and index extraction as kernels of their own instead of inside the multiplication
+    compare_sequence(layers, params, frames, 0.015, hold=hold, label=str(case), lists_every_frame=lists)
 
 
 # ------------------------------------------------------------------ degenerate inputs
@@ -329,13 +333,14 @@ def _integer_params(layers, seed):
 
 
 @pytest.mark.parametrize("hold", [False, True])
-def test_integer_network_every_layer_bit_exact(hold):
+@pytest.mark.parametrize("lists", [False, True])
+def test_integer_network_every_layer_bit_exact(hold, lists):
     layers = [conv(3, 8, 3), pool(), conv(8, 20, 3), conv(20, 12, 1), pool(), conv(12, 5, 3, relu=False)]
     params = _integer_params(layers, 31)
     H, W = 24, 36
     frames = _integer_video(H, W, 3, 7, 77)
     taus = [0.5, None, 1.5, 2.5, None, 3.5]
-    net = cb.CBInfer(layers, params, (3, H, W), taus, hold_reference=hold)
+    net = cb.CBInfer(layers, params, (3, H, W), taus, hold_reference=hold, lists_every_frame=lists)
     orc = oracle.OracleCBNet(layers, params, [0.0 if t is None else t for t in taus], ref_mode=1 if hold else 0)
     sparse_seen = False
     for t, f in enumerate(frames):
