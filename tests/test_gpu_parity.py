@@ -454,6 +454,47 @@ def test_selection_map_size_boundary(W):
     assert 0 < stats[-1][0] < 256 * W // 4
 
 
+@pytest.mark.parametrize("case", ["f32", "bf16", "two_streams", "wide"])
+def test_trailing_1x1_layers_bit_exact(case):
+    """Two 1x1 layers at the end of a network (the classification layers of the paper's network
+    are of this kind): each finds its changes while the layer before it writes its output.
+    Integer weights: lists and maps of all layers bit for bit, over several frames, one and two
+    streams, both storage types, then once more in dense mode."""
+    layers = [conv(3, 8, 3), conv(8, 64 if case == "wide" else 6, 1), conv(64 if case == "wide" else 6, 4, 1, relu=False)]
+    params = _integer_params(layers, 51)
+    H, W = 24, 36
+    S = 2 if case == "two_streams" else 1
+    bf16 = case == "bf16"
+    frames = [_integer_video(H, W, 3, 6, 90 + s) for s in range(S)]
+    taus = [0.5, 1.5, 2.5]
+    net = cb.CBInfer(layers, params, (3, H, W), taus, n_streams=S, dtype=cb.BF16 if bf16 else cb.F32)
+    orcs = [oracle.OracleCBNet(layers, params, taus, bf16=bf16) for _ in range(S)]
+    No = H * W
+    sparse_seen = False
+    for t in range(6):
+        want = np.stack([orcs[s].process_frame(frames[s][t]) for s in range(S)])
+        x = np.stack([frames[s][t] for s in range(S)])
+        got = net.process_frame(to_dev(x)).cpu().numpy()
+        for l in range(3):
+            what = "%s layer %d frame %d" % (case, l, t)
+            c_want = np.concatenate([orcs[s].trace[l]["C"] + s * No for s in range(S)])
+            u_want = np.concatenate([orcs[s].trace[l]["U"] + s * No for s in range(S)])
+            np.testing.assert_array_equal(net.read_list(l, cb.LIST_CHANGED), c_want, err_msg=what)
+            np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), u_want, err_msg=what)
+            m = net.read_map(l, cb.MAP_OUTPUT)
+            for s in range(S):
+                np.testing.assert_array_equal(m[s], orcs[s].out[l], err_msg=what)
+            if t and l == 2 and 0 < u_want.size < S * No:
+                sparse_seen = True
+        np.testing.assert_array_equal(got, want)
+    assert sparse_seen
+    net.set_mode(True)
+    dense = net.process_frame(to_dev(np.stack([frames[s][2] for s in range(S)])))
+    want = np.stack([oracle.dense_forward(layers, params, frames[s][2], bf16=bf16)[-1] for s in range(S)])
+    np.testing.assert_array_equal(dense.cpu().numpy(), want)
+    net.destroy()
+
+
 @pytest.mark.parametrize("hold", [False, True])
 def test_integer_network_large_maps_lists_exact(hold):
     """Maps beyond 131072 positions at every layer (dilation a word at a time from bit maps and
