@@ -56,6 +56,7 @@ struct Op {
     int kind = 0;
     // input map
     int C = 0, Cs = 0, H = 0, W = 0;
+    int pix_words = 0;   // CONV: 4-byte words per pixel of the input map (see GemmArgs::pix_words)
     // output map
     int M = 0, Ms = 0, Ho = 0, Wo = 0;
     int kh = 1, kw = 1, stride = 1, pad = 0, relu = 0, dense = 0, propagate = 0;
@@ -160,6 +161,12 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
             op.Wo = (w + 2 * L.pad - L.kw) / L.stride + 1;
             op.K = L.kh * L.kw * op.Cs;
             op.Kpad = round_up(op.K, cbk::gemm_k_multiple(P.dtype));
+            // A large camera frame of a float32 network with 1, 2, 3, 5, 6 or 7 channels is stored without
+            // padding channels: the detection pass then moves only what the method needs.
+            op.pix_words = (l == 0 && cbk::detect_frame_packs(P.dtype, op.C, (long long)P.S * h * w)) ? op.C
+                                                                                                     : op.Cs * (int)esz / 4;
+            if ((long long)P.S * h * w * op.pix_words + 4 > 0x7fffffffll)
+                return fail(CBINFER_EUNSUPPORTED, "layer %d: input map beyond 2^31-1 4-byte words", l);
             op.Mpad = round_up(op.M, cbk::gemm_channel_tile(op.M));
             if (op.Kpad / cbk::gemm_k_multiple(P.dtype) >= (1 << 20))
                 return fail(CBINFER_EUNSUPPORTED, "layer %d: more than 2^20 slices of 128 bytes per filter-matrix row", l);
@@ -201,8 +208,8 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
         if (op.kind == CBINFER_OP_CONV) {
             // Layers behind the first keep no copy of their previous input unless asked to hold it
             // or to run densely: their previous input is the stored output of the op before them.
-            if (l == 0 || ((P.hold || op.dense) && !op.propagate)) op.o_ref = cv.take(in_px * op.Cs * esz + 16);
-            if (l == 0 && P.hold) op.o_cur = cv.take(in_px * op.Cs * esz + 16);
+            if (l == 0 || ((P.hold || op.dense) && !op.propagate)) op.o_ref = cv.take(in_px * op.pix_words * 4 + 16);
+            if (l == 0 && P.hold) op.o_cur = cv.take(in_px * op.pix_words * 4 + 16);
             op.o_wt = cv.take((size_t)op.Mpad * op.Kpad * esz);
             op.o_bias = cv.take((size_t)op.Mpad * 4);
             op.o_taps = cv.take((size_t)op.Kpad / eu * sizeof(int2));
@@ -355,7 +362,7 @@ void build_taps(const Op &op, int dtype, std::vector<int2> &taps)
         if (k < op.K) {
             const int tap = k / op.Cs, c = k - tap * op.Cs;
             const int j = tap / op.kw, i = tap - j * op.kw;
-            t.x = ((j * op.W + i) * op.Cs + c) / eu;
+            t.x = (j * op.W + i) * op.pix_words + c / eu * 4;
             t.y = j | (i << 8) | (1 << 16);
         } else {
             t.x = 0;
@@ -506,8 +513,8 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                 // the same launch zeroes the byte change maps that this frame's kernels fill in
                 uint64_t *flags = s->force_dense ? nullptr : reinterpret_cast<uint64_t *>(s->ws + P.o_flags);
                 HIP_TRY(cbk::detect_frame(st, frame, ref, s->at<void>(op.o_cur), s->at<uint64_t>(op.o_chg), op.C,
-                                          op.Cs / eu, N, S, op.tau, hold, all ? 1 : 0, P.dtype, flags, P.flag_words,
-                                          t.timing()));
+                                          op.Cs / eu, N, S, op.tau, hold, all ? 1 : 0, P.dtype,
+                                          op.pix_words == op.C && op.C % 4 != 0, flags, P.flag_words, t.timing()));
                 x = hold ? s->at<void>(op.o_cur) : ref;
             } else {
                 x = s->at<void>(P.ops[l - 1].o_out);
@@ -560,8 +567,8 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             a.kh = op.kh; a.kw = op.kw; a.S = S;
             a.out = s->at<void>(op.o_out);
             a.N = N; a.H = op.H; a.W = op.W; a.No = No; a.Wo = op.Wo;
-            a.stride = op.stride; a.pad = op.pad; a.V = op.Cs / eu; a.Kpad = op.Kpad;
-            a.zero_unit = S * N * a.V;
+            a.stride = op.stride; a.pad = op.pad; a.pix_words = op.pix_words; a.Kpad = op.Kpad;
+            a.zero_word = S * N * op.pix_words;
             a.M = op.M; a.Mpad = op.Mpad; a.Ms = op.Ms; a.relu = op.relu;
             a.max_pixels = S * No;
             a.partial = s->at<float>(P.o_partial);
@@ -855,7 +862,7 @@ int cbinfer_read_map(cbinfer_state *s, int layer, int which, float *host, size_t
     if (which == CBINFER_MAP_REFERENCE) {
         if (op.kind != CBINFER_OP_CONV) return fail(CBINFER_EINVAL, "layer %d has no stored previous input", layer);
         if (s->force_dense && layer > 0) return fail(CBINFER_ESTATE, "dense mode keeps no previous input for layer %d", layer);
-        C = op.C; Cs = op.Cs; HW = op.H * op.W;
+        C = op.C; Cs = op.pix_words * 4 / cbk::elem_bytes(s->plan.dtype); HW = op.H * op.W;
         // a layer that keeps no copy of its own: its previous input is the stored map that feeds it
         src = op.o_ref != SIZE_MAX ? s->at<void>(op.o_ref) : s->at<void>(s->plan.ops[layer - 1].o_out);
     } else if (which == CBINFER_MAP_OUTPUT) {

@@ -105,8 +105,11 @@ __device__ __forceinline__ uint4 unit_max(const uint4 &a, const uint4 &b)
 // force != 0: every pixel is flagged and ref is not read (first frame / dense mode).
 // clear_words 64-bit words starting at clear are zeroed by the same launch (the byte change maps
 // that later kernels of the frame fill in); they must not overlap bits.
+// packed != 0 (only where detect_frame_packs(dtype, C, S * N)): the stored map holds C float32 values
+// per pixel and no padding channels.
+bool detect_frame_packs(int dtype, int C, long long pixels);
 hipError_t detect_frame(hipStream_t st, const float *frame, void *ref, void *cur, uint64_t *bits, int C, int V,
-                        int N, int S, float tau, int hold, int force, int dtype, uint64_t *clear,
+                        int N, int S, float tau, int hold, int force, int dtype, int packed, uint64_t *clear,
                         long long clear_words, const Timing &tm = Timing());
 
 // Map against map (layers fed by a stored output map).  x and ref are [S*N][V units].
@@ -178,11 +181,11 @@ hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, bool group
 // ---- gathered matrix generation + multiplication + output update (Section 3.1) -------------
 struct GemmArgs {
     int dtype;          // kF32 or kBF16: storage of x, wt and out
-    const void *x;      // input map [S*N][V units], followed by at least one unit of zeros
+    const void *x;      // input map, pix_words 4-byte words per pixel, followed by at least 16 bytes of zeros
     const void *wt;     // filter matrix, [Mpad][Kpad], k = (j*kw + i)*Cs + c, zero padded
     const float *bias;  // [Mpad] float32
     const int2 *taps;   // one entry per 16-byte unit of a filter-matrix row:
-                        //   .x = offset of the tap, in units, from the window origin in the input map,
+                        //   .x = offset of that unit, in 4-byte words, from the window origin in the input map,
                         //   .y = j | i << 8 | valid << 16
     const int *list;    // output pixels to recompute
     const int *count;   // their number (device)
@@ -205,8 +208,10 @@ struct GemmArgs {
     void *out;          // stored output map [S*No][Ms]
     int N, H, W, No, Wo, stride, pad;
     FastDiv dNo, dWo, dHo, dNk, dGrid; // by No, Wo, No / Wo, Kpad / gemm_k_multiple(dtype) and grid (gemm_set_divisors)
-    int V;              // units per input pixel
-    int zero_unit;      // index of a 16-byte unit of zeros relative to x (gathers outside the image read it)
+    int pix_words;      // 4-byte words per input pixel: a multiple of four (whole 16-byte units), or the channel
+                        // count of a float32 map stored without padding (units then start at any word and
+                        // run into the next pixel's channels, which meet zero filter weights)
+    int zero_word;      // word index, relative to x, of 16 bytes of zeros (gathers outside the image read them)
     int Kpad;           // filter-matrix row length in elements, a multiple of gemm_k_multiple(dtype)
     int M, Mpad, Ms, relu;
     int max_pixels;     // upper bound of *count

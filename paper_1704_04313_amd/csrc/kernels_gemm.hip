@@ -38,6 +38,7 @@
 namespace cbk {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef floatx4 floatx4_a4 __attribute__((aligned(4))); // a 16-byte unit that starts at any 4-byte word
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
@@ -444,7 +445,7 @@ template <int PA>
 __device__ __forceinline__ void gather_rows(const GemmArgs &a, const int2 tp, const int (&iy0)[PA],
                                             const int (&ix0)[PA], const int (&base)[PA], floatx4 (&ra)[PA])
 {
-    const floatx4 *x = static_cast<const floatx4 *>(a.x);
+    const float *x = static_cast<const float *>(a.x); // 4-byte words, whatever the storage type
     const int tj = tp.y & 0xff, ti = (tp.y >> 8) & 0xff;
     const bool tv = (tp.y >> 16) != 0;
 #pragma unroll
@@ -452,8 +453,8 @@ __device__ __forceinline__ void gather_rows(const GemmArgs &a, const int2 tp, co
         const bool ok = tv && (unsigned)(iy0[ps] + tj) < (unsigned)a.H && (unsigned)(ix0[ps] + ti) < (unsigned)a.W;
         // outside the image (or no pixel in this row): the zero unit kept behind the map, so that the
         // load needs no predication and the registers no clearing
-        const unsigned idx = ok ? (unsigned)(base[ps] + tp.x) : (unsigned)a.zero_unit;
-        ra[ps] = x[idx];
+        const unsigned idx = ok ? (unsigned)(base[ps] + tp.x) : (unsigned)a.zero_word;
+        ra[ps] = *reinterpret_cast<const floatx4_a4 *>(x + idx);
     }
 }
 
@@ -612,7 +613,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                     const int qy = fast_div(q, a.dWo), qx = q - qy * a.Wo;
                     iy0[ps] = qy * a.stride - a.pad;
                     ix0[ps] = qx * a.stride - a.pad;
-                    base[ps] = ((st * a.H + iy0[ps]) * a.W + ix0[ps]) * a.V;
+                    base[ps] = ((st * a.H + iy0[ps]) * a.W + ix0[ps]) * a.pix_words;
                 } else {
                     iy0[ps] = -(1 << 28);
                     ix0[ps] = -(1 << 28);
@@ -1024,7 +1025,7 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm)
 {
     const int bm = gemm_channel_tile(a.M);
     const int eu = elems_per_unit(a.dtype);
-    if (a.Mpad % bm != 0 || a.Kpad % gemm_k_multiple(a.dtype) != 0 || a.Ms % eu != 0 || a.V < 1 || !a.partial ||
+    if (a.Mpad % bm != 0 || a.Kpad % gemm_k_multiple(a.dtype) != 0 || a.Ms % eu != 0 || a.pix_words < 1 || !a.partial ||
         !a.tickets || a.grid < 8 || (a.grid & 7) || a.grid > kMaxGrid)
         return hipErrorInvalidValue;
     // the divisors must belong to these arguments, and the schedule's 32-bit arithmetic must hold

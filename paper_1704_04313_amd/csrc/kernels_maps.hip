@@ -75,13 +75,150 @@ __global__ __launch_bounds__(kBlock) void detect_frame_kernel(const float *__res
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// The same for a float32 map without padding channels (C = 1, 2, 3, 5, 6 or 7 values per pixel):
+// the stored input then moves exactly the bytes the method needs (with three channels 12
+// instead of 16 per pixel and direction).  A wave takes 256 consecutive pixels = 64 * C float4
+// of the map.  Lane l reads its pixels l, l + 64, ... from the frame's planes as before and
+// puts them into LDS in map order; from there every lane takes the float4 l, l + 64, ... of the
+// wave's piece, compares them with the stored ones, marks the pixels of the elements that differ
+// in an LDS flag array, and after that each lane collects the flags of its own pixels for the
+// bitmap words.  All global accesses stay full-wave coalesced.
+// ------------------------------------------------------------------------------------------
+static constexpr int kPackMaxC = 7;
+
+template <int HOLD>
+__global__ __launch_bounds__(kBlock) void detect_frame_packed_kernel(const float *__restrict__ frame,
+                                                                     float *__restrict__ ref, float *__restrict__ cur,
+                                                                     uint64_t *__restrict__ bits, int C, int N,
+                                                                     int total, float tau, int force,
+                                                                     uint64_t *__restrict__ clear, long long clear_words)
+{
+    constexpr int P = kDetectPix;       // pixels per lane
+    constexpr int WP = 64 * P;          // pixels per wave
+    constexpr int WAVES = kBlock / 64;
+    __shared__ __align__(16) float sX[WAVES][WP * kPackMaxC];
+    __shared__ int sF[WAVES][WP];
+    const int tid = blockIdx.x * kBlock + threadIdx.x;
+    for (long long i = tid; i < clear_words; i += (long long)gridDim.x * kBlock) clear[i] = 0ull;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int p0 = (tid >> 6) * WP; // the wave's first pixel
+    float *sx = sX[wave];
+    int *sf = sF[wave];
+    const long long e0 = (long long)p0 * C;          // the wave's first map element (a multiple of 4)
+    const long long e_end = (long long)total * C;    // elements of the whole map
+    const int inv = (65536 + C - 1) / C;             // e / C == (e * inv) >> 16 for e < 256 * 7, C <= 7
+    // all global loads first: the frame's values of this lane's pixels and its float4 of the stored map
+    float fv[P][kPackMaxC];
+    float4 xv[kPackMaxC], rv[kPackMaxC];
+#pragma unroll
+    for (int k = 0; k < P; ++k) {
+        const int g = p0 + lane + 64 * k;
+        const int st = g < total ? g / N : 0;
+        const float *fp = frame + (size_t)st * C * N + (g < total ? g - st * N : 0);
+#pragma unroll
+        for (int c = 0; c < kPackMaxC; ++c) fv[k][c] = (c < C && g < total) ? fp[(size_t)c * N] : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < kPackMaxC; ++j) {
+        rv[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (j >= C || force) continue;
+        const long long e = e0 + 4ll * (lane + 64 * j);
+        if (e + 4 <= e_end) {
+            rv[j] = *reinterpret_cast<const float4 *>(ref + e);
+        } else {
+            if (e + 0 < e_end) rv[j].x = ref[e + 0];
+            if (e + 1 < e_end) rv[j].y = ref[e + 1];
+            if (e + 2 < e_end) rv[j].z = ref[e + 2];
+        }
+    }
+    // frame values -> LDS in map order (pixel-major, C values each), back as float4 of the map
+#pragma unroll
+    for (int k = 0; k < P; ++k) {
+        const int pl = lane + 64 * k;
+        sf[pl] = (force && p0 + pl < total) ? 1 : 0;
+#pragma unroll
+        for (int c = 0; c < kPackMaxC; ++c)
+            if (c < C) sx[pl * C + c] = fv[k][c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kPackMaxC; ++j)
+        xv[j] = j < C ? *reinterpret_cast<const float4 *>(sx + 4 * (lane + 64 * j)) : make_float4(0.f, 0.f, 0.f, 0.f);
+    if (!force) {
+#pragma unroll
+        for (int j = 0; j < kPackMaxC; ++j) {
+            if (j >= C) break;
+            const int el = 4 * (lane + 64 * j); // element inside the wave's piece
+            const long long e = e0 + el;
+            if (e + 0 < e_end && fabsf(xv[j].x - rv[j].x) > tau) sf[((el + 0) * inv) >> 16] = 1;
+            if (e + 1 < e_end && fabsf(xv[j].y - rv[j].y) > tau) sf[((el + 1) * inv) >> 16] = 1;
+            if (e + 2 < e_end && fabsf(xv[j].z - rv[j].z) > tau) sf[((el + 2) * inv) >> 16] = 1;
+            if (e + 3 < e_end && fabsf(xv[j].w - rv[j].w) > tau) sf[((el + 3) * inv) >> 16] = 1;
+        }
+    }
+    __syncthreads();
+    // the stored map: everything (hold: the current frame everywhere, the reference where flagged)
+#pragma unroll
+    for (int j = 0; j < kPackMaxC; ++j) {
+        if (j >= C) break;
+        const int el = 4 * (lane + 64 * j);
+        const long long e = e0 + el;
+        if (e >= e_end) continue;
+        float4 nr = xv[j];
+        if (HOLD) {
+            if (!sf[((el + 0) * inv) >> 16]) nr.x = rv[j].x;
+            if (!sf[((el + 1) * inv) >> 16]) nr.y = rv[j].y;
+            if (!sf[((el + 2) * inv) >> 16]) nr.z = rv[j].z;
+            if (!sf[((el + 3) * inv) >> 16]) nr.w = rv[j].w;
+        }
+        if (e + 4 <= e_end) {
+            if (HOLD) *reinterpret_cast<float4 *>(cur + e) = xv[j];
+            *reinterpret_cast<float4 *>(ref + e) = nr;
+        } else { // the map's last elements: nothing may be written behind them
+            const float xs[3] = {xv[j].x, xv[j].y, xv[j].z}, ns[3] = {nr.x, nr.y, nr.z};
+            for (int i = 0; i < 3; ++i)
+                if (e + i < e_end) {
+                    if (HOLD) cur[e + i] = xs[i];
+                    ref[e + i] = ns[i];
+                }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < P; ++k) {
+        const int pl = lane + 64 * k, g = p0 + pl;
+        const uint64_t word = __ballot(sf[pl] != 0);
+        if (lane == 0 && g < total) bits[g >> 6] = word;
+    }
+}
+
+// Frames of fewer pixels stay with whole units: their pass is bound by latency, not by bytes, and
+// the way through LDS costs more than the padding.
+static constexpr long long kPackMinPixels = 1 << 18;
+
+bool detect_frame_packs(int dtype, int C, long long pixels)
+{
+    return dtype == kF32 && C % 4 != 0 && C <= kPackMaxC && pixels >= kPackMinPixels;
+}
+
 hipError_t detect_frame(hipStream_t st, const float *frame, void *ref, void *cur, uint64_t *bits, int C, int V,
-                        int N, int S, float tau, int hold, int force, int dtype, uint64_t *clear,
+                        int N, int S, float tau, int hold, int force, int dtype, int packed, uint64_t *clear,
                         long long clear_words, const Timing &tm)
 {
     if (!clear) clear_words = 0;
     const int total = S * N;
     const int grid = (total + kBlock * kDetectPix - 1) / (kBlock * kDetectPix);
+    if (packed) {
+        if (!detect_frame_packs(dtype, C, total)) return hipErrorInvalidValue;
+        float *r = static_cast<float *>(ref), *c = static_cast<float *>(cur);
+        if (hold)
+            launch_kernel(tm, detect_frame_packed_kernel<1>, dim3(grid), dim3(kBlock), 0, st, frame, r, c, bits, C, N, total,
+                          tau, force, clear, clear_words);
+        else
+            launch_kernel(tm, detect_frame_packed_kernel<0>, dim3(grid), dim3(kBlock), 0, st, frame, r, c, bits, C, N, total,
+                          tau, force, clear, clear_words);
+        return hipGetLastError();
+    }
     uint4 *r = static_cast<uint4 *>(ref), *c = static_cast<uint4 *>(cur);
 #define CBK_LAUNCH(DT_, HOLD_)                                                                                  \
     launch_kernel(tm, detect_frame_kernel<DT_, HOLD_>, dim3(grid), dim3(kBlock), 0, st, frame, r, c, bits, C, \

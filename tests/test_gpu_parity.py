@@ -454,6 +454,22 @@ def test_selection_map_size_boundary(W):
     assert 0 < stats[-1][0] < 256 * W // 4
 
 
+@pytest.mark.parametrize("C", [1, 2, 3, 5, 6, 7])
+@pytest.mark.parametrize("hold", [False, True])
+def test_large_frames_stored_without_padding_channels(C, hold):
+    """From 2^18 pixels on a float32 frame whose channel count is no multiple of four is stored
+    with C values per pixel (the detection pass then moves no padding); the gathers read 16 bytes
+    from any 4-byte word.  Frame size chosen so that the last wave and the last float4 of the map
+    are ragged."""
+    H, W = 509, 517
+    layers = [conv(C, 4, 3)]
+    params = make_weights(layers, 60 + C)
+    v = _video(H, W, C, sigma=0.003, n_objects=5, seed=700 + C, size_range=(10, 30))
+    frames = [v.frame(t) for t in range(3)]
+    stats = compare_sequence(layers, params, frames, 0.02, hold=hold, label="C=%d" % C)
+    assert 0 < stats[-1][0] < H * W // 4
+
+
 @pytest.mark.parametrize("case", ["f32", "bf16", "two_streams", "wide"])
 def test_trailing_1x1_layers_bit_exact(case):
     """Two 1x1 layers at the end of a network (the classification layers of the paper's network
