@@ -104,6 +104,10 @@ static constexpr int kStages = 3;   // K slices resident in LDS
 #ifndef CBK_THREE_SETS_UNITS
 #define CBK_THREE_SETS_UNITS 6 // tiles whose producer threads load at most this many 16-byte units per slice
 #endif
+#ifndef CBK_EPI_CHUNK
+#define CBK_EPI_CHUNK 4
+#endif
+static constexpr int kEpiChunk = CBK_EPI_CHUNK; // accumulators whose replaced values are loaded together in the output update
 #ifndef CBK_MIN_ITERS
 #define CBK_MIN_ITERS 8
 #endif
@@ -809,38 +813,43 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             bool changed[TP];
 #pragma unroll
             for (int i = 0; i < TP; ++i) changed[i] = false;
+            float4 bias[TC];
 #pragma unroll
-            for (int j = 0; j < TC; ++j) {
-                const int ch = mt * BM + wch0 + j * 16 + lk * 4;
-                const float4 bv = *reinterpret_cast<const float4 *>(a.bias + ch);
-                // The values about to be replaced are loaded a few positions at a time before the
-                // stores of those positions (the compiler cannot move a load across a store to the
-                // same map, and one round trip to memory per accumulator would line up at the very
-                // end of the kernel).
-                constexpr int CH = TP < 2 ? 1 : 2;
+            for (int j = 0; j < TC; ++j) bias[j] = *reinterpret_cast<const float4 *>(a.bias + mt * BM + wch0 + j * 16 + lk * 4);
+            // The values about to be replaced are loaded kEpiChunk accumulators at a time before the
+            // stores of those accumulators (the compiler cannot move a load across a store to the
+            // same map, and one round trip to memory per accumulator would line up at the very end
+            // of the kernel).  Accumulator q covers channels of block q / TP at the positions of block q % TP.
+            constexpr int CH = TC * TP < kEpiChunk ? TC * TP : kEpiChunk;
+            static_assert((TC * TP) % CH == 0, "whole chunks");
 #pragma unroll
-                for (int i0 = 0; i0 < TP; i0 += CH) {
+            for (int q0 = 0; q0 < TC * TP; q0 += CH) {
                 uintx4 replaced[CH];
                 if (detect) {
 #pragma unroll
-                    for (int ii = 0; ii < CH; ++ii) {
-                        const int g = sU[wpx0 + (i0 + ii) * 16 + lrow];
-                        replaced[ii] = (uintx4){0u, 0u, 0u, 0u};
+                    for (int qq = 0; qq < CH; ++qq) {
+                        const int j = (q0 + qq) / TP, i = (q0 + qq) % TP;
+                        const int ch = mt * BM + wch0 + j * 16 + lk * 4;
+                        const int g = sU[wpx0 + i * 16 + lrow];
+                        replaced[qq] = (uintx4){0u, 0u, 0u, 0u};
                         if (g >= 0 && ch < a.Ms) {
                             if constexpr (DT == kBF16) {
                                 const uint2 v = *reinterpret_cast<const uint2 *>(static_cast<const unsigned short *>(a.out) +
                                                                                  (size_t)g * a.Ms + ch);
-                                replaced[ii][0] = v.x;
-                                replaced[ii][1] = v.y;
+                                replaced[qq][0] = v.x;
+                                replaced[qq][1] = v.y;
                             } else {
-                                replaced[ii] = *reinterpret_cast<const uintx4 *>(static_cast<const float *>(a.out) +
+                                replaced[qq] = *reinterpret_cast<const uintx4 *>(static_cast<const float *>(a.out) +
                                                                                  (size_t)g * a.Ms + ch);
                             }
                         }
                     }
                 }
 #pragma unroll
-                for (int i = i0; i < i0 + CH; ++i) {
+                for (int qq = 0; qq < CH; ++qq) {
+                    const int j = (q0 + qq) / TP, i = (q0 + qq) % TP;
+                    const int ch = mt * BM + wch0 + j * 16 + lk * 4;
+                    const float4 bv = bias[j];
                     const int g = sU[wpx0 + i * 16 + lrow];
                     if (g >= 0 && ch < a.Ms) {
                         float4 o;
@@ -862,7 +871,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                             nv.x = (unsigned)bf16_bits(o.x) | ((unsigned)bf16_bits(o.y) << 16);
                             nv.y = (unsigned)bf16_bits(o.z) | ((unsigned)bf16_bits(o.w) << 16);
                             if (detect) {
-                                const uint2 ov = make_uint2(replaced[i - i0][0], replaced[i - i0][1]);
+                                const uint2 ov = make_uint2(replaced[qq][0], replaced[qq][1]);
                                 changed[i] |= fabsf(bf16_value(nv.x & 0xffff) - bf16_value(ov.x & 0xffff)) > a.next_tau ||
                                               fabsf(bf16_value(nv.x >> 16) - bf16_value(ov.x >> 16)) > a.next_tau ||
                                               fabsf(bf16_value(nv.y & 0xffff) - bf16_value(ov.y & 0xffff)) > a.next_tau ||
@@ -872,15 +881,14 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                         } else {
                             float4 *dst = reinterpret_cast<float4 *>(static_cast<float *>(a.out) + (size_t)g * a.Ms + ch);
                             if (detect) {
-                                const float4 ov = make_float4(__uint_as_float(replaced[i - i0][0]), __uint_as_float(replaced[i - i0][1]),
-                                                              __uint_as_float(replaced[i - i0][2]), __uint_as_float(replaced[i - i0][3]));
+                                const float4 ov = make_float4(__uint_as_float(replaced[qq][0]), __uint_as_float(replaced[qq][1]),
+                                                              __uint_as_float(replaced[qq][2]), __uint_as_float(replaced[qq][3]));
                                 changed[i] |= fabsf(o.x - ov.x) > a.next_tau || fabsf(o.y - ov.y) > a.next_tau ||
                                               fabsf(o.z - ov.z) > a.next_tau || fabsf(o.w - ov.w) > a.next_tau;
                             }
                             *dst = o;
                         }
                     }
-                }
                 }
             }
             if (a.next_flags) {
