@@ -817,18 +817,30 @@ hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, bool group
 // One pooled position g, one unit v of its channels: the maximum over the window, the optional
 // comparison with the value it replaces (all lanes of the wave must call this together: the
 // flag of a position is combined across its V lanes with a ballot when V is a power of two).
+// Geometry of a pooling launch; the divisors are the invariant ones of its index arithmetic
+// (integer division is emulated on this hardware, and these kernels are short).
+struct PoolGeom {
+    int V, k, Wo, No, Wp, Np;
+    FastDiv dV, dNp, dWp;
+};
+static PoolGeom pool_geom(int V, int k, int Wo, int No, int Wp, int Np)
+{
+    return {V, k, Wo, No, Wp, Np, make_fastdiv(V), make_fastdiv(Np), make_fastdiv(Wp)};
+}
+
 template <int DT>
 __device__ __forceinline__ void pool_unit(bool active, int g, int v, const uint4 *__restrict__ in,
-                                          uint4 *__restrict__ pooled, int V, int k, int Wo, int No, int Wp, int Np,
+                                          uint4 *__restrict__ pooled, const PoolGeom &pg,
                                           unsigned char *__restrict__ next_flags, float next_tau, int next_force)
 {
+    const int V = pg.V, k = pg.k, Wo = pg.Wo, No = pg.No, Wp = pg.Wp, Np = pg.Np;
     const int lane = threadIdx.x & 63;
     const bool pow2 = (V & (V - 1)) == 0 && V <= 64;
     uint4 m = make_uint4(0u, 0u, 0u, 0u);
     bool f = false;
     if (active) {
-        const int st = g / Np, pp = g - st * Np;
-        const int py = pp / Wp, px = pp - py * Wp;
+        const int st = fast_div(g, pg.dNp), pp = g - st * Np;
+        const int py = fast_div(pp, pg.dWp), px = pp - py * Wp;
         const long long base = (long long)st * No + (long long)(py * k) * Wo + px * k;
         m = in[base * V + v];
         for (int j = 0; j < k; ++j)
@@ -857,20 +869,19 @@ template <int DT>
 __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restrict__ list,
                                                              const int *__restrict__ count,
                                                              const uint4 *__restrict__ in,
-                                                             uint4 *__restrict__ pooled, int V, int k, int Wo,
-                                                             int No, int Wp, int Np,
+                                                             uint4 *__restrict__ pooled, PoolGeom pg,
                                                              unsigned char *__restrict__ next_flags,
                                                              float next_tau, int next_force)
 {
-    const long long total = (long long)(*count) * V;
-    const long long step = (long long)gridDim.x * kBlock;
+    const int total = *count * pg.V; // units: below 2^31 (the maps hold fewer 4-byte words than that)
+    const int step = (int)gridDim.x * kBlock;
     // whole waves iterate together (the last round with some lanes inactive)
-    for (long long i0 = (long long)blockIdx.x * kBlock; i0 < total; i0 += step) {
-        const long long idx = i0 + threadIdx.x;
+    for (int i0 = (int)blockIdx.x * kBlock; i0 < total; i0 += step) {
+        const int idx = i0 + (int)threadIdx.x;
         const bool active = idx < total;
-        const int u = active ? (int)(idx / V) : 0, v = active ? (int)(idx - (long long)u * V) : 0;
+        const int u = active ? fast_div(idx, pg.dV) : 0, v = active ? idx - u * pg.V : 0;
         const int g = active ? list[u] : 0;
-        pool_unit<DT>(active, g, v, in, pooled, V, k, Wo, No, Wp, Np, next_flags, next_tau, next_force);
+        pool_unit<DT>(active, g, v, in, pooled, pg, next_flags, next_tau, next_force);
     }
 }
 
@@ -878,32 +889,31 @@ template <int DT>
 __global__ __launch_bounds__(kBlock) void pool_masked_kernel(const uint64_t *__restrict__ bits, int from_outputs,
                                                              int total_px,
                                                              const uint4 *__restrict__ in,
-                                                             uint4 *__restrict__ pooled, int V, int k, int Wo,
-                                                             int No, int Wp, int Np,
+                                                             uint4 *__restrict__ pooled, PoolGeom pg,
                                                              unsigned char *__restrict__ next_flags,
                                                              float next_tau, int next_force)
 {
-    const long long total = (long long)total_px * V;
-    const long long step = (long long)gridDim.x * kBlock;
-    for (long long i0 = (long long)blockIdx.x * kBlock; i0 < total; i0 += step) {
-        const long long idx = i0 + threadIdx.x;
+    const int total = total_px * pg.V;
+    const int step = (int)gridDim.x * kBlock;
+    for (int i0 = (int)blockIdx.x * kBlock; i0 < total; i0 += step) {
+        const int idx = i0 + (int)threadIdx.x;
         bool active = idx < total;
-        const int g = active ? (int)(idx / V) : 0, v = active ? (int)(idx - (long long)g * V) : 0;
+        const int g = active ? fast_div(idx, pg.dV) : 0, v = active ? idx - g * pg.V : 0;
         if (active) {
             if (from_outputs) {
-                const int st = g / Np, pp = g - st * Np;
-                const int py = pp / Wp, px = pp - py * Wp;
+                const int st = fast_div(g, pg.dNp), pp = g - st * pg.Np;
+                const int py = fast_div(pp, pg.dWp), px = pp - py * pg.Wp;
                 bool any = false;
-                for (int j = 0; j < k; ++j) {
-                    const long long q0 = (long long)st * No + (long long)(py * k + j) * Wo + px * k;
-                    for (int i = 0; i < k; ++i) any |= ((bits[(q0 + i) >> 6] >> ((q0 + i) & 63)) & 1ull) != 0ull;
+                for (int j = 0; j < pg.k; ++j) {
+                    const int q0 = st * pg.No + (py * pg.k + j) * pg.Wo + px * pg.k;
+                    for (int i = 0; i < pg.k; ++i) any |= ((bits[(q0 + i) >> 6] >> ((q0 + i) & 63)) & 1ull) != 0ull;
                 }
                 active = any;
             } else {
                 active = ((bits[g >> 6] >> (g & 63)) & 1ull) != 0ull;
             }
         }
-        pool_unit<DT>(active, g, v, in, pooled, V, k, Wo, No, Wp, Np, next_flags, next_tau, next_force);
+        pool_unit<DT>(active, g, v, in, pooled, pg, next_flags, next_tau, next_force);
     }
 }
 
@@ -912,17 +922,19 @@ hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int ma
                        float next_tau, int next_force, int dtype, const Timing &tm)
 {
     long long work = (long long)max_count * V;
+    if (work >= (1ll << 30) || V < 1 || Np < 1 || Wp < 1) return hipErrorInvalidValue; // 32-bit indices, with room for the grid stride
+    const PoolGeom pg = pool_geom(V, k, Wo, No, Wp, Np);
     long long grid = (work + kBlock - 1) / kBlock;
     if (grid > 2048) grid = 2048;
     if (grid < 1) grid = 1;
     const uint4 *i4 = static_cast<const uint4 *>(in);
     uint4 *p4 = static_cast<uint4 *>(pooled);
     if (dtype == kBF16)
-        launch_kernel(tm, pool_sparse_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, list, count, i4, p4, V, k,
-                           Wo, No, Wp, Np, next_flags, next_tau, next_force);
+        launch_kernel(tm, pool_sparse_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, list, count, i4, p4, pg,
+                      next_flags, next_tau, next_force);
     else
-        launch_kernel(tm, pool_sparse_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, list, count, i4, p4, V, k,
-                           Wo, No, Wp, Np, next_flags, next_tau, next_force);
+        launch_kernel(tm, pool_sparse_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, list, count, i4, p4, pg,
+                      next_flags, next_tau, next_force);
     return hipGetLastError();
 }
 
@@ -931,17 +943,19 @@ hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int from_outputs, i
                        float next_tau, int next_force, int dtype, const Timing &tm)
 {
     long long work = (long long)total * V;
+    if (work >= (1ll << 30) || V < 1 || Np < 1 || Wp < 1) return hipErrorInvalidValue; // 32-bit indices, with room for the grid stride
+    const PoolGeom pg = pool_geom(V, k, Wo, No, Wp, Np);
     long long grid = (work + kBlock - 1) / kBlock;
     if (grid > 4096) grid = 4096;
     if (grid < 1) grid = 1;
     const uint4 *i4 = static_cast<const uint4 *>(in);
     uint4 *p4 = static_cast<uint4 *>(pooled);
     if (dtype == kBF16)
-        launch_kernel(tm, pool_masked_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, bits, from_outputs, total, i4, p4, V, k,
-                           Wo, No, Wp, Np, next_flags, next_tau, next_force);
+        launch_kernel(tm, pool_masked_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, bits, from_outputs, total, i4, p4,
+                      pg, next_flags, next_tau, next_force);
     else
-        launch_kernel(tm, pool_masked_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, bits, from_outputs, total, i4, p4, V, k,
-                           Wo, No, Wp, Np, next_flags, next_tau, next_force);
+        launch_kernel(tm, pool_masked_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, bits, from_outputs, total, i4, p4,
+                      pg, next_flags, next_tau, next_force);
     return hipGetLastError();
 }
 
