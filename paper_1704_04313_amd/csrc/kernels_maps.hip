@@ -21,7 +21,8 @@ __global__ __launch_bounds__(kBlock) void detect_frame_kernel(const float *__res
                                                               uint4 *__restrict__ ref, uint4 *__restrict__ cur,
                                                               uint64_t *__restrict__ bits, int C, int V, int N,
                                                               int total, float tau, int force,
-                                                              uint64_t *__restrict__ clear, long long clear_words)
+                                                              uint64_t *__restrict__ clear, long long clear_words,
+                                                              FastDiv dN)
 {
     constexpr int E = Unit<DT>::N;
     constexpr int P = kDetectPix;
@@ -36,7 +37,7 @@ __global__ __launch_bounds__(kBlock) void detect_frame_kernel(const float *__res
         const int g = g0 + 64 * k;
         ok[k] = g < total;
         flag[k] = false;
-        const int st = ok[k] ? g / N : 0;
+        const int st = ok[k] ? fast_div(g, dN) : 0;
         fp[k] = frame + (size_t)st * C * N + (ok[k] ? g - st * N : 0);
     }
     for (int u = 0; u < V; ++u) {
@@ -92,7 +93,8 @@ __global__ __launch_bounds__(kBlock) void detect_frame_packed_kernel(const float
                                                                      float *__restrict__ ref, float *__restrict__ cur,
                                                                      uint64_t *__restrict__ bits, int C, int N,
                                                                      int total, float tau, int force,
-                                                                     uint64_t *__restrict__ clear, long long clear_words)
+                                                                     uint64_t *__restrict__ clear, long long clear_words,
+                                                                     FastDiv dN)
 {
     constexpr int P = kDetectPix;       // pixels per lane
     constexpr int WP = 64 * P;          // pixels per wave
@@ -114,7 +116,7 @@ __global__ __launch_bounds__(kBlock) void detect_frame_packed_kernel(const float
 #pragma unroll
     for (int k = 0; k < P; ++k) {
         const int g = p0 + lane + 64 * k;
-        const int st = g < total ? g / N : 0;
+        const int st = g < total ? fast_div(g, dN) : 0;
         const float *fp = frame + (size_t)st * C * N + (g < total ? g - st * N : 0);
 #pragma unroll
         for (int c = 0; c < kPackMaxC; ++c) fv[k][c] = (c < C && g < total) ? fp[(size_t)c * N] : 0.f;
@@ -207,22 +209,23 @@ hipError_t detect_frame(hipStream_t st, const float *frame, void *ref, void *cur
 {
     if (!clear) clear_words = 0;
     const int total = S * N;
+    const FastDiv dN = make_fastdiv(N > 0 ? N : 1);
     const int grid = (total + kBlock * kDetectPix - 1) / (kBlock * kDetectPix);
     if (packed) {
         if (!detect_frame_packs(dtype, C, total)) return hipErrorInvalidValue;
         float *r = static_cast<float *>(ref), *c = static_cast<float *>(cur);
         if (hold)
             launch_kernel(tm, detect_frame_packed_kernel<1>, dim3(grid), dim3(kBlock), 0, st, frame, r, c, bits, C, N, total,
-                          tau, force, clear, clear_words);
+                          tau, force, clear, clear_words, dN);
         else
             launch_kernel(tm, detect_frame_packed_kernel<0>, dim3(grid), dim3(kBlock), 0, st, frame, r, c, bits, C, N, total,
-                          tau, force, clear, clear_words);
+                          tau, force, clear, clear_words, dN);
         return hipGetLastError();
     }
     uint4 *r = static_cast<uint4 *>(ref), *c = static_cast<uint4 *>(cur);
 #define CBK_LAUNCH(DT_, HOLD_)                                                                                  \
     launch_kernel(tm, detect_frame_kernel<DT_, HOLD_>, dim3(grid), dim3(kBlock), 0, st, frame, r, c, bits, C, \
-                       V, N, total, tau, force, clear, clear_words)
+                       V, N, total, tau, force, clear, clear_words, dN)
     if (dtype == kBF16) {
         if (hold) CBK_LAUNCH(kBF16, 1); else CBK_LAUNCH(kBF16, 0);
     } else {
@@ -966,37 +969,36 @@ hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int from_outputs, i
 template <int DT>
 __global__ __launch_bounds__(kBlock) void map_to_planar_kernel(const uint4 *__restrict__ map,
                                                                float *__restrict__ planar, int M, int V,
-                                                               int No, long long total)
+                                                               int No, int total, FastDiv dNo, FastDiv dV)
 {
     constexpr int E = Unit<DT>::N;
-    for (long long idx = (long long)blockIdx.x * kBlock + threadIdx.x; idx < total;
-         idx += (long long)gridDim.x * kBlock) {
-        const int q = (int)(idx % No);
-        const long long sv = idx / No;
-        const int v = (int)(sv % V);
-        const long long st = sv / V;
-        const uint4 a = map[(st * No + q) * V + v];
-        float *dst = planar + (st * M + (long long)E * v) * No + q;
+    for (int idx = (int)blockIdx.x * kBlock + (int)threadIdx.x; idx < total; idx += (int)gridDim.x * kBlock) {
+        const int sv = fast_div(idx, dNo), q = idx - sv * No;
+        const int st = fast_div(sv, dV), v = sv - st * V;
+        const uint4 a = map[(size_t)(st * No + q) * V + v];
+        float *dst = planar + ((size_t)st * M + (size_t)E * v) * No + q;
 #pragma unroll
         for (int i = 0; i < E; ++i)
-            if (E * v + i < M) dst[(long long)i * No] = Unit<DT>::get(a, i);
+            if (E * v + i < M) dst[(size_t)i * No] = Unit<DT>::get(a, i);
     }
 }
 
 hipError_t map_to_planar(hipStream_t st, const void *map, float *planar, int M, int V, int No, int S, int dtype,
                          const Timing &tm)
 {
-    const long long total = (long long)S * V * No;
+    const long long total = (long long)S * V * No; // units of the map
+    if (total >= (1ll << 30) || V < 1 || No < 1) return hipErrorInvalidValue; // 32-bit indices, with room for the grid stride
     long long grid = (total + kBlock - 1) / kBlock;
     if (grid > 8192) grid = 8192;
     if (grid < 1) grid = 1;
     const uint4 *m4 = static_cast<const uint4 *>(map);
+    const FastDiv dNo = make_fastdiv(No), dV = make_fastdiv(V);
     if (dtype == kBF16)
         launch_kernel(tm, map_to_planar_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, m4, planar, M, V, No,
-                           total);
+                      (int)total, dNo, dV);
     else
         launch_kernel(tm, map_to_planar_kernel<kF32>, dim3((int)grid), dim3(kBlock), 0, st, m4, planar, M, V, No,
-                           total);
+                      (int)total, dNo, dV);
     return hipGetLastError();
 }
 
