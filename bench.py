@@ -24,7 +24,7 @@ MI355X_BF16_MFMA_TFLOPS = 2500.0
 # HBM bytes per launch of the dominant kernel (gathered GEMM of the 64->256 7x7 layer) on the
 # benchmark workload, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by a plain
 # copy of known size); the commands and figures are in profiles/cfg2_hbm_traffic.md.
-CFG2_DOMINANT_GEMM_HBM_BYTES = 61.8e6
+CFG2_DOMINANT_GEMM_HBM_BYTES = 62.6e6
 
 
 def frame_order(n_frames: int, count: int, start: int = 0):
