@@ -470,6 +470,30 @@ def test_large_frames_stored_without_padding_channels(C, hold):
     assert 0 < stats[-1][0] < H * W // 4
 
 
+def test_large_multi_stream_frames_without_padding_channels():
+    """Two streams whose frames together pass 2^18 pixels (stored with three values per pixel), an
+    odd number of pixels per stream: waves and float4 of the stored map straddle the stream boundary."""
+    layers = [conv(3, 5, 3)]
+    params = make_weights(layers, 71)
+    S, H, W = 2, 363, 365
+    vids = [_video(H, W, seed=800 + s, n_objects=3, sigma=0.003, size_range=(8, 24)) for s in range(S)]
+    net = cb.CBInfer(layers, params, (3, H, W), 0.02, n_streams=S)
+    orcs = [oracle.OracleCBNet(layers, params, 0.02) for _ in range(S)]
+    for t in range(3):
+        fr = np.stack([vv.frame(t) for vv in vids])
+        got = net.process_frame(to_dev(fr)).cpu().numpy()
+        want = [o.process_frame(fr[s]) for s, o in enumerate(orcs)]
+        cl = np.concatenate([o.trace[0]["C"] + s * H * W for s, o in enumerate(orcs)])
+        ul = np.concatenate([o.trace[0]["U"] + s * H * W for s, o in enumerate(orcs)])
+        np.testing.assert_array_equal(net.read_list(0, cb.LIST_CHANGED), cl)
+        np.testing.assert_array_equal(net.read_list(0, cb.LIST_UPDATE), ul)
+        ref = net.read_map(0, cb.MAP_REFERENCE)
+        for s in range(S):
+            np.testing.assert_array_equal(ref[s], orcs[s].ref[0])
+            assert_features_close(got[s], want[s], "stream %d frame %d" % (s, t))
+    net.destroy()
+
+
 @pytest.mark.parametrize("case", ["f32", "bf16", "two_streams", "wide"])
 def test_trailing_1x1_layers_bit_exact(case):
     """Two 1x1 layers at the end of a network (the classification layers of the paper's network
