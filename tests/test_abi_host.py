@@ -139,3 +139,20 @@ def test_workspace_grows_with_streams_and_shrinks_with_bfloat16():
     half = cb.cbinfer_workspace_bytes(layers, params, (3, 240, 320), dtype=cb.BF16)
     assert four > 2 * one > 0
     assert half < one
+
+
+def test_large_three_channel_frames_are_stored_without_a_padding_channel():
+    """From 2^18 pixels on a float32 frame with 3 channels keeps 3 values per pixel in the stored
+    previous input (the detection pass then moves no padding); smaller frames, four channels and
+    bfloat16 keep whole 16-byte units.  Seen from the host through the workspace size."""
+    def ws(c, h, w, **kw):
+        layers = [conv(c, 8, 3)]
+        return cb.cbinfer_workspace_bytes(layers, make_weights(layers, 2), (c, h, w), **kw)
+
+    big = 512 * 512                                   # = 2^18 pixels
+    saved = ws(4, 512, 512) - ws(3, 512, 512)
+    assert big * 4 <= saved < big * 4 + 4096          # one float per pixel less, nothing else differs
+    assert ws(4, 256, 256) == ws(3, 256, 256)         # small frames: padded either way
+    assert ws(4, 512, 512, dtype=cb.BF16) == ws(3, 512, 512, dtype=cb.BF16)
+    held = ws(4, 512, 512, flags=cb.FLAG_HOLD_REFERENCE) - ws(3, 512, 512, flags=cb.FLAG_HOLD_REFERENCE)
+    assert 2 * big * 4 <= held < 2 * big * 4 + 8192   # hold mode keeps two such maps
