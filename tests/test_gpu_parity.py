@@ -470,6 +470,41 @@ def test_large_frames_stored_without_padding_channels(C, hold):
     assert 0 < stats[-1][0] < H * W // 4
 
 
+@pytest.mark.parametrize("lists", [False, True])
+def test_integer_network_three_streams_every_layer_bit_exact(lists):
+    """Three streams through a network with pooling and a 5x5 layer, stream sizes that are no
+    multiple of 64 positions (bitmap words straddle the streams); with `lists` the dilation and
+    extraction kernels see byte change maps, pooled maps and stream boundaries together."""
+    layers = [conv(3, 6, 3), pool(), conv(6, 9, 5), pool(), conv(9, 4, 3, relu=False)]
+    params = _integer_params(layers, 33)
+    S, H, W = 3, 20, 28
+    vids = [_integer_video(H, W, 3, 5, 200 + s) for s in range(S)]
+    taus = [0.5, None, 1.5, None, 2.5]
+    net = cb.CBInfer(layers, params, (3, H, W), taus, n_streams=S, lists_every_frame=lists)
+    orcs = [oracle.OracleCBNet(layers, params, [0.0 if t is None else t for t in taus]) for _ in range(S)]
+    for t in range(5):
+        fr = np.stack([vids[s][t] for s in range(S)])
+        want = np.stack([orcs[s].process_frame(fr[s]) for s in range(S)])
+        got = net.process_frame(to_dev(fr)).cpu().numpy()
+        for l, L in enumerate(layers):
+            what = "layer %d frame %d" % (l, t)
+            size = orcs[0].out[l].shape[1] * orcs[0].out[l].shape[2]
+            if L.kind == "conv":
+                n_in = orcs[0].trace[l]["x"][0].size
+                c = np.concatenate([orcs[s].trace[l]["C"] + s * n_in for s in range(S)])
+                u = np.concatenate([orcs[s].trace[l]["U"] + s * size for s in range(S)])
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_CHANGED), c, err_msg=what)
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), u, err_msg=what)
+            else:
+                pl = np.concatenate([orcs[s].trace[l]["P"] + s * size for s in range(S)])
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), pl, err_msg=what)
+            m = net.read_map(l, cb.MAP_OUTPUT)
+            for s in range(S):
+                np.testing.assert_array_equal(m[s], orcs[s].out[l], err_msg=what)
+        np.testing.assert_array_equal(got, want)
+    net.destroy()
+
+
 def test_large_multi_stream_frames_without_padding_channels():
     """Two streams whose frames together pass 2^18 pixels (stored with three values per pixel), an
     odd number of pixels per stream: waves and float4 of the stored map straddle the stream boundary."""
