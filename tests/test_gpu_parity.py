@@ -505,6 +505,55 @@ def test_integer_network_three_streams_every_layer_bit_exact(lists):
     net.destroy()
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_integer_networks_bit_exact(seed):
+    """Random stacks of 2-5 convolution layers (1x1 to 7x7, pooling in between, one to three
+    streams, either reference mode, either list path, some layers propagating): integer weights,
+    so every layer's lists and maps must match the oracle bit for bit on every frame."""
+    r = np.random.default_rng(4242 + seed)
+    H, W = int(r.integers(12, 40)) * 2, int(r.integers(12, 50)) * 2
+    C, S = int(r.integers(1, 6)), int(r.choice([1, 1, 2, 3]))
+    layers, c, h, w = [], C, H, W
+    depth = int(r.integers(2, 6))
+    for d in range(depth):
+        k, m = int(r.choice([1, 1, 3, 3, 5, 7])), int(r.choice([2, 4, 5, 8, 12, 20]))
+        layers.append(conv(c, m, k, relu=d < depth - 1))
+        c = m
+        if r.integers(0, 3) == 0 and h % 2 == 0 and w % 2 == 0 and h >= 8 and w >= 8 and d < depth - 1:
+            layers.append(pool())
+            h, w = h // 2, w // 2
+    hold, lists = bool(r.integers(0, 2)), bool(r.integers(0, 2))
+    prop = [l for l, L in enumerate(layers) if L.kind == "conv" and l > 0 and r.integers(0, 5) == 0 and not hold]
+    params = _integer_params(layers, int(r.integers(0, 1000)))
+    taus = [float(r.choice([0.5, 1.5, 2.5])) if L.kind == "conv" else None for L in layers]
+    vids = [_integer_video(H, W, C, 5, 300 + seed * 7 + s) for s in range(S)]
+    net = cb.CBInfer(layers, params, (C, H, W), taus, n_streams=S, hold_reference=hold, lists_every_frame=lists,
+                     propagate_layers=prop)
+    orcs = [oracle.OracleCBNet(layers, params, [0.0 if t is None else t for t in taus], ref_mode=1 if hold else 0,
+                               propagate_layers=prop) for _ in range(S)]
+    for t in range(5):
+        fr = np.stack([vids[s][t] for s in range(S)])
+        want = np.stack([orcs[s].process_frame(fr[s]) for s in range(S)])
+        got = net.process_frame(to_dev(fr)).cpu().numpy()
+        for l, L in enumerate(layers):
+            what = "seed %d layer %d frame %d" % (seed, l, t)
+            size = orcs[0].out[l].shape[1] * orcs[0].out[l].shape[2]
+            if L.kind == "conv":
+                n_in = orcs[0].trace[l]["x"][0].size
+                cl = np.concatenate([orcs[s].trace[l]["C"] + s * n_in for s in range(S)])
+                ul = np.concatenate([orcs[s].trace[l]["U"] + s * size for s in range(S)])
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_CHANGED), cl, err_msg=what)
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), ul, err_msg=what)
+            else:
+                pl = np.concatenate([orcs[s].trace[l]["P"] + s * size for s in range(S)])
+                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), pl, err_msg=what)
+            m = net.read_map(l, cb.MAP_OUTPUT)
+            for s in range(S):
+                np.testing.assert_array_equal(m[s], orcs[s].out[l], err_msg=what)
+        np.testing.assert_array_equal(got, want)
+    net.destroy()
+
+
 def test_large_multi_stream_frames_without_padding_channels():
     """Two streams whose frames together pass 2^18 pixels (stored with three values per pixel), an
     odd number of pixels per stream: waves and float4 of the stored map straddle the stream boundary."""
