@@ -3,28 +3,40 @@
 
 A step is one video frame through the whole hot path (change detection, index extraction,
 dilation, gathered matrix multiplication with output update, change propagation through
-pooling) of the 320x240 scene-labeling workload.  Frames are synthetic, seeded and already
-resident in HBM when the timed region starts.  Prints ONE JSON line.
+pooling).  Frames are synthetic, seeded and already resident in HBM when the timed region
+starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg3|cfg4|cfg5|hbm] [--rate R]
-                    [--dtype f32|bf16]
+The default run measures
+  * `value`: the 320x240 scene-labeling workload as written (sigma 0.005, tau 0.02), median over
+    --blocks timed blocks of --steps frames each, next to the dense HIP baseline of the same library;
+  * `sweep`: the same network and frame size, noise-free, with the motion chosen for about 1, 5
+    and 20 % changed input pixels: change-based and dense frames/s, speed-up, measured rates;
+  * `hbm`: the memory-bound kernels (detection, dilation, index extraction, pooling) on one
+    3x4096x4096 frame per step with a fifth of the pixels flagged, as fractions of the HBM peak;
+  * `roofline`: the dominant kernel against its peak; `cpu_baseline`: the CPU oracle on the host.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--blocks B]
+                    [--workload cfg2|cfg1|cfg3|cfg3-sweep|cfg4|cfg5|hbm|strided] [--rate R] [--dtype f32|bf16]
 """
 from __future__ import annotations
 
 import argparse
 import json
+import os
 import sys
 import time
 
 import numpy as np
 
+ROOT = os.path.dirname(os.path.abspath(__file__))
 MI355X_HBM_GBS = 8000.0
 MI355X_FP32_MFMA_TFLOPS = 157.3
 MI355X_BF16_MFMA_TFLOPS = 2500.0
-# HBM bytes per launch of the dominant kernel (gathered GEMM of the 64->256 7x7 layer) on the
-# benchmark workload, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by a plain
-# copy of known size); the commands and figures are in profiles/cfg2_hbm_traffic.md.
-CFG2_DOMINANT_GEMM_HBM_BYTES = 62.6e6
+# Counter-measured HBM bytes per launch of the dominant kernel: written next to
+# profiles/cfg2_hbm_traffic.md from the same two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE,
+# scaled by a plain copy of known size).  Missing or for another kernel: traffic is null.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "cfg2_hbm_traffic.json")
+METRIC = "frames/s and speed-up vs dense HIP conv at 1/5/20% change rate; HBM GB/s"
 
 
 def frame_order(n_frames: int, count: int, start: int = 0):
@@ -35,29 +47,49 @@ def frame_order(n_frames: int, count: int, start: int = 0):
         yield u if u < n_frames else period - u
 
 
+def hbm_config(frames: int, flagged: float = 0.2):
+    """One 1x1 layer and a 2x2 pooling on a 3x4096x4096 frame: a frame's traffic (0.6 GB for the
+    detection alone) exceeds the 256 MB last-level cache, so kernel rates are HBM rates.
+    flagged > 0: sensor noise sized so that this share of the pixels exceeds the threshold in
+    every frame, uniformly scattered (P(|d| > tau) = p per channel for d ~ N(0, 2 sigma^2) with
+    1 - (1 - p)^3 = flagged): index lists of millions of entries.  flagged = 0: two small moving
+    objects, everything but the detection pass is negligible."""
+    from statistics import NormalDist
+    from workloads import Config, conv, pool
+    tau = 0.02
+    if flagged > 0:
+        p = 1.0 - (1.0 - flagged) ** (1.0 / 3.0)
+        sigma = tau / (NormalDist().inv_cdf(1.0 - p / 2.0) * 2.0 ** 0.5)
+        return Config("hbm-4096x4096x3-flagged%g" % flagged, 0, [conv(3, 8, 1), pool()], 4096, 4096, 3,
+                      frames or 3, tau, sigma, video_kwargs={"n_objects": 0})
+    return Config("hbm-detect-4096x4096x3", 0, [conv(3, 4, 1, relu=False)], 4096, 4096, 3,
+                  frames or 3, tau, 0.0, video_kwargs={"n_objects": 2})
+
+
 def build_workload(args):
     from workloads import get_config
-    if args.workload == "cfg1":
+    w = args.workload
+    if w == "cfg1":
         cfg = get_config(1)
-    elif args.workload == "cfg2":
-        cfg = get_config(2)
-    elif args.workload == "cfg3":
-        cfg = get_config(3, change_rate=args.rate, sigma=args.sigma, n_frames=args.frames or 24)
-    elif args.workload == "cfg4":
+    elif w == "cfg2":
+        cfg = get_config(2) if args.rate is None else get_config(2, change_rate=args.rate)
+    elif w == "cfg3":
+        cfg = get_config(3, change_rate=0.02 if args.rate is None else args.rate, sigma=args.sigma,
+                         n_frames=args.frames or 24)
+    elif w == "cfg4":
         cfg = get_config(4, n_frames=args.frames or 24)
-    elif args.workload == "cfg5":
+    elif w == "cfg5":
         cfg = get_config(5, n_frames=args.frames or 12)
-    elif args.workload == "hbm":
-        # One 1x1 layer on a 3x4096x4096 frame with a handful of changing pixels: everything but
-        # change detection is negligible, and a frame's traffic (~0.7 GB) exceeds the last-level
-        # cache, so the detection kernel's rate is an HBM rate.
-        from workloads import Config, conv
-        cfg = Config("hbm-detect-4096x4096x3", 0, [conv(3, 4, 1, relu=False)], 4096, 4096, 3,
-                     args.frames or 3, 0.02, 0.0, video_kwargs={"n_objects": 2})
+    elif w == "strided":
+        cfg = get_config(6, n_frames=args.frames or 24)
+    elif w == "hbm":
+        cfg = hbm_config(args.frames, 0.2 if args.rate is None else args.rate)
     else:
-        raise SystemExit("unknown workload " + args.workload)
+        raise SystemExit("unknown workload " + w)
     if args.frames:
         cfg.n_frames = args.frames
+    if args.sigma is not None and w != "cfg3":
+        cfg.sigma = args.sigma
     if args.dtype:
         cfg.dtype = args.dtype
     return cfg
@@ -73,6 +105,171 @@ def time_steps(net, frames_dev, out, order):
         net.process_frame_ptr(p, optr)
     torch.cuda.synchronize()
     return time.perf_counter() - t0
+
+
+def timed_blocks(net, frames_dev, out, n_frames, warmup, steps, blocks):
+    """`warmup` untimed frames (the first is the dense one), then `blocks` timed blocks of exactly
+    `steps` frames each; returns the seconds of every block."""
+    for t in frame_order(n_frames, warmup):
+        net.process_frame(frames_dev[t], out)
+    return [time_steps(net, frames_dev, out, list(frame_order(n_frames, steps, warmup + b * steps)))
+            for b in range(blocks)]
+
+
+def kernel_entries(cfg, net, prof, sums, P, in_shape):
+    """Per-kernel records (mean microseconds, algorithmic bytes or flops per launch, rates) and
+    the measured change rates per layer."""
+    import paper_1704_04313_amd as cb
+    bf16 = cfg.dtype == "bf16"
+    esz = 2.0 if bf16 else 4.0         # bytes per stored map element
+    mfma_peak = MI355X_BF16_MFMA_TFLOPS if bf16 else MI355X_FP32_MFMA_TFLOPS
+    n_ops = len(cfg.layers)
+    S = cfg.n_streams
+    shapes = [in_shape] + [net.layer_shape(l) for l in range(n_ops)]
+    rates, kernels = {}, {}
+    for l in range(n_ops):
+        L = cfg.layers[l]
+        c_in, h_in, w_in = shapes[l]
+        c_out, h_out, w_out = shapes[l + 1]
+        n_c, n_u = sums[l] / P           # all streams together
+        if L.kind == "conv":
+            rates["L%d" % l] = {"changed_in": n_c / (S * h_in * w_in), "updated_out": n_u / (S * h_out * w_out)}
+        else:
+            rates["L%d" % l] = {"updated_pooled": n_u / (S * h_out * w_out)}
+        pooled_next = l + 1 < n_ops and cfg.layers[l + 1].kind == "pool"
+        n_p = sums[l + 1][1] / P if pooled_next else 0.0
+        for (ll, name), (ms, n) in prof.items():
+            if ll != l:
+                continue
+            e = {"us": 1e3 * ms}
+            by = None
+            if name == "detect":
+                # frame read (float32) + stored previous input read and written + change bitmap
+                by = S * ((4.0 + 2.0 * esz) * c_in * h_in * w_in + h_in * w_in / 8.0)
+            elif name == "gemm":
+                fl = 2.0 * L.cout * L.cin * L.kh * L.kw * n_u
+                e.update(flops=fl, TFLOPs=fl / (ms * 1e-3) / 1e12, frac_mfma=fl / (ms * 1e-3) / 1e12 / mfma_peak)
+            elif name == "dilate":
+                # change map read (one bit per pixel; one byte behind the first layer), update and pooled bitmaps written
+                chg = S * h_in * w_in * (1.0 if l > 0 else 0.125)
+                by = chg + S * h_out * w_out / 8.0 + (S * h_out * w_out / 32.0 if pooled_next else 0.0)
+            elif name == "compact":
+                # every bitmap read once, every list written once (changed inputs, outputs to update, pooled)
+                maps = S * (h_in * w_in * (1.0 if l > 0 else 0.125) + h_out * w_out / 8.0)
+                if pooled_next:
+                    maps += S * h_out * w_out / 32.0
+                by = maps + 4.0 * (n_c + n_u + n_p)
+            elif name == "pool":
+                # list entry, k*k window values read, one value written, per pooled position and channel
+                by = 4.0 * n_u + (L.kh * L.kw + 1.0) * esz * c_out * n_u
+            elif name == "output":
+                by = S * (esz + 4.0) * c_out * h_out * w_out
+            if by is not None:
+                gbs = by / (ms * 1e-3) / 1e9
+                e.update(bytes=by, GBps=gbs, frac_hbm=gbs / MI355X_HBM_GBS)
+            kernels["L%d.%s" % (l, name)] = e
+    return kernels, rates
+
+
+def measure(cfg, args, *, steps, warmup, blocks, profile=True):
+    """Change-based and dense frames/s of one workload (medians over timed blocks) and, with
+    `profile`, per-kernel times from events attached to every launch plus measured change rates."""
+    import torch
+    import paper_1704_04313_amd as cb
+
+    params = cfg.weights()
+    videos = [cfg.video(s) for s in range(cfg.n_streams)]
+    if cfg.n_streams == 1:
+        frames = np.stack([videos[0].frame(t) for t in range(cfg.n_frames)])
+    else:   # [T][S][C][H][W]: one frame of every stream per step
+        frames = np.stack([np.stack([v.frame(t) for v in videos]) for t in range(cfg.n_frames)])
+    frames_dev = torch.from_numpy(frames).cuda()
+    del frames
+    in_shape = (cfg.channels, cfg.height, cfg.width)
+    bf16 = cfg.dtype == "bf16"
+    conv_ids = [l for l, L in enumerate(cfg.layers) if L.kind == "conv"]
+    net = cb.CBInfer(cfg.layers, params, in_shape, cfg.tau, n_streams=cfg.n_streams,
+                     dtype=cb.BF16 if bf16 else cb.F32, hold_reference=args.hold,
+                     propagate_layers=conv_ids[1:] if args.propagate else ())
+    out = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
+
+    sec_cb = timed_blocks(net, frames_dev, out, cfg.n_frames, warmup, steps, blocks)
+    # dense HIP baseline: same kernels, identity lists, no change detection
+    net.set_mode(True)
+    sec_dense = timed_blocks(net, frames_dev, out, cfg.n_frames, warmup, steps, blocks)
+    net.set_mode(False)
+    med_cb, med_dense = float(np.median(sec_cb)), float(np.median(sec_dense))
+    fps = [cfg.n_streams * steps / s for s in sec_cb]
+    res = {
+        "fps": cfg.n_streams * steps / med_cb, "ms_per_step": 1e3 * med_cb / steps,
+        "fps_blocks": fps, "fps_spread": (max(fps) - min(fps)) / (cfg.n_streams * steps / med_cb),
+        "dense_fps": cfg.n_streams * steps / med_dense, "speedup": med_dense / med_cb,
+    }
+    if profile:
+        n_ops = len(cfg.layers)
+        net.reset()
+        for t in frame_order(cfg.n_frames, warmup):
+            net.process_frame(frames_dev[t], out)
+        net.set_profiling(True)
+        P = min(steps, 100)
+        sums = {l: np.zeros(2) for l in range(n_ops)}
+        for t in frame_order(cfg.n_frames, P, warmup):
+            net.process_frame(frames_dev[t], out)
+            for l in range(n_ops):
+                sums[l] += np.maximum(np.array(net.layer_counts(l), dtype=np.float64), 0)
+        prof = {}
+        for l in range(n_ops):
+            for s, name in enumerate(cb.STEP_NAMES):
+                ms, n = net.read_profile(l, s)
+                if n:
+                    prof[(l, name)] = (ms / n, n)
+        net.set_profiling(False)
+        res["kernels"], res["change_rates"] = kernel_entries(cfg, net, prof, sums, P, in_shape)
+    net.destroy()
+    del frames_dev, out
+    torch.cuda.empty_cache()
+    return res
+
+
+def roofline_of(cfg, kernels):
+    """The dominant kernel (largest mean time per launch) against the peak that bounds it."""
+    bf16 = cfg.dtype == "bf16"
+    dom = max(kernels, key=lambda k: kernels[k]["us"])
+    d = kernels[dom]
+    if "TFLOPs" in d:
+        roof = {"bound": "mfma", "achieved": d["TFLOPs"],
+                "peak": MI355X_BF16_MFMA_TFLOPS if bf16 else MI355X_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": d["frac_mfma"], "traffic": None}
+    else:
+        roof = {"bound": "hbm", "achieved": d.get("GBps"), "peak": MI355X_HBM_GBS, "unit": "GB/s",
+                "frac": d.get("frac_hbm", 0.0), "traffic": None}
+    try:
+        with open(TRAFFIC_FILE) as f:
+            tr = json.load(f)
+        if tr.get("workload") == cfg.name and tr.get("kernel") == dom and tr.get("dtype") == cfg.dtype:
+            roof["traffic"] = float(tr["hbm_bytes_per_launch"])
+            roof["traffic_source"] = "profiles/cfg2_hbm_traffic.json (%s, %s)" % (tr.get("commit"), tr.get("date"))
+    except (OSError, ValueError, KeyError):
+        pass
+    roof["kernel"] = dom
+    roof["avg_us"] = d["us"]
+    roof["sum_kernel_us_per_frame"] = sum(k["us"] for k in kernels.values())
+    return roof
+
+
+def sweep_rows(configs, args, steps, warmup, blocks):
+    rows = []
+    for nominal, cfg in configs:
+        m = measure(cfg, args, steps=steps, warmup=warmup, blocks=blocks)
+        cr = m["change_rates"]
+        g = max((k for k in m["kernels"] if k.endswith(".gemm")), key=lambda k: m["kernels"][k]["us"])
+        rows.append({"nominal_changed": nominal, "workload": cfg.name, "n_objects": cfg.video_kwargs.get("n_objects"),
+                     "sigma": cfg.sigma, "frames_per_s": m["fps"], "dense_hip_frames_per_s": m["dense_fps"],
+                     "speedup_vs_dense_hip": m["speedup"], "fps_spread": m["fps_spread"],
+                     "changed_input_pixels": cr["L0"]["changed_in"], "change_rates": cr,
+                     "largest_gemm": {"kernel": g, "us": m["kernels"][g]["us"], "TFLOPs": m["kernels"][g]["TFLOPs"]}})
+        print("sweep %s: %.0f vs %.0f frames/s" % (cfg.name, m["fps"], m["dense_fps"]), file=sys.stderr, flush=True)
+    return rows
 
 
 def cpu_baseline(cfg, budget_s: float):
@@ -108,10 +305,12 @@ def cpu_baseline(cfg, budget_s: float):
 def parse_args(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--steps", type=int, default=300, help="frames per timed block")
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--blocks", type=int, default=5, help="timed blocks; the median block gives `value`")
     ap.add_argument("--workload", default="cfg2")
-    ap.add_argument("--rate", type=float, default=0.02, help="cfg3: nominal changed-pixel share")
+    ap.add_argument("--rate", type=float, default=None,
+                    help="cfg2 / cfg3: nominal changed-pixel share of the noise-free sweep; hbm: flagged share")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default=None,
                     help="storage type of maps and weights (default: the workload's)")
     ap.add_argument("--sigma", type=float, default=None, help="override sensor noise")
@@ -122,6 +321,8 @@ def parse_args(argv=None):
     ap.add_argument("--frames", type=int, default=0, help="frames generated (default: the workload's)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg (0: skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel timing pass")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="default workload only: skip the change-rate sweep and the HBM leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run three 256 MiB device copies (reference for profiler byte counters)")
     return ap.parse_args(argv)
@@ -135,8 +336,7 @@ def run(args) -> dict:
         sys.exit(2)
 
     import torch
-    import paper_1704_04313_amd as cb
-    from workloads import dense_flops
+    from workloads import dense_flops, get_config
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
@@ -152,122 +352,63 @@ def run(args) -> dict:
         torch.cuda.synchronize()
         del src, dst
 
+    W, K, B = args.warmup, args.steps, max(1, args.blocks)
+    if args.workload == "cfg3-sweep":
+        # the 1280x720 frames of the same network: speed-up against change rate (Section 4.4 in kind)
+        rates = (0.005, 0.02, 0.10, 0.30, 1.0)
+        sig = 0.0 if args.sigma is None else args.sigma
+        rows = sweep_rows([(r, get_config(3, change_rate=r, sigma=sig, n_frames=args.frames or 24)) for r in rates],
+                          args, min(K, 60), min(W, 6), min(B, 3))
+        mid = rows[1]
+        return {"metric": METRIC, "value": mid["frames_per_s"], "unit": "frames/s", "n_gpus": 1, "steps": min(K, 60),
+                "warmup": min(W, 6), "ms_per_step": 1e3 / mid["frames_per_s"], "higher_is_better": True,
+                "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                "config": {"workload": "cfg3-sweep-1280x720", "value_row": mid["workload"], "sigma": sig, "tau": 0.02},
+                "sweep": rows, "roofline": None, "cpu_baseline": None}
+
     cfg = build_workload(args)
-    params = cfg.weights()
-    videos = [cfg.video(s) for s in range(cfg.n_streams)]
-    if cfg.n_streams == 1:
-        frames = np.stack([videos[0].frame(t) for t in range(cfg.n_frames)])
-    else:   # [T][S][C][H][W]: one frame of every stream per step
-        frames = np.stack([np.stack([v.frame(t) for v in videos]) for t in range(cfg.n_frames)])
-    frames_dev = torch.from_numpy(frames).cuda()
     in_shape = (cfg.channels, cfg.height, cfg.width)
-    bf16 = cfg.dtype == "bf16"
-    esz = 2.0 if bf16 else 4.0         # bytes per stored map element
-    mfma_peak = MI355X_BF16_MFMA_TFLOPS if bf16 else MI355X_FP32_MFMA_TFLOPS
-    conv_ids = [l for l, L in enumerate(cfg.layers) if L.kind == "conv"]
-    net = cb.CBInfer(cfg.layers, params, in_shape, cfg.tau, n_streams=cfg.n_streams,
-                     dtype=cb.BF16 if bf16 else cb.F32, hold_reference=args.hold,
-                     propagate_layers=conv_ids[1:] if args.propagate else ())
-    out = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
-
-    W, K = args.warmup, args.steps
-    # ---- change-based: warm-up (includes the dense first frame), then exactly K timed steps
-    for t in frame_order(cfg.n_frames, W):
-        net.process_frame(frames_dev[t], out)
-    sec_cb = time_steps(net, frames_dev, out, list(frame_order(cfg.n_frames, K, W)))
-
-    # ---- dense HIP baseline: same kernels, identity lists, no change detection
-    net.set_mode(True)
-    for t in frame_order(cfg.n_frames, W):
-        net.process_frame(frames_dev[t], out)
-    sec_dense = time_steps(net, frames_dev, out, list(frame_order(cfg.n_frames, K, W)))
-    net.set_mode(False)
-
+    m = measure(cfg, args, steps=K, warmup=W, blocks=B, profile=not args.no_profile)
     result = {
-        "metric": "frames/s and speed-up vs dense HIP conv at 1/5/20% change rate; HBM GB/s",
-        "value": cfg.n_streams * K / sec_cb, "unit": "frames/s", "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": 1e3 * sec_cb / K, "higher_is_better": True, "scaling": "weak",
+        "metric": METRIC,
+        "value": m["fps"], "unit": "frames/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "frame": "%dx%dx%d" % (cfg.width, cfg.height, cfg.channels),
                    "tau": cfg.tau, "sigma": cfg.sigma, "n_frames": cfg.n_frames, "n_streams": cfg.n_streams,
                    "reference_update": "where flagged" if args.hold else "previous frame",
                    "detection": "first layer only, changes propagated" if args.propagate else "every layer"},
-        "dense_hip_frames_per_s": cfg.n_streams * K / sec_dense,
-        "speedup_vs_dense_hip": sec_dense / sec_cb,
+        "timing": {"blocks": B, "frames_per_block": K, "value_is": "median block",
+                   "frames_per_s_blocks": m["fps_blocks"], "spread": m["fps_spread"]},
+        "dense_hip_frames_per_s": m["dense_fps"],
+        "speedup_vs_dense_hip": m["speedup"],
         "paper_context": "8.6x (Tegra X1) / 7.6x (GTX 1080) over cuDNN, 327.6 GOp/s/W; other hardware, other data",
     }
-
-    # ---- per-kernel timing pass (HIP events around every launch, on the library's stream)
     if not args.no_profile:
-        n_ops = len(cfg.layers)
-        net.reset()
-        for t in frame_order(cfg.n_frames, W):
-            net.process_frame(frames_dev[t], out)
-        net.set_profiling(True)
-        P = min(K, 100)
-        sums = {l: np.zeros(2) for l in range(n_ops)}
-        for t in frame_order(cfg.n_frames, P, W):
-            net.process_frame(frames_dev[t], out)
-            for l in range(n_ops):
-                sums[l] += np.maximum(np.array(net.layer_counts(l), dtype=np.float64), 0)
-        prof = {}
-        for l in range(n_ops):
-            for s, name in enumerate(cb.STEP_NAMES):
-                ms, n = net.read_profile(l, s)
-                if n:
-                    prof[(l, name)] = (ms / n, n)
-        net.set_profiling(False)
-        shapes = [in_shape] + [net.layer_shape(l) for l in range(n_ops)]
-        rates, kernels = {}, {}
-        for l in range(n_ops):
-            L = cfg.layers[l]
-            c_in, h_in, w_in = shapes[l]
-            c_out, h_out, w_out = shapes[l + 1]
-            n_c, n_u = sums[l] / P / cfg.n_streams
-            if L.kind == "conv":
-                rates["L%d" % l] = {"changed_in": n_c / (h_in * w_in), "updated_out": n_u / (h_out * w_out)}
-            else:
-                rates["L%d" % l] = {"updated_pooled": n_u / (h_out * w_out)}
-            for (ll, name), (ms, n) in prof.items():
-                if ll != l:
-                    continue
-                e = {"us": 1e3 * ms}
-                if name == "detect":
-                    # frame read (float32) + stored input read and written
-                    by = cfg.n_streams * ((4.0 + 2.0 * esz) * c_in * h_in * w_in + h_in * w_in / 8.0)
-                    e.update(bytes=by, GBps=by / (ms * 1e-3) / 1e9, frac_hbm=by / (ms * 1e-3) / 1e9 / MI355X_HBM_GBS)
-                elif name == "gemm":
-                    fl = 2.0 * L.cout * L.cin * L.kh * L.kw * n_u * cfg.n_streams
-                    e.update(flops=fl, TFLOPs=fl / (ms * 1e-3) / 1e12,
-                             frac_mfma=fl / (ms * 1e-3) / 1e12 / mfma_peak)
-                elif name == "compact":
-                    by = (h_in * w_in + h_out * w_out) / 8.0 + 4.0 * (n_c + n_u)
-                    e.update(bytes=by, GBps=by / (ms * 1e-3) / 1e9)
-                elif name == "pool":
-                    by = 4.0 * n_u + 5.0 * esz * c_out * n_u
-                    e.update(bytes=by, GBps=by / (ms * 1e-3) / 1e9)
-                kernels["L%d.%s" % (l, name)] = e
-        dom = max(kernels, key=lambda k: kernels[k]["us"])
-        d = kernels[dom]
-        if "TFLOPs" in d:
-            roof = {"bound": "mfma", "achieved": d["TFLOPs"], "peak": mfma_peak, "unit": "TFLOP/s",
-                    "frac": d["frac_mfma"], "traffic": None}
-        else:
-            roof = {"bound": "hbm", "achieved": d.get("GBps"), "peak": MI355X_HBM_GBS, "unit": "GB/s",
-                    "frac": (d.get("GBps") or 0.0) / MI355X_HBM_GBS, "traffic": None}
-        if cfg.name.startswith("cfg2") and dom == "L4.gemm" and not bf16:
-            roof["traffic"] = CFG2_DOMINANT_GEMM_HBM_BYTES
-        roof["kernel"] = dom
-        roof["avg_us"] = d["us"]
-        roof["sum_kernel_us_per_frame"] = sum(k["us"] for k in kernels.values())
-        result["roofline"] = roof
-        result["kernels"] = kernels
-        result["change_rates"] = rates
+        result["roofline"] = roofline_of(cfg, m["kernels"])
+        result["kernels"] = m["kernels"]
+        result["change_rates"] = m["change_rates"]
         result["dense_gflop_per_frame"] = sum(dense_flops(cfg.layers, *in_shape)) / 1e9    # per stream
     else:
         result["roofline"] = None
 
-    net.destroy()
+    default_run = args.workload == "cfg2" and args.rate is None and not args.no_extras and not args.no_profile
+    if default_run:
+        # ---- speed-up against change rate on the benchmark network (noise-free; Section 4.4 in kind)
+        result["sweep"] = sweep_rows([(r, get_config(2, change_rate=r)) for r in (0.01, 0.05, 0.20)], args,
+                                     min(K, 200), W, min(B, 3))
+        # ---- the memory-bound kernels at a size that leaves the last-level cache
+        hcfg = hbm_config(3, 0.2)
+        h = measure(hcfg, args, steps=12, warmup=4, blocks=1)
+        pick = {k: v for k, v in h["kernels"].items() if "frac_hbm" in v}
+        result["hbm"] = {"workload": hcfg.name, "sigma": hcfg.sigma, "tau": hcfg.tau,
+                         "peak_GBps": MI355X_HBM_GBS, "change_rates": h["change_rates"],
+                         "kernels": {k: {"us": v["us"], "bytes": v["bytes"], "GBps": v["GBps"], "frac_hbm": v["frac_hbm"]}
+                                     for k, v in pick.items()},
+                         "note": "algorithmic bytes per launch / mean kernel time (events attached to the launch); "
+                                 "there is no stand-alone scatter kernel: the output update is the GEMM's epilogue"}
+        print("hbm leg done", file=sys.stderr, flush=True)
+
     result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds) if args.cpu_seconds > 0 else None
     return result
 

@@ -110,11 +110,15 @@ cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold);
  * frame_dev: DEVICE, [n_streams][in_c][in_h][in_w] float32.
  * out_dev:   DEVICE, [n_streams][cout_last][Ho][Wo] float32; receives the complete stored
  *            output of the last operation.
- * Asynchronous: all work is enqueued on the state's stream; the host is never blocked and
- * nothing is allocated.  Both buffers must stay valid until that work has run. */
+ * Asynchronous: all work is enqueued on the state's stream and nothing is allocated; the host
+ * does not wait for the device -- except while per-step timing is enabled
+ * (cbinfer_set_profiling), when the call returns only after the frame has run and its kernel
+ * times have been collected.  Both buffers must stay valid until that work has run. */
 int cbinfer_process_frame(cbinfer_state *s, const void *frame_dev, void *out_dev);
 
-/* Forget the video history: the next frame is evaluated densely.  Frees nothing. */
+/* Forget the video history: the stored previous inputs and outputs of Section 3.2 count as
+ * absent, so the next frame is evaluated densely like the first one (all positions flagged, identity
+ * lists).  Frees nothing, waits for nothing. */
 int cbinfer_reset(cbinfer_state *s);
 
 /* Waits for the stream, then releases everything the library allocated.  NULL is a no-op. */
@@ -133,19 +137,24 @@ int cbinfer_set_mode(cbinfer_state *s, int force_dense);
 /* Shape of operation `layer`'s output map, per stream. */
 int cbinfer_layer_shape(cbinfer_state *s, int layer, int32_t *c, int32_t *h, int32_t *w);
 
-/* Counts of the last frame for operation `layer`: changed input positions (CONV; -1 for
- * MAXPOOL) and output positions recomputed (CONV: the update list; MAXPOOL: pooled positions). */
+/* Lengths of the index lists of Section 3.1 ("Change Indexes Extraction") for operation `layer`
+ * in the last frame: changed input positions (CONV; -1 for MAXPOOL) and output positions
+ * recomputed (CONV: the dilated change map's positions; MAXPOOL: pooled positions recomputed). */
 int cbinfer_layer_counts(cbinfer_state *s, int layer, int64_t *n_changed, int64_t *n_update);
 
-enum { CBINFER_LIST_CHANGED = 0, CBINFER_LIST_UPDATE = 1 };
-/* Copy an index list of the last frame to HOST memory.  CONV: CHANGED = input positions whose
- * change exceeded tau, UPDATE = output positions recomputed.  MAXPOOL: UPDATE only.
+enum { CBINFER_LIST_CHANGED = 0, CBINFER_LIST_UPDATE = 1, CBINFER_LIST_POOLED = 2 };
+/* Copy an index list of the last frame (Section 3.1, "Change Indexes Extraction") to HOST memory.
+ * CONV: CHANGED = input positions whose change exceeded tau (first formula of Section 3.1),
+ * UPDATE = output positions recomputed (the dilated change map, second formula), POOLED = the
+ * positions of the pooling operation directly behind this layer that were recomputed (an error if
+ * there is none).  MAXPOOL: UPDATE only (the same list as the convolution's POOLED).
  * *n receives the list length; at most cap entries are written. */
 int cbinfer_read_list(cbinfer_state *s, int layer, int which, int32_t *host, int64_t cap, int64_t *n);
 
 enum { CBINFER_MAP_REFERENCE = 0, CBINFER_MAP_OUTPUT = 1 };
-/* Copy a stored map to HOST memory as planar float32 [n_streams][C][H][W].
- * REFERENCE: the stored previous input of a CONV layer.  OUTPUT: the stored output map.
+/* Copy one of the per-layer buffers of Section 3.2 to HOST memory as planar float32
+ * [n_streams][C][H][W] (bfloat16 storage is widened).  REFERENCE: the stored previous input of a
+ * CONV layer.  OUTPUT: the stored output map.
  * count = number of floats `host` can take; must equal the map size. */
 int cbinfer_read_map(cbinfer_state *s, int layer, int which, float *host, size_t count);
 

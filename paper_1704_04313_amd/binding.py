@@ -13,7 +13,7 @@ OP_CONV, OP_MAXPOOL = 0, 1
 F32, BF16 = 0, 1
 FLAG_HOLD_REFERENCE = 1
 FLAG_LISTS_EVERY_FRAME = 2
-LIST_CHANGED, LIST_UPDATE = 0, 1
+LIST_CHANGED, LIST_UPDATE, LIST_POOLED = 0, 1, 2
 MAP_REFERENCE, MAP_OUTPUT = 0, 1
 STEP_NAMES = ["detect", "dilate", "compact", "gemm", "pool", "output"]
 
@@ -62,6 +62,10 @@ def load_library():
     path = library_path()
     if not os.path.exists(path):
         raise FileNotFoundError(path + " is not built; run `python -m paper_1704_04313_amd.build`")
+    # torch first: its wheel carries a HIP runtime of its own (same soname as the system's).  Loaded
+    # first, it is the one this library binds to as well; loaded second, the process would hold two
+    # runtimes and the later one finds no device.
+    import torch  # noqa: F401
     lib = C.CDLL(path)
     st = C.c_void_p
     lib.cbinfer_workspace_bytes.argtypes = [C.POINTER(cbinfer_network)]

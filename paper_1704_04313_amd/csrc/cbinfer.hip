@@ -13,24 +13,6 @@
 #include <string>
 #include <vector>
 
-#ifdef CBK_TRACE
-// timing study builds only
-static unsigned long long *g_trace = nullptr;
-static unsigned long long *cbk_trace_buffer()
-{
-    if (!g_trace) {
-        (void)hipMalloc(&g_trace, 1024 * 2 * 16 * 8);
-        (void)hipMemset(g_trace, 0, 1024 * 2 * 16 * 8);
-    }
-    return g_trace;
-}
-extern "C" int cbinfer_debug_read_trace(unsigned long long *host)
-{
-    (void)hipDeviceSynchronize();
-    return (int)hipMemcpy(host, cbk_trace_buffer(), 1024 * 2 * 16 * 8, hipMemcpyDeviceToHost);
-}
-#endif
-
 namespace {
 
 thread_local std::string g_err = "";
@@ -581,9 +563,6 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                 a.next_flags = s->at<unsigned char>(P.ops[l + 1].o_chg);
                 a.next_tau = P.ops[l + 1].tau;
             }
-#ifdef CBK_TRACE
-            a.trace = cbk_trace_buffer();
-#endif
             cbk::gemm_set_divisors(a);
             {
                 StepTimer t(s, l, CBINFER_STEP_GEMM);
@@ -640,30 +619,15 @@ size_t cbinfer_workspace_bytes(const cbinfer_network *net)
     return P.bytes;
 }
 
-cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold)
+// Builds the state.  ws: device memory for the whole
+// workspace (P.bytes, 256-byte aligned) or nullptr to allocate it here.
+static cbinfer_state *create_state(const cbinfer_network *net, const Plan &P, char *ws)
 {
-    Plan P;
-    if (make_plan(net, threshold, true, P) != CBINFER_OK) return nullptr;
-    int ndev = 0;
-    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
-        fail(CBINFER_EDEVICE, "no HIP device available (this library has no CPU path)");
-        return nullptr;
-    }
     cbinfer_state *s = new cbinfer_state();
     s->plan = P;
     s->stream = reinterpret_cast<hipStream_t>(net->stream);
-    if (net->workspace) {
-        if (reinterpret_cast<uintptr_t>(net->workspace) % kAlign) {
-            fail(CBINFER_EINVAL, "workspace must be %zu-byte aligned", kAlign);
-            delete s;
-            return nullptr;
-        }
-        if (net->workspace_bytes < P.bytes) {
-            fail(CBINFER_ENOMEM, "workspace has %zu bytes, %zu needed", net->workspace_bytes, P.bytes);
-            delete s;
-            return nullptr;
-        }
-        s->ws = static_cast<char *>(net->workspace);
+    if (ws) {
+        s->ws = ws;
     } else {
         void *p = nullptr;
         hipError_t e = hipMalloc(&p, P.bytes);
@@ -694,6 +658,7 @@ cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold)
 
     auto setup = [&]() -> int {
         HIP_TRY(cbk::gemm_prepare());
+        // everything starts at zero: stored maps and their zero units, change maps, counters, tickets
         HIP_TRY(hipMemsetAsync(s->ws, 0, P.bytes, s->stream));
         std::vector<unsigned char> wt;
         std::vector<float> bias;
@@ -726,6 +691,28 @@ cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold)
         return nullptr;
     }
     return s;
+}
+
+cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold)
+{
+    Plan P;
+    if (make_plan(net, threshold, true, P) != CBINFER_OK) return nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
+        fail(CBINFER_EDEVICE, "no HIP device available (this library has no CPU path)");
+        return nullptr;
+    }
+    if (net->workspace) {
+        if (reinterpret_cast<uintptr_t>(net->workspace) % kAlign) {
+            fail(CBINFER_EINVAL, "workspace must be %zu-byte aligned", kAlign);
+            return nullptr;
+        }
+        if (net->workspace_bytes < P.bytes) {
+            fail(CBINFER_ENOMEM, "workspace has %zu bytes, %zu needed", net->workspace_bytes, P.bytes);
+            return nullptr;
+        }
+    }
+    return create_state(net, P, static_cast<char *>(net->workspace));
 }
 
 int cbinfer_process_frame(cbinfer_state *s, const void *frame_dev, void *out_dev)
@@ -828,8 +815,17 @@ int cbinfer_read_list(cbinfer_state *s, int layer, int which, int32_t *host, int
 {
     int rc = check_query(s, layer);
     if (rc) return rc;
+    if (which != CBINFER_LIST_CHANGED && which != CBINFER_LIST_UPDATE && which != CBINFER_LIST_POOLED)
+        return fail(CBINFER_EINVAL, "unknown list %d", which);
+    if (which == CBINFER_LIST_POOLED) {
+        // the pooled positions behind a convolution: the update list of the pooling op that follows it
+        const Op &cv = s->plan.ops[layer];
+        if (cv.kind != CBINFER_OP_CONV || cv.pool_after < 0)
+            return fail(CBINFER_EINVAL, "layer %d is not a convolution directly followed by pooling", layer);
+        layer = cv.pool_after;
+        which = CBINFER_LIST_UPDATE;
+    }
     const Op &op = s->plan.ops[layer];
-    if (which != CBINFER_LIST_CHANGED && which != CBINFER_LIST_UPDATE) return fail(CBINFER_EINVAL, "unknown list %d", which);
     if (which == CBINFER_LIST_CHANGED && op.kind != CBINFER_OP_CONV)
         return fail(CBINFER_EINVAL, "layer %d is a pooling layer and has no changed-input list", layer);
     if (cap < 0 || (cap > 0 && !host)) return fail(CBINFER_EINVAL, "bad host buffer");

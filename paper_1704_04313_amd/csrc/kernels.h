@@ -227,9 +227,6 @@ struct GemmArgs {
     unsigned char *next_flags; // nullptr: off
     float next_tau;
     int next_force;            // flag every recomputed position (first frame)
-#ifdef CBK_TRACE
-    unsigned long long *trace; // timing study builds only: [grid][2 roles][16] timestamps
-#endif
 };
 int gemm_channel_tile(int M);   // channel tile BM used for M output channels (Mpad = M rounded up to it)
 int gemm_k_multiple(int dtype); // Kpad must be a multiple of this many elements (128 bytes)

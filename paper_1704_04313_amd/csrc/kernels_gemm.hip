@@ -51,35 +51,6 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_resource(const float *p, 
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p), 0, bytes, 0x00020000);
 }
 
-#ifdef CBK_TRACE
-#ifdef CBK_TRACE_FRONT // slots 8-11 stamp the phases of the map ranking instead of a second segment
-#define CBK_STAMP_SLOTS 8
-#define CBK_FRONT(slot)                                                                         \
-    do {                                                                                        \
-        if (lane == 0 && (wave == 0 || wave == kConsWaves))                                      \
-            a.trace[((size_t)blockIdx.x * 2 + (wave != 0)) * 16 + (slot)] = wall_clock64();      \
-    } while (0)
-#else
-#define CBK_STAMP_SLOTS 16
-#define CBK_FRONT(slot) do { } while (0)
-#endif
-// timing study builds only: lane 0 of wave 0 (consumer) and of wave 4 (producer) stamp events
-#define CBK_STAMP(slot)                                                                         \
-    do {                                                                                        \
-        if (lane == 0 && (wave == 0 || wave == kConsWaves) && (slot) < CBK_STAMP_SLOTS)                  \
-            a.trace[((size_t)blockIdx.x * 2 + (wave != 0)) * 16 + (slot)] = wall_clock64();      \
-    } while (0)
-#define CBK_CYCLES(slot)                                                                        \
-    do {                                                                                        \
-        if (lane == 0 && (wave == 0 || wave == kConsWaves) && seg == 0)                                  \
-            a.trace[((size_t)blockIdx.x * 2 + (wave != 0)) * 16 + (slot)] = clock64();          \
-    } while (0)
-#else
-#define CBK_STAMP(slot) do { } while (0)
-#define CBK_CYCLES(slot) do { } while (0)
-#define CBK_FRONT(slot) do { } while (0)
-#endif
-
 
 static constexpr int BK = 32;       // K slice per pipeline stage: 128 bytes = 32 floats or 64 bfloat16,
                                     // i.e. 8 units of 16 bytes
@@ -89,34 +60,18 @@ static constexpr int LDK = BK;      // LDS row pitch in 4-byte words: 128 bytes,
                                     // u ^ lds_swizzle(r)) so that the 16-lane groups of a ds_read_b128
                                     // (16 rows, one or two neighbouring units) and of a ds_write_b128 (two rows,
                                     // all units) each cover all 64 banks once
-#ifndef CBK_CONS_WAVES
-#define CBK_CONS_WAVES 8
-#endif
-static constexpr int kConsWaves = CBK_CONS_WAVES; // consumer waves per workgroup (one or two per SIMD)
-#ifndef CBK_PROD_WAVES
-#define CBK_PROD_WAVES 4
-#endif
-static constexpr int NPROD = 64 * CBK_PROD_WAVES; // producer threads (one or two waves per SIMD)
+static constexpr int kConsWaves = 8;              // consumer waves per workgroup (two per SIMD)
+static constexpr int NPROD = 64 * 4;              // producer threads (one wave per SIMD)
 static constexpr int kRP = NPROD / 8;             // tile rows staged per pass: eight threads (units) per row
 static constexpr int NCONS = 64 * kConsWaves;     // consumer threads: waves 0 .. kConsWaves-1
 static constexpr int NT = NCONS + NPROD;          // threads per workgroup
 static constexpr int kStages = 3;   // K slices resident in LDS
-#ifndef CBK_THREE_SETS_UNITS
-#define CBK_THREE_SETS_UNITS 6 // tiles whose producer threads load at most this many 16-byte units per slice
-#endif
-#ifndef CBK_EPI_CHUNK
-#define CBK_EPI_CHUNK 4
-#endif
-static constexpr int kEpiChunk = CBK_EPI_CHUNK; // accumulators whose replaced values are loaded together in the output update
-#ifndef CBK_MIN_ITERS
-#define CBK_MIN_ITERS 8
-#endif
-#ifndef CBK_SMALL_FACTOR
-#define CBK_SMALL_FACTOR 2
-#endif
-static constexpr int kMinIters = CBK_MIN_ITERS; // shortest K range worth giving to a workgroup
+static constexpr int kThreeSetsUnits = 6; // tiles whose producer threads load at most this many 16-byte units per
+                                          // slice keep three register sets of loads in flight, the others two
+static constexpr int kEpiChunk = 4;       // accumulators whose replaced values are loaded together in the output update
+static constexpr int kMinIters = 8;       // shortest K range worth giving to a workgroup
 static constexpr int kMaxGrid = 1024;
-static constexpr int kSmallTileFactor = CBK_SMALL_FACTOR; // big tiles are used from (workgroups / this) big tiles on
+static constexpr int kSmallTileFactor = 2; // big tiles are used from (workgroups / this) big tiles on
 
 static constexpr int kSelMaxWords = 2048; // largest selection map ranked in-kernel (131072 pixels)
 static constexpr int kSelWordsPerThread = (kSelMaxWords + NT - 1) / NT;
@@ -300,12 +255,10 @@ __device__ __forceinline__ int rank_selection(const GemmArgs &a, uint64_t *sW, i
         load_bitmap(a.sel_map, a.sel_bytes, in_words, sC);
         if (tid < 2) sC[in_words + tid] = 0ull;
         __syncthreads();
-        CBK_FRONT(8);
         for (int v = tid; v < hd_words; v += NT) sH[v] = row_dilated_word(a, sC, v, hd_total);
         if (tid < 2) sH[hd_words + tid] = 0ull;
         for (int i = tid; i < nw; i += NT) sW[i] = 0ull;
         __syncthreads();
-        CBK_FRONT(9);
         // 2^sh threads per word share its kh tap rows (as many as keeps all words in one round, at
         // most one thread per row); their parts are OR-ed together in LDS
         const int out_total = a.S * a.No;
@@ -324,7 +277,6 @@ __device__ __forceinline__ int rank_selection(const GemmArgs &a, uint64_t *sW, i
         load_bitmap(a.sel_map, a.sel_bytes, nw, sW);
     }
     __syncthreads();
-    CBK_FRONT(10);
 #pragma unroll
     for (int j = 0; j < kSelWordsPerThread; ++j) {
         const int i = kSelWordsPerThread * tid + j;
@@ -356,7 +308,6 @@ __device__ __forceinline__ int rank_selection(const GemmArgs &a, uint64_t *sW, i
         e += c[j];
     }
     __syncthreads();
-    CBK_FRONT(11);
     return total;
 }
 
@@ -506,7 +457,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
     constexpr int TC = BM / WM / 16; // 16-channel MFMA tiles per consumer wave
     constexpr int PA = BN / kRP;     // image-matrix rows staged per producer thread and slice
     constexpr int PB = (BM + kRP - 1) / kRP;
-    constexpr int NS = PA + PB <= CBK_THREE_SETS_UNITS ? 3 : 2; // register sets of loads in flight per producer thread
+    constexpr int NS = PA + PB <= kThreeSetsUnits ? 3 : 2; // register sets of loads in flight per producer thread
     static_assert(BN % kRP == 0, "whole passes over the pixel rows");
     constexpr int ASZ = BN * LDK, BSZ = BM * LDK;
     constexpr int SLAB = BM * BN; // floats of one partial-accumulator slab
@@ -544,8 +495,6 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
 
     int round = 0;
     int it = it_begin;
-    [[maybe_unused]] int seg = 0; // numbers the time stamps of timing-study builds
-    CBK_STAMP(1);
     while (true) {
         // ---- next segment of this workgroup: a whole tile, or part of a shared tile's K range
         int tile, kc0, kc1, shared_j = -1;
@@ -568,7 +517,6 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
         const int mt = tile - pt * mtiles;
         const bool partial = (kc1 - kc0) != nk;
 
-        CBK_STAMP(2 + 6 * seg);
         // Producers: the tap descriptors of the first slices do not depend on the tile's pixel list,
         // so their loads are in flight while the list is made.
         const int ptid = producer ? tid - NCONS : 0;
@@ -648,7 +596,6 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                 tp[u] = tap(kc0 + 2 + NS + u);
             }
             __syncthreads();
-            CBK_STAMP(3 + 6 * seg);
             int slot = 2; // ring slot of slice kc+2
             for (int kc = kc0; kc < kc1; kc += NS) {
 #pragma unroll
@@ -715,8 +662,6 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                 }
             };
             __syncthreads();
-            CBK_STAMP(3 + 6 * seg);
-            CBK_CYCLES(14);
             // the wave feeding the matrix pipeline wins instruction-issue arbitration on its SIMD
             __builtin_amdgcn_s_setprio(3);
             read_frags(0, 0, 0);
@@ -741,13 +686,11 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                 __syncthreads();
             }
             __builtin_amdgcn_s_setprio(0);
-            CBK_CYCLES(15);
         }
 
         // ---- a shared tile: store this K range's accumulators, take a ticket; the workgroup
         //      holding the last ticket adds up all ranges (ascending K) and does the output update.
         //      Slab stores are complete (vmcnt(0)) before the ticket is taken.
-        CBK_STAMP(4 + 6 * seg);
         bool finish = true;
         if (partial) {
             const int t0 = shared_j * nk;
@@ -773,7 +716,6 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             if (tid == 0)
                 *sFlag = __hip_atomic_fetch_add(a.tickets + shared_j, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __syncthreads();
-            CBK_STAMP(5 + 6 * seg);
             finish = (*sFlag == w_last - w_first);
             if (finish) {
                 if (tid == 0) a.tickets[shared_j] = 0; // ready for the next launch
@@ -805,7 +747,6 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             }
         }
 
-        CBK_STAMP(6 + 6 * seg);
         // ---- output update: bias, activation, scatter to the stored map; optionally the change
         //      detection of the layer this map feeds (new value against the one it replaces)
         if (finish && !producer) {
@@ -903,8 +844,6 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                 }
             }
         }
-        CBK_STAMP(7 + 6 * seg);
-        ++seg;
     }
 }
 
@@ -916,10 +855,6 @@ template <int DT, int BM, int BNB, int WMB, int WNB, int BNS, int WMS, int WNS>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT + 255) / 256, (NT + 255) / 256))) void gemm_gather_kernel(GemmArgs a)
 {
     extern __shared__ __align__(16) float smem[];
-#ifdef CBK_TRACE
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#endif
-    CBK_STAMP(0);
     Selection sel = {nullptr, nullptr, 0};
     int n;
     if (a.sel_words > 0) {
@@ -993,11 +928,7 @@ int gemm_grid(const GemmArgs &a, int compute_units)
 }
 
 // BM, big tile (BN, WM, WN), small tile (BN, WM, WN)
-#if CBK_CONS_WAVES == 8
 #define CBK_VARIANTS(X) X(16, 256, 1, 8, 128, 1, 8) X(32, 256, 1, 8, 64, 2, 4) X(64, 256, 2, 4, 64, 2, 4) X(128, 128, 2, 4, 64, 4, 2)
-#else
-#define CBK_VARIANTS(X) X(16, 256, 1, 4, 64, 1, 4) X(32, 256, 1, 4, 64, 1, 4) X(64, 256, 1, 4, 64, 1, 4) X(128, 128, 2, 2, 64, 2, 2)
-#endif
 
 hipError_t gemm_prepare(void)
 {

@@ -156,3 +156,4 @@ def test_large_three_channel_frames_are_stored_without_a_padding_channel():
     assert ws(4, 512, 512, dtype=cb.BF16) == ws(3, 512, 512, dtype=cb.BF16)
     held = ws(4, 512, 512, flags=cb.FLAG_HOLD_REFERENCE) - ws(3, 512, 512, flags=cb.FLAG_HOLD_REFERENCE)
     assert 2 * big * 4 <= held < 2 * big * 4 + 8192   # hold mode keeps two such maps
+

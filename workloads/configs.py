@@ -19,6 +19,9 @@ SEED_BASE = 170404313
 # (beside this file): the smallest count whose mean share of moved pixels
 # (SyntheticVideo.moved_fraction, noise-free) over frames 1..8 reaches the nominal rate.
 SWEEP_OBJECTS: Dict[float, int] = {0.005: 6, 0.02: 23, 0.10: 126, 0.30: 445}
+# The same for the 320x240 frames of the benchmark network, where one rectangle more is a large
+# step: the count whose moved share is nearest to the nominal rate (measured 0.61 / 5.04 / 19.8 %).
+SWEEP320_OBJECTS: Dict[float, int] = {0.01: 1, 0.05: 5, 0.20: 25}
 
 
 @dataclass
@@ -70,6 +73,11 @@ def get_config(index: int, *, height: Optional[int] = None, width: Optional[int]
     if index == 1:
         c = Config("cfg1-single-7x7", 1, single_layer_net(), 64, 64, 3, 8, 0.02, 0.005,
                    video_kwargs={"objects_fn": _cfg1_objects})
+    elif index == 2 and change_rate is not None:
+        # the benchmark network and frame size, noise-free, motion chosen per nominal change rate
+        rate = float(change_rate)
+        c = Config("cfg2-sweep-320x240-rate%g" % rate, 2, scene_labeling_net(), 240, 320, 3, 100, 0.02, 0.0,
+                   video_kwargs={"n_objects": SWEEP320_OBJECTS[rate]})
     elif index == 2:
         c = Config("cfg2-scene-labeling-320x240", 2, scene_labeling_net(), 240, 320, 3, 100, 0.02, 0.005,
                    video_kwargs={"n_objects": 3})
