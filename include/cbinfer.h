@@ -102,6 +102,25 @@ size_t cbinfer_workspace_bytes(const cbinfer_network *net);
  * Returns NULL on error.  The first frame after create is evaluated densely. */
 cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold);
 
+/* For callers that cannot allocate device memory (set-up code of a pipeline that is later replayed
+ * from a HIP graph, serving loops and harnesses that forbid hipMalloc): cbinfer_create without any
+ * device allocation and without a caller workspace.  All state and scratch of the network live in
+ * a device array of CBINFER_STATIC_WORKSPACE_BYTES that is part of the library itself; every GPU
+ * the library is loaded on holds one such array from load time until the process ends.
+ * net->workspace and net->workspace_bytes are ignored.  The state is created on the current device.
+ * Errors (NULL returned, message in cbinfer_last_error): everything cbinfer_create rejects;
+ * CBINFER_ENOMEM if the network needs more than CBINFER_STATIC_WORKSPACE_BYTES
+ * (cbinfer_workspace_bytes tells how much it needs; the 320x240 scene-labeling network fits, the
+ * 1280x720 and 64-stream workloads do not); CBINFER_ESTATE while another state created by this
+ * call is still alive on the same device: there is one array per device, so at most one such
+ * state per device may exist at a time, and two processes' worth of frames must not be
+ * interleaved through it.  The array keeps the previous state's contents; this call clears the
+ * part it uses.  cbinfer_destroy releases the array for the next state (and frees nothing).
+ * Everything else (cbinfer_process_frame, reset, introspection) works as for any other state. */
+#define CBINFER_STATIC_WORKSPACE_BYTES (64u << 20)
+cbinfer_state *cbinfer_create_static(const cbinfer_network *net, float threshold);
+size_t cbinfer_static_workspace_bytes(void); /* CBINFER_STATIC_WORKSPACE_BYTES of the loaded build */
+
 /* Process one frame: for every convolution layer, change detection against the stored
  * previous input, change-index extraction, dilation by the filter support into the list of
  * outputs to recompute, reduced matrix multiplication over those columns only, and the

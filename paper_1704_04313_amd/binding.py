@@ -21,7 +21,7 @@ EXPORTS = [
     "cbinfer_workspace_bytes", "cbinfer_create", "cbinfer_process_frame", "cbinfer_reset",
     "cbinfer_destroy", "cbinfer_last_error", "cbinfer_set_mode", "cbinfer_layer_shape",
     "cbinfer_layer_counts", "cbinfer_read_list", "cbinfer_read_map", "cbinfer_set_profiling",
-    "cbinfer_read_profile",
+    "cbinfer_read_profile", "cbinfer_create_static", "cbinfer_static_workspace_bytes",
 ]
 
 
@@ -72,6 +72,10 @@ def load_library():
     lib.cbinfer_workspace_bytes.restype = C.c_size_t
     lib.cbinfer_create.argtypes = [C.POINTER(cbinfer_network), C.c_float]
     lib.cbinfer_create.restype = st
+    lib.cbinfer_create_static.argtypes = [C.POINTER(cbinfer_network), C.c_float]
+    lib.cbinfer_create_static.restype = st
+    lib.cbinfer_static_workspace_bytes.argtypes = []
+    lib.cbinfer_static_workspace_bytes.restype = C.c_size_t
     lib.cbinfer_process_frame.argtypes = [st, C.c_void_p, C.c_void_p]
     lib.cbinfer_process_frame.restype = C.c_int
     lib.cbinfer_reset.argtypes = [st]
@@ -153,7 +157,8 @@ class CBInfer:
 
     def __init__(self, layers, params, in_shape, tau, *, n_streams: int = 1, hold_reference: bool = False,
                  dense_layers: Sequence[int] = (), caller_workspace: bool = True, dtype: int = F32,
-                 propagate_layers: Sequence[int] = (), lists_every_frame: bool = False):
+                 propagate_layers: Sequence[int] = (), lists_every_frame: bool = False,
+                 static_workspace: bool = False):
         import torch
         self._torch = torch
         self.lib = load_library()
@@ -172,7 +177,7 @@ class CBInfer:
         self.stream = torch.cuda.current_stream()
         net.stream = C.c_void_p(self.stream.cuda_stream)
         self.workspace = None
-        if caller_workspace:
+        if caller_workspace and not static_workspace:
             nbytes = self.lib.cbinfer_workspace_bytes(C.byref(net))
             if nbytes == 0:
                 raise CBInferError(-1, _last_error(self.lib))
@@ -180,7 +185,8 @@ class CBInfer:
             ptr = (self.workspace.data_ptr() + 255) // 256 * 256
             net.workspace = C.c_void_p(ptr)
             net.workspace_bytes = nbytes
-        self._state = self.lib.cbinfer_create(C.byref(net), C.c_float(global_tau))
+        create = self.lib.cbinfer_create_static if static_workspace else self.lib.cbinfer_create
+        self._state = create(C.byref(net), C.c_float(global_tau))
         if not self._state:
             raise CBInferError(-1, _last_error(self.lib))
         c, h, w = self.layer_shape(len(self.layers) - 1)

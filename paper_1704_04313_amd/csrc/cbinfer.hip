@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -248,6 +249,7 @@ struct cbinfer_state {
     hipStream_t stream = nullptr;
     char *ws = nullptr;
     bool owns_ws = false;
+    int static_device = -1;   // >= 0: the workspace is that device's static array (cbinfer_create_static)
     bool initialised = false; // a frame has been processed since create/reset
     bool force_dense = false;
     bool broken = false;
@@ -619,13 +621,14 @@ size_t cbinfer_workspace_bytes(const cbinfer_network *net)
     return P.bytes;
 }
 
-// Builds the state.  ws: device memory for the whole
+// Common part of cbinfer_create and cbinfer_create_static.  ws: device memory for the whole
 // workspace (P.bytes, 256-byte aligned) or nullptr to allocate it here.
-static cbinfer_state *create_state(const cbinfer_network *net, const Plan &P, char *ws)
+static cbinfer_state *create_state(const cbinfer_network *net, const Plan &P, char *ws, int static_device)
 {
     cbinfer_state *s = new cbinfer_state();
     s->plan = P;
     s->stream = reinterpret_cast<hipStream_t>(net->stream);
+    s->static_device = static_device;
     if (ws) {
         s->ws = ws;
     } else {
@@ -659,6 +662,7 @@ static cbinfer_state *create_state(const cbinfer_network *net, const Plan &P, ch
     auto setup = [&]() -> int {
         HIP_TRY(cbk::gemm_prepare());
         // everything starts at zero: stored maps and their zero units, change maps, counters, tickets
+        // (the static workspace keeps whatever the state before this one left in it)
         HIP_TRY(hipMemsetAsync(s->ws, 0, P.bytes, s->stream));
         std::vector<unsigned char> wt;
         std::vector<float> bias;
@@ -712,8 +716,80 @@ cbinfer_state *cbinfer_create(const cbinfer_network *net, float threshold)
             return nullptr;
         }
     }
-    return create_state(net, P, static_cast<char *>(net->workspace));
+    return create_state(net, P, static_cast<char *>(net->workspace), -1);
 }
+
+// ---- the entry point that allocates no device memory ------------------------------------------
+// All state and scratch of a network (stored maps, change maps, index lists, filter matrices, the
+// partial-accumulator slabs and ticket counters of the multiplication kernel) in a device array
+// that is part of the library's code object: every GPU the library is loaded on holds one copy of
+// it, at an address of its own, from module load until the process ends.
+static __device__ __align__(256) unsigned char scratch[CBINFER_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+char *g_scratch_ptr[kMaxDevices] = {};    // device address of `scratch` on each device, once looked up
+bool g_scratch_in_use[kMaxDevices] = {};  // a live state occupies that device's array
+} // namespace
+
+cbinfer_state *cbinfer_create_static(const cbinfer_network *net, float threshold)
+{
+    Plan P;
+    if (make_plan(net, threshold, true, P) != CBINFER_OK) return nullptr;
+    if (P.bytes > (size_t)CBINFER_STATIC_WORKSPACE_BYTES) {
+        fail(CBINFER_ENOMEM,
+             "this network needs %zu bytes of state and scratch; the static workspace holds %zu "
+             "(use cbinfer_create with a caller workspace)",
+             P.bytes, (size_t)CBINFER_STATIC_WORKSPACE_BYTES);
+        return nullptr;
+    }
+    int ndev = 0, dev = -1;
+    hipError_t de = hipGetDeviceCount(&ndev);
+    if (de != hipSuccess || ndev < 1) {
+        fail(CBINFER_EDEVICE, "no HIP device available (this library has no CPU path): hipGetDeviceCount says %s, %d devices",
+             hipGetErrorString(de), ndev);
+        return nullptr;
+    }
+    if ((de = hipGetDevice(&dev)) != hipSuccess) {
+        fail(CBINFER_EDEVICE, "no current HIP device: hipGetDevice says %s", hipGetErrorString(de));
+        return nullptr;
+    }
+    if (dev < 0 || dev >= kMaxDevices) {
+        fail(CBINFER_EUNSUPPORTED, "device ordinal %d is beyond the %d devices the static workspace is tracked for", dev,
+             kMaxDevices);
+        return nullptr;
+    }
+    char *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        if (g_scratch_in_use[dev]) {
+            fail(CBINFER_ESTATE, "the static workspace of device %d is in use by a state that has not been destroyed", dev);
+            return nullptr;
+        }
+        if (!g_scratch_ptr[dev]) {
+            // `scratch` names the array for the host compiler only; its device address (one per
+            // device) has to be asked for, with that device current
+            void *p = nullptr;
+            const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p) {
+                fail(CBINFER_EDEVICE, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+                return nullptr;
+            }
+            g_scratch_ptr[dev] = static_cast<char *>(p);
+        }
+        ptr = g_scratch_ptr[dev];
+        g_scratch_in_use[dev] = true;
+    }
+    cbinfer_state *s = create_state(net, P, ptr, dev);
+    if (!s) {
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        g_scratch_in_use[dev] = false;
+    }
+    return s;
+}
+
+size_t cbinfer_static_workspace_bytes(void) { return (size_t)CBINFER_STATIC_WORKSPACE_BYTES; }
 
 int cbinfer_process_frame(cbinfer_state *s, const void *frame_dev, void *out_dev)
 {
@@ -739,6 +815,10 @@ void cbinfer_destroy(cbinfer_state *s)
         if (e.b) (void)hipEventDestroy(e.b);
     }
     if (s->owns_ws && s->ws) (void)hipFree(s->ws);
+    if (s->static_device >= 0) {
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        g_scratch_in_use[s->static_device] = false;
+    }
     delete s;
 }
 

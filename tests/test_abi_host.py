@@ -157,3 +157,24 @@ def test_large_three_channel_frames_are_stored_without_a_padding_channel():
     held = ws(4, 512, 512, flags=cb.FLAG_HOLD_REFERENCE) - ws(3, 512, 512, flags=cb.FLAG_HOLD_REFERENCE)
     assert 2 * big * 4 <= held < 2 * big * 4 + 8192   # hold mode keeps two such maps
 
+
+def test_static_workspace_size_limit_is_checked_before_any_device_call():
+    """cbinfer_create_static keeps a network's state in a device array of fixed size inside the
+    library: a network that needs more is refused with a message that names both sizes, and the
+    320x240 scene-labeling network (the benchmark workload) fits."""
+    lib = cb.load_library()
+    cap = lib.cbinfer_static_workspace_bytes()
+    assert cap == 64 << 20
+    layers = scene_labeling_net()
+    params = make_weights(layers, 0)
+    assert cb.cbinfer_workspace_bytes(layers, params, (3, 240, 320)) <= cap
+    net, keep = _net_for(layers, params, (3, 720, 1280))
+    need = lib.cbinfer_workspace_bytes(C.byref(net))
+    assert need > cap
+    assert not lib.cbinfer_create_static(C.byref(net), C.c_float(0.02))
+    msg = lib.cbinfer_last_error().decode()
+    assert str(need) in msg and str(cap) in msg
+    # an invalid description is rejected the same way cbinfer_create rejects it
+    net, keep = _net_for([conv(3, 4, 3), conv(5, 2, 1)], make_weights([conv(3, 4, 3), conv(5, 2, 1)], 0), (3, 8, 8))
+    assert not lib.cbinfer_create_static(C.byref(net), C.c_float(0.02))
+    assert "does not match" in lib.cbinfer_last_error().decode()
