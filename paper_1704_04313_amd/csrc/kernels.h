@@ -204,10 +204,11 @@ struct GemmArgs {
     int sel_dilate;
     int sel_in_words;
     uint64_t *upd_out;
-    int kh, kw, S;      // filter size and number of streams (used by sel_dilate only)
+    int kh, kw, S;      // filter size; number of streams (used by sel_dilate only)
     void *out;          // stored output map [S*No][Ms]
     int N, H, W, No, Wo, stride, pad;
     FastDiv dNo, dWo, dHo, dNk, dGrid; // by No, Wo, No / Wo, Kpad / gemm_k_multiple(dtype) and grid (gemm_set_divisors)
+    FastDiv dVin, dKw;  // by the 16-byte units per filter tap, (pix_words + 3) / 4, and by kw
     int pix_words;      // 4-byte words per input pixel: a multiple of four (whole 16-byte units), or the channel
                         // count of a float32 map stored without padding (units then start at any word and
                         // run into the next pixel's channels, which meet zero filter weights)

@@ -65,9 +65,9 @@ static constexpr int NPROD = 64 * 4;              // producer threads (one wave 
 static constexpr int kRP = NPROD / 8;             // tile rows staged per pass: eight threads (units) per row
 static constexpr int NCONS = 64 * kConsWaves;     // consumer threads: waves 0 .. kConsWaves-1
 static constexpr int NT = NCONS + NPROD;          // threads per workgroup
-static constexpr int kStages = 3;   // K slices resident in LDS
-static constexpr int kThreeSetsUnits = 6; // tiles whose producer threads load at most this many 16-byte units per
-                                          // slice keep three register sets of loads in flight, the others two
+static constexpr int kStagedRing = 3; // K slices resident in LDS when the producers stage them through registers
+static constexpr int kThreeSetsUnits = 6; // (register staging) tiles whose producer threads load at most this many 16-byte
+                                          // units per slice keep three register sets of loads in flight, the others two
 static constexpr int kEpiChunk = 4;       // accumulators whose replaced values are loaded together in the output update
 static constexpr int kMinIters = 8;       // shortest K range worth giving to a workgroup
 static constexpr int kMaxGrid = 1024;
@@ -77,14 +77,22 @@ static constexpr int kSelMaxWords = 2048; // largest selection map ranked in-ker
 static constexpr int kSelWordsPerThread = (kSelMaxWords + NT - 1) / NT;
 static constexpr int kSelSlots = kSelWordsPerThread * NT; // LDS words per ranking array (>= kSelMaxWords)
 
-template <int BM, int BN>
+// LDS of one tile shape: a ring of STAGES K slices of both operands, then the tile's pixel list,
+// the ticket and two ints for the tile selection.
+template <int BM, int BN, int STAGES>
 struct TileSmem {
     static constexpr int a_floats = BN * LDK;
     static constexpr int b_floats = BM * LDK;
-    static constexpr int tile_bytes = kStages * (a_floats + b_floats) * 4 + BN * 4 + 16; // + list, ticket, range
-    // behind the tile: the selection map's words, their exclusive ranks, and the wave totals of the scan
-    static constexpr int sel_offset = (tile_bytes + 15) / 16 * 16;
+    static constexpr int tile_bytes = STAGES * (a_floats + b_floats) * 4 + BN * 4 + 16;
+};
+// LDS of a kernel instantiation (a big and a small tile shape share it): behind the larger of the
+// two tiles the selection map's words, their exclusive ranks, and the wave totals of the scan.
+template <int BM, int BNB, int SB, int BNS, int SS>
+struct KernelSmem {
+    static constexpr int tb = TileSmem<BM, BNB, SB>::tile_bytes, ts = TileSmem<BM, BNS, SS>::tile_bytes;
+    static constexpr int sel_offset = ((tb > ts ? tb : ts) + 15) / 16 * 16;
     static constexpr int bytes = sel_offset + kSelSlots * 12 + 64;
+    static_assert(bytes <= 160 * 1024, "a workgroup has 160 KiB of LDS");
 };
 
 // Selection-map mode: the words of the map and the rank of each word's first set bit, in LDS.
@@ -443,21 +451,111 @@ __device__ __forceinline__ void stage_rows(float *A, float *B, int r0, int v, co
     }
 }
 
+// s_waitcnt vmcnt(N), everything else unconstrained (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a six-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
+// The workgroup barrier as the direct-to-LDS producers execute it: the bare instruction.  The
+// fences of __syncthreads() would make the wave wait for all of its loads in flight, which are
+// exactly what has to stay in flight across the barrier; the one ordering the producers owe the
+// consumers -- a slice has landed in LDS before the barrier that publishes it -- is the explicit
+// wait_vmcnt in front of it, and the compiler must not move memory operations across either.
+__device__ __forceinline__ void producer_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+typedef __attribute__((address_space(1))) const void *GlobalPtr;
+typedef __attribute__((address_space(3))) void *LdsPtr;
+
+// Producer waves, direct-to-LDS variant: global_load_lds_dwordx4 moves 16 bytes per lane from
+// global memory into LDS without passing through registers -- lane l of an instruction lands at
+// the wave-uniform LDS base + 16 l, i.e. in slot l & 7 of row l >> 3 of eight consecutive rows --
+// so the producers only compute addresses.  Wave pw covers rows 8 pw .. 8 pw + 7 of every pass of
+// kRP rows; vf is the unit column this lane fetches (its slot with the row permutation undone).
+// The ring holds STAGES slices: slice kc + STAGES - 1 is issued in iteration kc into the slot
+// that slice kc - 1 occupied, and has to have landed by the barrier that ends iteration
+// kc + STAGES - 3 (the consumers read the first fragments of a slice one iteration early).  The
+// loads of a wave complete in order, so "at most (STAGES - 3) slices' worth of instructions
+// outstanding" means slice kc + 2 is in LDS.  No LDS reads and no other vector memory
+// instructions occur in this loop, which keeps the instruction count per slice exact.
+template <int DT, int BM, int BN, int STAGES, int PA>
+__device__ __forceinline__ void direct_producer(const GemmArgs &a, float *As, float *Bs, int kc0, int kc1, int mt,
+                                                int krow, int pw, int r0, int vf, const int (&iy0)[PA],
+                                                const int (&ix0)[PA], const int (&base)[PA])
+{
+    constexpr int PB = (BM + kRP - 1) / kRP; // filter-row passes (a tile of 16 channels: two waves repeat the others' rows)
+    constexpr int PS = PA + PB;              // instructions per slice and wave
+    constexpr int ASZ = BN * LDK, BSZ = BM * LDK;
+    static_assert((STAGES - 3) * PS < 64, "outstanding loads must fit the counter");
+    const float *x = static_cast<const float *>(a.x);
+    const floatx4 *wrow = static_cast<const floatx4 *>(a.wt) + (size_t)(mt * BM + (r0 % BM)) * krow + vf;
+    auto issue = [&](int kc, int slot) {
+        // tap of this lane's unit in slice kc: unit index -> (filter tap, channel unit) -> (j, i)
+        const int q = kc * KU + vf;
+        const int tap = fast_div(q, a.dVin), cu = q - tap * a.dVin.d;
+        const int tj = fast_div(tap, a.dKw), ti = tap - tj * a.kw;
+        const bool tv = tj < a.kh;
+        const int off = (tj * a.W + ti) * a.pix_words + cu * 4;
+        float *A = As + slot * ASZ + pw * 8 * LDK, *B = Bs + slot * BSZ + (pw * 8 % BM) * LDK;
+#pragma unroll
+        for (int ps = 0; ps < PA; ++ps) {
+            const bool ok = tv && (unsigned)(iy0[ps] + tj) < (unsigned)a.H && (unsigned)(ix0[ps] + ti) < (unsigned)a.W;
+            const unsigned idx = ok ? (unsigned)(base[ps] + off) : (unsigned)a.zero_word;
+            __builtin_amdgcn_global_load_lds((GlobalPtr)(x + idx), (LdsPtr)(A + kRP * ps * LDK), 16, 0, 0);
+        }
+#pragma unroll
+        for (int ps = 0; ps < PB; ++ps)
+            __builtin_amdgcn_global_load_lds((GlobalPtr)(wrow + (size_t)(kRP * ps) * krow + kc * KU),
+                                             (LdsPtr)(B + kRP * ps * LDK), 16, 0, 0);
+    };
+    // Nothing of this wave is in flight here; saying so keeps the compiler, which tracks loads into
+    // registers along every path through the kernel, from waiting for imagined ones inside the loop.
+    wait_vmcnt<0>();
+    // prologue: STAGES - 1 slices in flight, the first two landed
+#pragma unroll
+    for (int d = 0; d < STAGES - 1; ++d)
+        if (kc0 + d < kc1) issue(kc0 + d, d);
+    if (kc0 + STAGES - 2 < kc1)
+        wait_vmcnt<(STAGES - 3) * PS>();
+    else
+        wait_vmcnt<0>();
+    producer_barrier();
+    int slot = STAGES - 1; // ring slot of slice kc + STAGES - 1
+    for (int kc = kc0; kc < kc1; ++kc) {
+        if (kc + STAGES - 1 < kc1) {
+            issue(kc + STAGES - 1, slot);
+            wait_vmcnt<(STAGES - 3) * PS>();
+        } else {
+            wait_vmcnt<0>();
+        }
+        slot = slot == STAGES - 1 ? 0 : slot + 1;
+        producer_barrier();
+    }
+}
+
 // BM x BN workgroup tile; the consumer waves are arranged WM (channels) x WN (pixels).
 //
 // LDS holds a ring of three K slices.  In iteration kc the producers store slice kc+2 and issue
 // the global loads of a slice two or three further on (one per register set), while the consumers
 // multiply slice kc and already read the first fragments of slice kc+1, so the matrix pipeline
 // keeps running across the one barrier per slice.
-template <int DT, int BM, int BN, int WM, int WN>
+template <int DT, int BM, int BN, int WM, int WN, int STAGES, bool DIRECT>
 __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n, float *smem, const Selection sel)
 {
     static_assert(WM * WN == kConsWaves, "one sub-tile per consumer wave");
+    static_assert(DIRECT ? STAGES >= 3 : STAGES == kStagedRing, "ring depth");
     constexpr int TP = BN / WN / 16; // 16-pixel MFMA tiles per consumer wave
     constexpr int TC = BM / WM / 16; // 16-channel MFMA tiles per consumer wave
     constexpr int PA = BN / kRP;     // image-matrix rows staged per producer thread and slice
     constexpr int PB = (BM + kRP - 1) / kRP;
-    constexpr int NS = PA + PB <= kThreeSetsUnits ? 3 : 2; // register sets of loads in flight per producer thread
+    constexpr int NS = PA + PB <= kThreeSetsUnits ? 3 : 2; // (register staging) sets of loads in flight per producer thread
     static_assert(BN % kRP == 0, "whole passes over the pixel rows");
     constexpr int ASZ = BN * LDK, BSZ = BM * LDK;
     constexpr int SLAB = BM * BN; // floats of one partial-accumulator slab
@@ -465,9 +563,9 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
     static_assert(BK == 32, "two 16-wide fragment groups per slice");
     static_assert(TC * TP * 4 * NCONS == SLAB, "a slab holds every consumer lane's accumulators");
 
-    float *As = smem;                                      // [3][BN][LDK]  gathered image-matrix slices
-    float *Bs = smem + kStages * ASZ;                      // [3][BM][LDK]  filter-matrix slices
-    int *sU = reinterpret_cast<int *>(Bs + kStages * BSZ); // [BN] listed pixels of this tile (-1: none)
+    float *As = smem;                                     // [STAGES][BN][LDK]  gathered image-matrix slices
+    float *Bs = smem + STAGES * ASZ;                      // [STAGES][BM][LDK]  filter-matrix slices
+    int *sU = reinterpret_cast<int *>(Bs + STAGES * BSZ); // [BN] listed pixels of this tile (-1: none)
     int *sFlag = sU + BN;                                  // ticket of the tile just finished
 
     const int tid = threadIdx.x;
@@ -526,7 +624,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
         const int2 *taps = a.taps + v;
         auto tap = [&](int kc) { return taps[(kc < kc1 ? kc : kc0) * KU]; };
         int2 tp0, tp1, tp[NS];
-        if (producer) {
+        if (producer && !DIRECT) {
             tp0 = tap(kc0);
             tp1 = tap(kc0 + 1);
 #pragma unroll
@@ -555,7 +653,10 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
 
         // Both roles execute the same number of barriers: one after the prologue, one per slice.
         if (producer) {
-            const int vs = v ^ lds_swizzle(r0); // slot of that unit in those rows
+            // staging through registers: this thread loads unit column v and stores it to slot vs;
+            // direct to LDS: the hardware puts lane l's 16 bytes into slot l & 7 of row l >> 3 of the
+            // eight rows an instruction covers, so the thread fetches the unit that belongs there
+            const int vs = v ^ lds_swizzle(r0);
             int iy0[PA], ix0[PA], base[PA];
 #pragma unroll
             for (int ps = 0; ps < PA; ++ps) {
@@ -572,6 +673,9 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                     base[ps] = 0;
                 }
             }
+            if constexpr (DIRECT) {
+                direct_producer<DT, BM, BN, STAGES>(a, As, Bs, kc0, kc1, mt, krow, wave - kConsWaves, r0, vs, iy0, ix0, base);
+            } else {
             // NS register sets: in iteration kc the slice kc+2, loaded NS iterations ago, is stored to
             // the LDS ring and the loads of slice kc+2+NS are issued into the same registers.  The
             // loop runs at the pace of these loads when NS slices of MFMA work are shorter than a
@@ -609,11 +713,12 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                                 tp[u] = tap(kc + u + 2 + 2 * NS);
                             }
                         }
-                        slot = slot == kStages - 1 ? 0 : slot + 1;
+                        slot = slot == kStagedRing - 1 ? 0 : slot + 1;
                         __syncthreads();
                     }
                 }
             }
+            } // register staging
 #pragma unroll
             for (int j = 0; j < TC; ++j)
 #pragma unroll
@@ -667,7 +772,7 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
             read_frags(0, 0, 0);
             int slot = 0; // ring slot of slice kc
             for (int kc = kc0; kc < kc1; ++kc) {
-                const int nslot = slot == kStages - 1 ? 0 : slot + 1;
+                const int nslot = slot == STAGES - 1 ? 0 : slot + 1;
                 // The scheduling barriers pin the order "issue the LDS reads of the next fragment
                 // group, then the MFMAs of the current one", so that LDS latency and bandwidth
                 // are spent while the matrix pipeline is busy.
@@ -851,14 +956,14 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
 // the tile shape that suits it -- BNB listed pixels per tile normally, BNS when even the deepest K
 // split of the big tiles would leave compute units idle (short lists): small tiles then need no
 // or fewer shared tiles, whose partial sums and reduction are pure overhead.
-template <int DT, int BM, int BNB, int WMB, int WNB, int BNS, int WMS, int WNS>
+template <int DT, int BM, int BNB, int WMB, int WNB, int SB, bool DB, int BNS, int WMS, int WNS, int SS, bool DS>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT + 255) / 256, (NT + 255) / 256))) void gemm_gather_kernel(GemmArgs a)
 {
     extern __shared__ __align__(16) float smem[];
     Selection sel = {nullptr, nullptr, 0};
     int n;
     if (a.sel_words > 0) {
-        char *base = reinterpret_cast<char *>(smem) + TileSmem<BM, BNB>::sel_offset;
+        char *base = reinterpret_cast<char *>(smem) + KernelSmem<BM, BNB, SB, BNS, SS>::sel_offset;
         uint64_t *sW = reinterpret_cast<uint64_t *>(base);
         int *sRank = reinterpret_cast<int *>(base + kSelSlots * 8);
         n = rank_selection(a, sW, sRank, sRank + kSelSlots, reinterpret_cast<uint64_t *>(smem));
@@ -870,9 +975,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT + 255) /
     }
     const long long big_tiles = (long long)((n + BNB - 1) / BNB) * (a.Mpad / BM);
     if (big_tiles * kSmallTileFactor >= (long long)gridDim.x)
-        gemm_gather_body<DT, BM, BNB, WMB, WNB>(a, n, smem, sel);
+        gemm_gather_body<DT, BM, BNB, WMB, WNB, SB, DB>(a, n, smem, sel);
     else
-        gemm_gather_body<DT, BM, BNS, WMS, WNS>(a, n, smem, sel);
+        gemm_gather_body<DT, BM, BNS, WMS, WNS, SS, DS>(a, n, smem, sel);
 }
 
 // ---- host side --------------------------------------------------------------------------
@@ -886,6 +991,8 @@ void gemm_set_divisors(GemmArgs &a)
     const int nk = a.Kpad / gemm_k_multiple(a.dtype);
     a.dNk = make_fastdiv(nk > 0 ? nk : 1);
     a.dGrid = make_fastdiv(a.grid > 0 ? a.grid : 1);
+    a.dVin = make_fastdiv(a.pix_words > 0 ? (a.pix_words + 3) / 4 : 1);
+    a.dKw = make_fastdiv(a.kw > 0 ? a.kw : 1);
 }
 
 int gemm_select_max_words(void) { return kSelMaxWords; }
@@ -927,36 +1034,40 @@ int gemm_grid(const GemmArgs &a, int compute_units)
     return (int)(need < W ? need : W);
 }
 
-// BM, big tile (BN, WM, WN), small tile (BN, WM, WN)
-#define CBK_VARIANTS(X) X(16, 256, 1, 8, 128, 1, 8) X(32, 256, 1, 8, 64, 2, 4) X(64, 256, 2, 4, 64, 2, 4) X(128, 128, 2, 4, 64, 4, 2)
+// BM; big tile (BN, WM, WN, ring slices, direct-to-LDS producers); small tile (the same)
+#define CBK_VARIANTS(X)                                         \
+    X(16, 256, 1, 8, 3, false, 128, 1, 8, 3, false)             \
+    X(32, 256, 1, 8, 3, false, 64, 2, 4, 3, false)              \
+    X(64, 256, 2, 4, 3, false, 64, 2, 4, 3, false)              \
+    X(128, 128, 2, 4, 4, true, 64, 4, 2, 5, true)
 
 hipError_t gemm_prepare(void)
 {
     hipError_t e = hipSuccess;
-#define X(BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_)                                                                  \
-    if (e == hipSuccess)                                                                                            \
-        e = hipFuncSetAttribute(                                                                                    \
-            reinterpret_cast<const void *>(&gemm_gather_kernel<kF32, BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_>),      \
-            hipFuncAttributeMaxDynamicSharedMemorySize, TileSmem<BM_, BNB_>::bytes);                                \
-    if (e == hipSuccess)                                                                                            \
-        e = hipFuncSetAttribute(                                                                                    \
-            reinterpret_cast<const void *>(&gemm_gather_kernel<kBF16, BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_>),     \
-            hipFuncAttributeMaxDynamicSharedMemorySize, TileSmem<BM_, BNB_>::bytes);
+#define X(BM_, BNB_, WMB_, WNB_, SB_, DB_, BNS_, WMS_, WNS_, SS_, DS_)                                                        \
+    if (e == hipSuccess)                                                                                                      \
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(                                                               \
+                                    &gemm_gather_kernel<kF32, BM_, BNB_, WMB_, WNB_, SB_, DB_, BNS_, WMS_, WNS_, SS_, DS_>),   \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, KernelSmem<BM_, BNB_, SB_, BNS_, SS_>::bytes);    \
+    if (e == hipSuccess)                                                                                                      \
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(                                                               \
+                                    &gemm_gather_kernel<kBF16, BM_, BNB_, WMB_, WNB_, SB_, DB_, BNS_, WMS_, WNS_, SS_, DS_>),  \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, KernelSmem<BM_, BNB_, SB_, BNS_, SS_>::bytes);
     CBK_VARIANTS(X)
 #undef X
     return e;
 }
 
-template <int BM, int BNB, int WMB, int WNB, int BNS, int WMS, int WNS>
+template <int BM, int BNB, int WMB, int WNB, int SB, bool DB, int BNS, int WMS, int WNS, int SS, bool DS>
 static hipError_t launch(hipStream_t st, const GemmArgs &a, const Timing &tm)
 {
-    constexpr int smem_bytes = TileSmem<BM, BNB>::bytes;
+    constexpr int smem_bytes = KernelSmem<BM, BNB, SB, BNS, SS>::bytes;
     if (a.dtype == kBF16)
-        launch_kernel(tm, gemm_gather_kernel<kBF16, BM, BNB, WMB, WNB, BNS, WMS, WNS>, dim3(a.grid), dim3(NT), smem_bytes,
-                      st, a);
+        launch_kernel(tm, gemm_gather_kernel<kBF16, BM, BNB, WMB, WNB, SB, DB, BNS, WMS, WNS, SS, DS>, dim3(a.grid),
+                      dim3(NT), smem_bytes, st, a);
     else
-        launch_kernel(tm, gemm_gather_kernel<kF32, BM, BNB, WMB, WNB, BNS, WMS, WNS>, dim3(a.grid), dim3(NT), smem_bytes,
-                      st, a);
+        launch_kernel(tm, gemm_gather_kernel<kF32, BM, BNB, WMB, WNB, SB, DB, BNS, WMS, WNS, SS, DS>, dim3(a.grid),
+                      dim3(NT), smem_bytes, st, a);
     return hipGetLastError();
 }
 
@@ -968,6 +1079,7 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm)
         !a.tickets || a.grid < 8 || (a.grid & 7) || a.grid > kMaxGrid)
         return hipErrorInvalidValue;
     // the divisors must belong to these arguments, and the schedule's 32-bit arithmetic must hold
+    if (a.kh < 1 || a.kw < 1 || a.dKw.d != a.kw || a.dVin.d != (a.pix_words + 3) / 4) return hipErrorInvalidValue;
     if (a.dNo.d != a.No || a.dWo.d != a.Wo || a.dHo.d * a.Wo != a.No || a.dGrid.d != a.grid ||
         a.dNk.d != a.Kpad / gemm_k_multiple(a.dtype) || a.dNk.d >= (1 << 20))
         return hipErrorInvalidValue;
@@ -979,8 +1091,8 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm)
     if (a.sel_words < 0 || a.sel_words > kSelMaxWords || (a.sel_words > 0 && !a.sel_map) ||
         (a.sel_words == 0 && (!a.list || !a.count)) || (long long)a.sel_words * 64 < a.max_pixels * (a.sel_words > 0))
         return hipErrorInvalidValue;
-#define X(BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_) \
-    if (bm == BM_) return launch<BM_, BNB_, WMB_, WNB_, BNS_, WMS_, WNS_>(st, a, tm);
+#define X(BM_, BNB_, WMB_, WNB_, SB_, DB_, BNS_, WMS_, WNS_, SS_, DS_) \
+    if (bm == BM_) return launch<BM_, BNB_, WMB_, WNB_, SB_, DB_, BNS_, WMS_, WNS_, SS_, DS_>(st, a, tm);
     CBK_VARIANTS(X)
 #undef X
     return hipErrorInvalidValue;

@@ -429,7 +429,9 @@ __global__ __launch_bounds__(kBlock) void dilate_kernel(const uint64_t *__restri
 // dilation with that window at stride 2.  The workgroup also leaves the number of set bits of
 // its words, which is what the index extraction needs to place its output.
 // ------------------------------------------------------------------------------------------
-static constexpr int kCompactWords = 128; // words per workgroup of the index extraction
+static constexpr int kCompactWords = 512; // words per workgroup of the index extraction: two per thread
+static constexpr int kCompactStage = 4096; // list entries a workgroup stages in LDS (16 KiB); more go straight to the list
+static constexpr int kCompactDense = 12;   // words with more set bits than this are expanded by a whole wave
 static constexpr int kCountWords = 32;    // words per entry of the group-count arrays
 static constexpr int kWordLanes = 8;
 static constexpr int kRegionWords = 4096; // LDS bitmap of the input piece: 32 KiB
@@ -527,12 +529,13 @@ struct DilateWords {
     FastDiv dWo, dHo, dWp, dHp;
     int upd_words, pool_words, chg_words;
     int upd_blocks, pool_blocks; // workgroups per role, in this order; the rest count the change map
+    int region_words;            // capacity of the LDS piece in words
 };
 
 template <bool BYTES>
 __global__ __launch_bounds__(kBlock) void dilate_words_kernel(DilateWords a)
 {
-    __shared__ uint64_t sM[kRegionWords + 2];
+    extern __shared__ uint64_t sM[]; // region_words + 2 words: the piece of the change map this workgroup reads
     __shared__ int swave[kBlock / 64];
     const DilateGeom &g = a.g;
     const int tid = threadIdx.x, r = tid & (kWordLanes - 1);
@@ -564,7 +567,7 @@ __global__ __launch_bounds__(kBlock) void dilate_words_kernel(DilateWords a)
         int w_hi = (((st_hi * g.H + iy_hi) * g.W + g.W - 1) >> 6) + 1; // one past the last word
         if (w_hi > a.chg_words) w_hi = a.chg_words;
         int nw = w_hi - w_lo;
-        if (nw > kRegionWords) nw = kRegionWords; // the host launches this kernel only if every piece fits
+        if (nw > a.region_words) nw = a.region_words; // the host sizes the LDS for the largest piece
         const int bit0 = w_lo * 64;
         if (BYTES) {
             unsigned char *sB = reinterpret_cast<unsigned char *>(sM);
@@ -670,10 +673,16 @@ hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, 
         a.upd_blocks = (a.upd_words + kCountWords - 1) / kCountWords;
         a.pool_blocks = (a.pool_words + kCountWords - 1) / kCountWords;
         const int grid = a.upd_blocks + a.pool_blocks + (count ? (a.chg_words + kCountWords - 1) / kCountWords : 0);
+        // LDS for the largest piece any workgroup reads (at most kRegionWords, or dilate_counts() is
+        // false): small pieces leave room for more workgroups per compute unit
+        long long rw = dilate_region_words(g, false);
+        if (pooled && dilate_region_words(g, true) > rw) rw = dilate_region_words(g, true);
+        a.region_words = (int)rw;
+        const unsigned lds = (unsigned)(rw + 2) * 8u;
         if (g.chg_bytes)
-            launch_kernel(tm, dilate_words_kernel<true>, dim3(grid), dim3(kBlock), 0, st, a);
+            launch_kernel(tm, dilate_words_kernel<true>, dim3(grid), dim3(kBlock), lds, st, a);
         else
-            launch_kernel(tm, dilate_words_kernel<false>, dim3(grid), dim3(kBlock), 0, st, a);
+            launch_kernel(tm, dilate_words_kernel<false>, dim3(grid), dim3(kBlock), lds, st, a);
         return hipGetLastError();
     }
     const int ub = (g.S * g.Ho * g.Wo + kBlock - 1) / kBlock;
@@ -688,11 +697,18 @@ hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, 
 }
 
 // ------------------------------------------------------------------------------------------
-// Change-index extraction.  Each workgroup owns kCompactWords bitmap words.  It obtains its
-// output offset by counting the set bits of all preceding words itself (the bitmaps are a
-// few KiB to a few hundred KiB and L2 resident, so this is cheaper and simpler than a second
-// launch or a cross-workgroup handshake, and it is deterministic), scans its own words'
-// popcounts, expands the bits into an LDS staging buffer and copies that out coalesced.
+// Change-index extraction.  A workgroup owns kCompactWords bitmap words, two consecutive ones per
+// thread.  Where its output starts it finds out itself, without waiting for anybody: by adding the
+// set-bit counts of all groups of words before its own (left by the dilation kernel or by
+// compact_count_kernel; 16-byte loads, at most 32 KiB from L2), or for small maps by counting the
+// preceding words.  Ordered and deterministic.  The threads scan the popcounts of their words and
+// expand the bits.  A workgroup with at most kCompactStage entries goes through an LDS staging
+// buffer, shifted so that LDS index and global address agree modulo 16 bytes -- a word with few
+// set bits is walked by its holder, a word with many by the whole wave at once (lane b tests bit
+// b and ranks it with a popcount) -- and copies it out with 16-byte stores, every wave writing
+// one contiguous kilobyte.  A workgroup with more (a moving object's solid block of set words)
+// writes straight to the list: completely set words four per wave step with 16-byte stores, the
+// others one per step.
 // ------------------------------------------------------------------------------------------
 struct CompactJobs {
     CompactJob j[3];
@@ -709,84 +725,179 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane)
 }
 
 // Word i (64 pixels) of a job's map as a bit mask.  A byte map (one byte per pixel, nonzero =
-// set) is packed on the fly: the high bit of (x | (x & 0x7f..7f) + 0x7f..7f) marks nonzero bytes,
-// and the multiplication gathers those eight marks into one byte.
+// set) is packed on the fly.
 __device__ __forceinline__ uint64_t map_word(const CompactJob &job, int i)
 {
     if (!job.bytes) return job.bits[i];
     uint64_t w = 0;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const uint64_t x = job.bits[(size_t)i * 8 + k];
-        const uint64_t nz = ((x | ((x & 0x7f7f7f7f7f7f7f7full) + 0x7f7f7f7f7f7f7f7full)) & 0x8080808080808080ull) >> 7;
-        w |= ((nz * 0x0102040810204080ull) >> 56) << (8 * k);
-    }
+    for (int k = 0; k < 8; ++k) w |= (uint64_t)nonzero_bytes(job.bits[(size_t)i * 8 + k]) << (8 * k);
     return w;
 }
 
-// Set bits per workgroup-sized group of words, for maps with so many groups that letting every
-// workgroup recount all preceding words would dominate (see compact_kernel).
+// Set bits per group of kCountWords words, for maps with so many words that letting every
+// workgroup recount all preceding ones would dominate (see compact_kernel).
 __global__ __launch_bounds__(kBlock) void compact_count_kernel(CompactJobs jobs)
 {
     const CompactJob job = jobs.j[blockIdx.y];
-    const int w0 = blockIdx.x * kCompactWords;
-    if (w0 >= job.nwords) return;
-    const int tid = threadIdx.x;
-    if (tid >= kCompactWords) return;
-    int c = w0 + tid < job.nwords ? __popcll(map_word(job, w0 + tid)) : 0;
-    // one entry per kCountWords consecutive words
+    const int i = blockIdx.x * kBlock + threadIdx.x; // one word per thread; a wave covers two groups
+    if (blockIdx.x * kBlock >= job.nwords) return;
+    int c = i < job.nwords ? __popcll(map_word(job, i)) : 0;
 #pragma unroll
     for (int d = kCountWords / 2; d >= 1; d >>= 1) c += __shfl_xor(c, d, 64);
-    if ((tid & (kCountWords - 1)) == 0) job.group_counts[(w0 + tid) / kCountWords] = c;
+    if ((threadIdx.x & (kCountWords - 1)) == 0 && i < job.nwords) job.group_counts[i / kCountWords] = c;
 }
+
+typedef int intx4_a4 __attribute__((ext_vector_type(4), aligned(4))); // four list entries starting at any of them
 
 template <bool TWO_LEVEL>
 __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
 {
-    __shared__ int stage[kCompactWords * 64];
-    __shared__ int swave[4];
-    __shared__ int swave2[4];
+    __shared__ __align__(16) int stage[kCompactStage + 4];
+    __shared__ uint64_t sword[kCompactWords];
+    __shared__ int soff[kCompactWords];
+    __shared__ int2 sfull[kBlock / 64][2 * 64]; // per wave: offset and first position of its completely set words
+    __shared__ int swave[kBlock / 64];
+    __shared__ int swave2[kBlock / 64];
     const CompactJob job = jobs.j[blockIdx.y];
     const int w0 = blockIdx.x * kCompactWords;
     if (w0 >= job.nwords) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
+    // this workgroup's words: for the scan thread t holds words 2t and 2t + 1 of them
+    {
+        const int i0 = w0 + 2 * tid;
+        uint64_t m0 = 0, m1 = 0;
+        if (!job.bytes && i0 + 1 < job.nwords) {
+            const ulonglong2 v = *reinterpret_cast<const ulonglong2 *>(job.bits + i0);
+            m0 = v.x;
+            m1 = v.y;
+        } else {
+            if (i0 < job.nwords) m0 = map_word(job, i0);
+            if (i0 + 1 < job.nwords) m1 = map_word(job, i0 + 1);
+        }
+        const int c0 = __popcll(m0), sum = c0 + __popcll(m1);
+        const int incl = wave_incl_scan(sum, lane);
+        if (lane == 63) swave2[wave] = incl;
+        sword[2 * tid] = m0;
+        sword[2 * tid + 1] = m1;
+        soff[2 * tid] = incl - sum;          // still without the waves before this one
+        soff[2 * tid + 1] = incl - sum + c0;
+    }
+    __syncthreads();
+    int total = 0, wave_off[kBlock / 64];
+#pragma unroll
+    for (int i = 0; i < kBlock / 64; ++i) {
+        wave_off[i] = total;
+        total += swave2[i];
+    }
+    const bool last = w0 + kCompactWords >= job.nwords;
+    if (total == 0 && !last) return; // nothing to write: most workgroups of a quiet scene end here
+
     // set bits in all words before this workgroup's
     int before = 0;
     if (TWO_LEVEL) {
-        for (int i = tid; i < (int)blockIdx.x * (kCompactWords / kCountWords); i += kBlock) before += job.group_counts[i];
+        const int4 *g4 = reinterpret_cast<const int4 *>(job.group_counts);
+        const int n4 = (int)blockIdx.x * (kCompactWords / kCountWords / 4);
+        for (int i = tid; i < n4; i += kBlock) {
+            const int4 v = g4[i];
+            before += v.x + v.y + v.z + v.w;
+        }
     } else {
         for (int i = tid; i < w0; i += kBlock) before += __popcll(map_word(job, i));
     }
-    before = wave_incl_scan(before, lane);
-    if (lane == 63) swave[wave] = before;
-
-    // this workgroup's words, one per thread of the first two waves
-    uint64_t mine = 0;
-    if (tid < kCompactWords && w0 + tid < job.nwords) mine = map_word(job, w0 + tid);
-    const int cnt = __popcll(mine);
-    const int incl = wave_incl_scan(cnt, lane);
-    if (lane == 63) swave2[wave] = incl;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) before += __shfl_xor(before, d, 64);
+    if (lane == 0) swave[wave] = before;
     __syncthreads();
-    const int prefix = swave[0] + swave[1] + swave[2] + swave[3];
-    int off = incl - cnt;
-    for (int i = 0; i < wave; ++i) off += swave2[i];
-    const int total = swave2[0] + swave2[1] + swave2[2] + swave2[3];
-
-    const int pos0 = (w0 + tid) * 64;
-    while (mine) {
-        const int b = __ffsll((unsigned long long)mine) - 1;
-        stage[off++] = pos0 + b;
-        mine &= mine - 1ull;
+    int prefix = 0;
+#pragma unroll
+    for (int i = 0; i < kBlock / 64; ++i) prefix += swave[i];
+    // For the expansion the words are dealt out again: lane l of wave v takes words 4 l + v and
+    // 256 + 4 l + v, so that of any run of consecutive words -- a solid block of set words, say --
+    // each wave holds a quarter.
+    uint64_t m[2];
+    int c[2], o[2], pos[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int wi = 256 * h + 4 * lane + wave;
+        m[h] = sword[wi];
+        c[h] = __popcll(m[h]);
+        o[h] = soff[wi] + wave_off[h * 2 + (lane >> 5)]; // word wi was scanned by thread wi / 2, of wave wi / 128
+        pos[h] = (w0 + wi) * 64;
     }
-    __syncthreads();
-    for (int i = tid; i < total; i += kBlock) job.list[prefix + i] = stage[i];
-    if (tid == 0 && w0 + kCompactWords >= job.nwords) *job.count = prefix + total;
+    int *dst = job.list + prefix;
+    if (total > kCompactStage) {
+        // Many entries: straight to the list.  Completely set words -- the inside of a moving object --
+        // four at a time: each quarter of the wave writes the 64 consecutive positions of one of them
+        // as sixteen 16-byte stores.  Any other word by the whole wave at once: lane b tests bit b, ranks
+        // it with a popcount, and the set lanes write consecutive entries.
+        const uint64_t below = (1ull << lane) - 1ull;
+        int nfull = 0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const bool full = c[h] == 64;
+            const uint64_t fb = __ballot(full);
+            if (full) sfull[wave][nfull + __popcll(fb & below)] = make_int2(o[h], pos[h]);
+            nfull += __popcll(fb);
+            uint64_t todo = __ballot(c[h] > 0 && !full);
+            while (todo) {
+                const int src = __ffsll((unsigned long long)todo) - 1;
+                todo &= todo - 1ull;
+                const uint64_t w = ((uint64_t)(unsigned)__builtin_amdgcn_readlane((int)(m[h] >> 32), src) << 32) |
+                                   (unsigned)__builtin_amdgcn_readlane((int)m[h], src);
+                const int ow = __builtin_amdgcn_readlane(o[h], src), pw = __builtin_amdgcn_readlane(pos[h], src);
+                if ((w >> lane) & 1ull) dst[ow + __popcll(w & below)] = pw + lane;
+            }
+        }
+        __builtin_amdgcn_wave_barrier(); // sfull[wave] is written and read by this wave only
+        for (int j = lane >> 4; j < nfull; j += 4) {
+            const int2 e = sfull[wave][j];
+            const int q = 4 * (lane & 15);
+            *reinterpret_cast<intx4_a4 *>(dst + e.x + q) = (intx4_a4){e.y + q, e.y + q + 1, e.y + q + 2, e.y + q + 3};
+        }
+    } else {
+        // few: through the staging buffer, shifted so that dst[e] and stage[e + shift] are aligned alike
+        const int shift = (int)((reinterpret_cast<uintptr_t>(dst) >> 2) & 3);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (c[h] > 0 && c[h] <= kCompactDense) { // a word with few set bits: its holder walks them
+                int e = o[h] + shift;
+                uint64_t r = m[h];
+                while (r) {
+                    stage[e++] = pos[h] + __ffsll((unsigned long long)r) - 1;
+                    r &= r - 1ull;
+                }
+            }
+            uint64_t todo = __ballot(c[h] > kCompactDense); // one with many: the whole wave, one step
+            while (todo) {
+                const int src = __ffsll((unsigned long long)todo) - 1;
+                todo &= todo - 1ull;
+                const uint64_t w = ((uint64_t)(unsigned)__builtin_amdgcn_readlane((int)(m[h] >> 32), src) << 32) |
+                                   (unsigned)__builtin_amdgcn_readlane((int)m[h], src);
+                const int ow = __builtin_amdgcn_readlane(o[h], src), pw = __builtin_amdgcn_readlane(pos[h], src);
+                if ((w >> lane) & 1ull) stage[ow + shift + __popcll(w & ((1ull << lane) - 1ull))] = pw + lane;
+            }
+        }
+        __syncthreads();
+        int head = (4 - shift) & 3; // entries before the first 16-byte boundary of dst
+        if (head > total) head = total;
+        if (tid < head) dst[tid] = stage[tid + shift];
+        const int body = (total - head) >> 2;
+        const int4 *s4 = reinterpret_cast<const int4 *>(stage + head + shift); // a multiple of four ints (or body == 0)
+        int4 *d4 = reinterpret_cast<int4 *>(dst + head);
+        for (int j = tid; j < body; j += kBlock) d4[j] = s4[j];
+        const int done = head + 4 * body;
+        if (tid < total - done) dst[done + tid] = stage[done + tid + shift];
+    }
+    if (tid == 0 && last) *job.count = prefix + total;
 }
 
-bool compact_two_level(int nwords) { return nwords > kCompactWords * 48; }
+bool compact_two_level(int nwords) { return nwords > 6144; }
 
-size_t compact_group_count_bytes(int nwords) { return ((size_t)nwords / kCountWords + 8) * sizeof(int); }
+// a multiple of 16 bytes, so that the arrays of a layer's three maps, one behind the other, all
+// start on a 16-byte boundary
+size_t compact_group_count_bytes(int nwords) { return (((size_t)nwords / kCountWords + 8 + 3) & ~(size_t)3) * sizeof(int); }
 
 hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, bool groups_ready, const Timing &tm)
 {
@@ -797,14 +908,18 @@ hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, bool group
         js.j[i] = jobs[i < njobs ? i : 0];
         if (i < njobs && jobs[i].nwords > maxw) maxw = jobs[i].nwords;
     }
+    for (int i = 0; i < njobs; ++i) // 16-byte loads of word pairs
+        if (!jobs[i].bits || reinterpret_cast<uintptr_t>(jobs[i].bits) % 16 || !jobs[i].list || !jobs[i].count) return hipErrorInvalidValue;
     const int gx = (maxw + kCompactWords - 1) / kCompactWords;
     if (groups_ready || compact_two_level(maxw)) {
         for (int i = 0; i < njobs; ++i)
             if (!jobs[i].group_counts) return hipErrorInvalidValue;
+        for (int i = 0; i < njobs; ++i)
+            if (reinterpret_cast<uintptr_t>(jobs[i].group_counts) % 16) return hipErrorInvalidValue;
         if (groups_ready) {
             launch_kernel(tm, compact_kernel<true>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
         } else {
-            launch_kernel(Timing{tm.start, nullptr}, compact_count_kernel, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+            launch_kernel(Timing{tm.start, nullptr}, compact_count_kernel, dim3((maxw + kBlock - 1) / kBlock, njobs), dim3(kBlock), 0, st, js);
             launch_kernel(Timing{nullptr, tm.stop}, compact_kernel<true>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
         }
     } else {
@@ -868,6 +983,56 @@ __device__ __forceinline__ void pool_unit(bool active, int g, int v, const uint4
     if (active) pooled[(long long)g * V + v] = m;
 }
 
+// The 2 x 2 window, kPoolBatch items per thread: the list entries (or map bits) of all items are
+// fetched first, then all window values (and the values about to be replaced), so that a thread
+// has up to 4 * kPoolBatch 16-byte loads in flight instead of one dependent round trip after the
+// other -- on maps of millions of positions the kernel is bound by exactly that latency.
+static constexpr int kPoolBatch = 4;
+
+template <int DT>
+__device__ __forceinline__ void pool_batch_2x2(const bool (&active)[kPoolBatch], const int (&g)[kPoolBatch],
+                                               const int (&v)[kPoolBatch], const uint4 *__restrict__ in,
+                                               uint4 *__restrict__ pooled, const PoolGeom &pg,
+                                               unsigned char *__restrict__ next_flags, float next_tau, int next_force)
+{
+    const int V = pg.V, lane = threadIdx.x & 63;
+    const bool pow2 = (V & (V - 1)) == 0 && V <= 64;
+    const bool compare = next_flags != nullptr && !next_force;
+    uint4 w[kPoolBatch][4], old[kPoolBatch];
+#pragma unroll
+    for (int k = 0; k < kPoolBatch; ++k) {
+        if (!active[k]) continue;
+        const int st = fast_div(g[k], pg.dNp), pp = g[k] - st * pg.Np;
+        const int py = fast_div(pp, pg.dWp), px = pp - py * pg.Wp;
+        const long long base = ((long long)st * pg.No + (long long)(py * 2) * pg.Wo + px * 2) * V + v[k];
+        w[k][0] = in[base];
+        w[k][1] = in[base + V];
+        w[k][2] = in[base + (long long)pg.Wo * V];
+        w[k][3] = in[base + (long long)pg.Wo * V + V];
+        if (compare) old[k] = pooled[(long long)g[k] * V + v[k]];
+    }
+#pragma unroll
+    for (int k = 0; k < kPoolBatch; ++k) {
+        uint4 m = make_uint4(0u, 0u, 0u, 0u);
+        bool f = false;
+        if (active[k]) {
+            m = unit_max<DT>(unit_max<DT>(w[k][0], w[k][1]), unit_max<DT>(w[k][2], w[k][3]));
+            // change detection of the layer this map feeds: new value against the one it replaces
+            if (next_flags) f = next_force != 0 || unit_exceeds<DT>(m, old[k], next_tau);
+        }
+        if (next_flags) {
+            if (pow2) { // the V lanes of a position sit next to each other in the wave
+                const unsigned long long B = __ballot(f);
+                const unsigned long long grp = (V == 64) ? ~0ull : (((1ull << V) - 1ull) << (lane & ~(V - 1)));
+                if (active[k] && v[k] == 0 && (B & grp) != 0ull) next_flags[g[k]] = 1;
+            } else if (f) {
+                next_flags[g[k]] = 1;
+            }
+        }
+        if (active[k]) pooled[(long long)g[k] * V + v[k]] = m;
+    }
+}
+
 template <int DT>
 __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restrict__ list,
                                                              const int *__restrict__ count,
@@ -876,9 +1041,25 @@ __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restri
                                                              unsigned char *__restrict__ next_flags,
                                                              float next_tau, int next_force)
 {
-    const int total = *count * pg.V; // units: below 2^31 (the maps hold fewer 4-byte words than that)
+    const int total = *count * pg.V; // units: below 2^30 (checked by the host)
     const int step = (int)gridDim.x * kBlock;
     // whole waves iterate together (the last round with some lanes inactive)
+    if (pg.k == 2) {
+        for (int i0 = (int)blockIdx.x * kBlock; i0 < total; i0 += kPoolBatch * step) {
+            bool active[kPoolBatch];
+            int g[kPoolBatch], v[kPoolBatch];
+#pragma unroll
+            for (int k = 0; k < kPoolBatch; ++k) {
+                const long long idx = (long long)i0 + (long long)k * step + (int)threadIdx.x;
+                active[k] = idx < total;
+                const int u = active[k] ? fast_div((int)idx, pg.dV) : 0;
+                v[k] = active[k] ? (int)idx - u * pg.V : 0;
+                g[k] = active[k] ? list[u] : 0;
+            }
+            pool_batch_2x2<DT>(active, g, v, in, pooled, pg, next_flags, next_tau, next_force);
+        }
+        return;
+    }
     for (int i0 = (int)blockIdx.x * kBlock; i0 < total; i0 += step) {
         const int idx = i0 + (int)threadIdx.x;
         const bool active = idx < total;
@@ -886,6 +1067,21 @@ __global__ __launch_bounds__(kBlock) void pool_sparse_kernel(const int *__restri
         const int g = active ? list[u] : 0;
         pool_unit<DT>(active, g, v, in, pooled, pg, next_flags, next_tau, next_force);
     }
+}
+
+// Whether pooled position g is to be recomputed according to the bitmap (over the pooled positions,
+// or from_outputs: over the convolution outputs, any of the k x k under g).
+__device__ __forceinline__ bool pool_bit(const uint64_t *__restrict__ bits, int from_outputs, int g, const PoolGeom &pg)
+{
+    if (!from_outputs) return ((bits[g >> 6] >> (g & 63)) & 1ull) != 0ull;
+    const int st = fast_div(g, pg.dNp), pp = g - st * pg.Np;
+    const int py = fast_div(pp, pg.dWp), px = pp - py * pg.Wp;
+    bool any = false;
+    for (int j = 0; j < pg.k; ++j) {
+        const int q0 = st * pg.No + (py * pg.k + j) * pg.Wo + px * pg.k;
+        for (int i = 0; i < pg.k; ++i) any |= ((bits[(q0 + i) >> 6] >> ((q0 + i) & 63)) & 1ull) != 0ull;
+    }
+    return any;
 }
 
 template <int DT>
@@ -898,24 +1094,27 @@ __global__ __launch_bounds__(kBlock) void pool_masked_kernel(const uint64_t *__r
 {
     const int total = total_px * pg.V;
     const int step = (int)gridDim.x * kBlock;
+    if (pg.k == 2) {
+        for (int i0 = (int)blockIdx.x * kBlock; i0 < total; i0 += kPoolBatch * step) {
+            bool active[kPoolBatch];
+            int g[kPoolBatch], v[kPoolBatch];
+#pragma unroll
+            for (int k = 0; k < kPoolBatch; ++k) {
+                const long long idx = (long long)i0 + (long long)k * step + (int)threadIdx.x;
+                const bool in_range = idx < total;
+                g[k] = in_range ? fast_div((int)idx, pg.dV) : 0;
+                v[k] = in_range ? (int)idx - g[k] * pg.V : 0;
+                active[k] = in_range && pool_bit(bits, from_outputs, g[k], pg);
+            }
+            pool_batch_2x2<DT>(active, g, v, in, pooled, pg, next_flags, next_tau, next_force);
+        }
+        return;
+    }
     for (int i0 = (int)blockIdx.x * kBlock; i0 < total; i0 += step) {
         const int idx = i0 + (int)threadIdx.x;
         bool active = idx < total;
         const int g = active ? fast_div(idx, pg.dV) : 0, v = active ? idx - g * pg.V : 0;
-        if (active) {
-            if (from_outputs) {
-                const int st = fast_div(g, pg.dNp), pp = g - st * pg.Np;
-                const int py = fast_div(pp, pg.dWp), px = pp - py * pg.Wp;
-                bool any = false;
-                for (int j = 0; j < pg.k; ++j) {
-                    const int q0 = st * pg.No + (py * pg.k + j) * pg.Wo + px * pg.k;
-                    for (int i = 0; i < pg.k; ++i) any |= ((bits[(q0 + i) >> 6] >> ((q0 + i) & 63)) & 1ull) != 0ull;
-                }
-                active = any;
-            } else {
-                active = ((bits[g >> 6] >> (g & 63)) & 1ull) != 0ull;
-            }
-        }
+        if (active) active = pool_bit(bits, from_outputs, g, pg);
         pool_unit<DT>(active, g, v, in, pooled, pg, next_flags, next_tau, next_force);
     }
 }
@@ -927,7 +1126,8 @@ hipError_t pool_sparse(hipStream_t st, const int *list, const int *count, int ma
     long long work = (long long)max_count * V;
     if (work >= (1ll << 30) || V < 1 || Np < 1 || Wp < 1) return hipErrorInvalidValue; // 32-bit indices, with room for the grid stride
     const PoolGeom pg = pool_geom(V, k, Wo, No, Wp, Np);
-    long long grid = (work + kBlock - 1) / kBlock;
+    const int per_thread = k == 2 ? kPoolBatch : 1;
+    long long grid = (work + (long long)kBlock * per_thread - 1) / ((long long)kBlock * per_thread);
     if (grid > 2048) grid = 2048;
     if (grid < 1) grid = 1;
     const uint4 *i4 = static_cast<const uint4 *>(in);
@@ -948,7 +1148,8 @@ hipError_t pool_masked(hipStream_t st, const uint64_t *bits, int from_outputs, i
     long long work = (long long)total * V;
     if (work >= (1ll << 30) || V < 1 || Np < 1 || Wp < 1) return hipErrorInvalidValue; // 32-bit indices, with room for the grid stride
     const PoolGeom pg = pool_geom(V, k, Wo, No, Wp, Np);
-    long long grid = (work + kBlock - 1) / kBlock;
+    const int per_thread = k == 2 ? kPoolBatch : 1;
+    long long grid = (work + (long long)kBlock * per_thread - 1) / ((long long)kBlock * per_thread);
     if (grid > 4096) grid = 4096;
     if (grid < 1) grid = 1;
     const uint4 *i4 = static_cast<const uint4 *>(in);
