@@ -416,8 +416,10 @@ __global__ __launch_bounds__(kBlock) void dilate_kernel(const uint64_t *__restri
 }
 
 // ------------------------------------------------------------------------------------------
-// Dilation a word at a time, for stride-1 layers with filters up to 16 wide (and a 2 x 2
-// pooling behind them, if any).  A workgroup produces kCountWords words of the update map or of
+// Dilation a word at a time, for layers of stride 1 with filters up to 16 wide (and a 2 x 2
+// pooling behind them, if any) and of stride 2 without pooling behind them (Section 3: a strided
+// convolution drops the unused columns of the image matrix; here it keeps every other bit of the
+// dilated row).  A workgroup produces kCountWords words of the update map or of
 // the pooled map, or counts as many of the change map.  It first brings the input rows its
 // outputs read -- a contiguous piece of the change map -- into LDS as bits (a byte map is packed
 // on the way): one round of coalesced loads, everything after that reads LDS.  Eight lanes then
@@ -559,9 +561,13 @@ __global__ __launch_bounds__(kBlock) void dilate_words_kernel(DilateWords a)
         const int r_lo = fast_div(q_lo, dper), r_hi = fast_div(q_hi, dper);
         const int st_lo = fast_div(r_lo, drows), st_hi = fast_div(r_hi, drows);
         const int y_lo = r_lo - st_lo * rows, y_hi = r_hi - st_hi * rows;
-        const int up = role == 0 ? 1 : 2; // output rows per row of this map
+        // a row (column) of this map steps `up` input rows (columns) and reads nrows (ncols) of them:
+        // the filter's own reach for the update map of a layer of stride 1 or 2; for the pooled map
+        // (stride-1 layers only) the kh + 1 rows that the 2 x 2 outputs under a pooled position tile
+        const int up = role == 0 ? g.stride : 2;
+        const int nrows = role == 0 ? g.kh : g.kh + 1;
         const int iy_lo = up * y_lo - g.pad > 0 ? up * y_lo - g.pad : 0;
-        int iy_hi = up * y_hi + (up - 1) - g.pad + g.kh - 1;
+        int iy_hi = up * y_hi - g.pad + nrows - 1;
         if (iy_hi > g.H - 1) iy_hi = g.H - 1;
         const int w_lo = ((st_lo * g.H + iy_lo) * g.W) >> 6;
         int w_hi = (((st_hi * g.H + iy_hi) * g.W + g.W - 1) >> 6) + 1; // one past the last word
@@ -586,10 +592,15 @@ __global__ __launch_bounds__(kBlock) void dilate_words_kernel(DilateWords a)
             while (pos < p1) { // one piece of a row at a time
                 const int len = per - x < p1 - pos ? per - x : p1 - pos;
                 uint64_t bits;
-                if (role == 0) {
+                if (role == 0 && g.stride == 1) {
                     Window wd = rows_or(sM, bit0, g, st, y - g.pad, g.kh, x - g.pad, len + g.kw - 1, r, kWordLanes);
                     spread(wd, g.kw);
                     bits = wd.w[0];
+                } else if (role == 0) { // stride 2: the dilation at every input column, then every other bit
+                    Window wd = rows_or(sM, bit0, g, st, 2 * y - g.pad, g.kh, 2 * x - g.pad, 2 * (len - 1) + g.kw, r,
+                                        kWordLanes);
+                    spread(wd, g.kw);
+                    bits = even_bits(wd.w[0]) | (even_bits(wd.w[1]) << 32);
                 } else {
                     Window wd = rows_or(sM, bit0, g, st, 2 * y - g.pad, g.kh + 1, 2 * x - g.pad, 2 * len + g.kw - 1, r,
                                         kWordLanes);
@@ -641,14 +652,15 @@ static long long dilate_region_words(const DilateGeom &g, bool pooled)
     // outputs' own rows, the filter's reach at both ends, and per stream boundary crossed the
     // rows by which a stream's input is taller than the output rows that count here; never more
     // than all input rows of those streams
-    long long in_rows = (pooled ? 2 : 1) * out_rows + (g.kh + 1) * (streams + 1);
+    long long in_rows = (pooled ? 2 : g.stride) * out_rows + (g.kh + 2) * (streams + 1);
     if (in_rows > (streams + 1) * g.H) in_rows = (streams + 1) * g.H;
     return in_rows * g.W / 64 + 2;
 }
 
 bool dilate_counts(const DilateGeom &g)
 {
-    return g.stride == 1 && g.kw >= 1 && g.kw <= 16 && g.kh >= 1 && (g.pool_k == 0 || g.pool_k == 2) &&
+    return (g.stride == 1 || (g.stride == 2 && g.pool_k == 0)) && g.kw >= 1 && g.kw <= 16 && g.kh >= 1 &&
+           (g.pool_k == 0 || g.pool_k == 2) &&
            (long long)g.S * g.H * g.W < (1ll << 31) && (long long)g.S * g.Ho * g.Wo < (1ll << 31) &&
            dilate_region_words(g, false) <= kRegionWords && (g.pool_k == 0 || dilate_region_words(g, true) <= kRegionWords);
 }

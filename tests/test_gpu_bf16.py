@@ -159,3 +159,29 @@ def test_vgg_layer_full_size_sampled_bf16():
                        n_objects=5)
     frames = [v.frame(t) for t in range(3)]
     compare_sampled(L, (w, b), frames, cfg.tau, n_samples=400, label="vgg L1 640x480 bf16", bf16=True)
+
+
+@pytest.mark.parametrize("shape", [
+    # C, M, H, W -- the first and the last layer shape of the VGG-style workload
+    (3, 64, 480, 640),
+    (512, 512, 60, 80),
+])
+def test_vgg_layer_shapes_full_size_sampled(shape):
+    """bfloat16 storage at the workload's full size: exact lists on the whole maps, feature values on
+    sampled positions the oracle computes one by one (K = 27 and K = 4608)."""
+    from gpu_util import compare_sampled
+    from workloads import conv, make_weights
+    C, M, H, W = shape
+    L = conv(C, M, 3)
+    params = make_weights([L], 4000 + C)[0]
+    r = np.random.default_rng(C)
+    x = r.random((C, H, W), dtype=np.float32)
+    seq = [x]
+    for t in range(1, 3):
+        y = seq[-1].copy()
+        for _ in range(6):
+            h, w = int(r.integers(3, 12)), int(r.integers(3, 16))
+            y0, x0 = int(r.integers(0, H - h)), int(r.integers(0, W - w))
+            y[:, y0:y0 + h, x0:x0 + w] = r.random((C, h, w), dtype=np.float32)
+        seq.append(y)
+    compare_sampled(L, params, seq, 0.05, bf16=True, n_samples=300, label="vgg layer %s" % (shape,))

@@ -8,7 +8,7 @@ import oracle
 import paper_1704_04313_amd as cb
 from workloads import (conv, pool, get_config, make_weights, scene_labeling_net, SyntheticVideo)
 
-from gpu_util import (assert_features_close, compare_sequence, oracle_layer_inputs, to_dev)
+from gpu_util import (assert_features_close, compare_chained, compare_sequence, oracle_layer_inputs, to_dev)
 
 pytestmark = pytest.mark.gpu
 
@@ -164,8 +164,9 @@ def test_threshold_knife_edge_is_strict():
 
 # ------------------------------------------------------------------ whole network
 def test_threshold_zero_equals_dense_mode_bit_for_bit():
-    """Section 3.3: a threshold of zero reproduces the non-change-based result.  On the GPU the
-    change-based and the dense schedule run the same kernels, so the match is exact."""
+    """Section 3.3: a threshold of zero reproduces the non-change-based result.  With noise on every
+    pixel everything is recomputed in every frame, the change-based and the dense schedule then run
+    the same kernels over the same positions, and the match is exact."""
     layers = scene_labeling_net()
     params = make_weights(layers, 8)
     v = _video(48, 64, sigma=0.01, seed=9)
@@ -182,49 +183,40 @@ def test_threshold_zero_equals_dense_mode_bit_for_bit():
     dn.destroy()
 
 
-def _knife_edge(x, ref, tau, eps):
-    d = np.abs(np.abs(x.astype(np.float64) - ref.astype(np.float64)) - tau)
-    return (d < eps).any(axis=0)
-
-
 def test_scene_network_end_to_end_reduced():
-    """Whole network, change-based, against the oracle.  Layer 1 sees identical inputs, so its
-    lists are exact.  Deeper layers see inputs that differ in the last float bits, so a list may
-    differ only at positions whose difference sits on the threshold."""
+    """Whole network, change-based, against the oracle, every layer: the first layer's lists exact,
+    deeper lists different only on the threshold's knife edge, and every value that both sides
+    computed from equivalent data within the float32 tolerance (gpu_util.compare_chained)."""
     layers = scene_labeling_net()
     params = make_weights(layers, 2001)
-    H, W, tau = 80, 96, 0.02
-    v = _video(H, W, sigma=0.005, n_objects=3, seed=40)
-    net = cb.CBInfer(layers, params, (3, H, W), tau)
-    orc = oracle.OracleCBNet(layers, params, tau)
-    conv_ids = [l for l, L in enumerate(layers) if L.kind == "conv"]
-    total_mismatch = 0
+    v = _video(80, 96, sigma=0.005, n_objects=3, seed=40)
+    n_diff, tainted = compare_chained(layers, params, [v.frame(t) for t in range(6)], 0.02, label="scene 96x80")
+    assert tainted <= 0.02
+
+
+def test_threshold_zero_noise_free_video_matches_dense_mode_within_tolerance():
+    """Threshold zero on a noise-free video: most outputs are retained from earlier frames, in which
+    the multiplication split its sums differently (the split along K follows the number of
+    positions), so the match with dense mode is to rounding, not to the bit; the oracle's dense
+    inference is held to the same tolerance (Section 3.3: threshold zero reproduces it)."""
+    layers = scene_labeling_net()
+    params = make_weights(layers, 8)
+    v = _video(48, 64, sigma=0.0, seed=9, n_objects=2)
+    cbn = cb.CBInfer(layers, params, (3, 48, 64), 0.0)
+    dn = cb.CBInfer(layers, params, (3, 48, 64), 0.0)
+    dn.set_mode(True)
+    retained = False
     for t in range(5):
-        f = v.frame(t)
-        prev_ref = [None if r is None else r.copy() for r in orc.ref]
-        want = orc.process_frame(f)
-        got = net.process_frame(to_dev(f)).cpu().numpy()[0]
-        for l in conv_ids:
-            c_gpu = net.read_list(l, cb.LIST_CHANGED)
-            c_or = orc.trace[l]["C"]
-            if l == 0:
-                np.testing.assert_array_equal(c_gpu, c_or)
-                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), orc.trace[l]["U"])
-                assert_features_close(net.read_map(0, cb.MAP_OUTPUT)[0], orc.out[0], "L1 frame %d" % t)
-                continue
-            diff = np.setxor1d(c_gpu, c_or)
-            total_mismatch += diff.size
-            if diff.size:
-                assert t > 0
-                edge = _knife_edge(orc.trace[l]["x"], prev_ref[l], tau, 2e-5).ravel()
-                assert edge[diff].all(), "layer %d frame %d: list differs away from the threshold" % (l, t)
-            assert diff.size <= 0.01 * c_or.size + 2
-        if total_mismatch == 0:
-            assert_features_close(got, want, "network output frame %d" % t)
-        else:
-            bad = np.abs(got - want) > 1e-5 + 1e-4 * np.abs(want)
-            assert bad.mean() < 0.02
-    net.destroy()
+        f = to_dev(v.frame(t))
+        a = cbn.process_frame(f).cpu().numpy()
+        b = dn.process_frame(f).cpu().numpy()
+        assert_features_close(a[0], b[0], "change-based against dense mode, frame %d" % t)
+        assert_features_close(a[0], oracle.dense_forward(layers, params, v.frame(t))[-1], "against O-dense, frame %d" % t)
+        if t:
+            retained |= cbn.layer_counts(4)[1] < 12 * 16
+    assert retained, "every output was recomputed in every frame; the test is too easy"
+    cbn.destroy()
+    dn.destroy()
 
 
 def test_reset_and_mode_switch():

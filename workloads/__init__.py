@@ -7,6 +7,6 @@ thresholding, no index lists, no convolution), so both sides can consume it with
 sharing any part of what is being compared.
 """
 from .video import SyntheticVideo, MovingObject
-from .networks import (LayerSpec, conv, pool, single_layer_net, scene_labeling_net,
+from .networks import (LayerSpec, conv, pool, single_layer_net, scene_labeling_net, strided_net,
                        vgg10_net, make_weights, out_shape, dense_flops)
 from .configs import Config, get_config, SEED_BASE

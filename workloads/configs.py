@@ -10,7 +10,7 @@ from typing import Dict, List, Optional
 
 import numpy as np
 
-from .networks import (LayerSpec, make_weights, scene_labeling_net, single_layer_net, vgg10_net)
+from .networks import (LayerSpec, make_weights, scene_labeling_net, single_layer_net, strided_net, vgg10_net)
 from .video import MovingObject, SyntheticVideo, _rng
 
 SEED_BASE = 170404313
@@ -68,7 +68,7 @@ def _cfg5_count(cfg: Config, stream: int) -> int:
 def get_config(index: int, *, height: Optional[int] = None, width: Optional[int] = None,
                n_frames: Optional[int] = None, sigma: Optional[float] = None,
                change_rate: Optional[float] = None, n_streams: Optional[int] = None) -> Config:
-    """index 1..5 = the five workloads; the keyword arguments make reduced-size or
+    """index 1..5 = the five workloads, 6 = a strided / mixed-filter-size network; the keyword arguments make reduced-size or
     swept replicas of the same recipe (same seeds)."""
     if index == 1:
         c = Config("cfg1-single-7x7", 1, single_layer_net(), 64, 64, 3, 8, 0.02, 0.005,
@@ -95,8 +95,14 @@ def get_config(index: int, *, height: Optional[int] = None, width: Optional[int]
     elif index == 5:
         c = Config("cfg5-64-streams-320x240", 5, scene_labeling_net(), 240, 320, 3, 100, 0.02, 0.005,
                    n_streams=64, video_kwargs={"n_objects_fn": _cfg5_count})
+    elif index == 6:
+        # A strided first layer and other filter sizes (Section 3: a strided convolution drops the unused
+        # columns of the image matrix): conv 5x5 / stride 2, conv 3x3, conv 1x1 on 640x480 frames; the
+        # sensor noise stays below the threshold, so only the moving objects are recomputed.
+        c = Config("cfg6-strided-640x480", 6, strided_net(), 480, 640, 3, 100, 0.02, 0.002,
+                   video_kwargs={"n_objects": 5})
     else:
-        raise ValueError("config index must be 1..5")
+        raise ValueError("config index must be 1..6")
     if height is not None:
         c.height = int(height)
     if width is not None:

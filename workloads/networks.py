@@ -50,6 +50,10 @@ def vgg10_net() -> List[LayerSpec]:
             conv(256, 512, 3), conv(512, 512, 3), conv(512, 512, 3)]
 
 
+def strided_net() -> List[LayerSpec]:
+    return [conv(3, 32, 5, stride=2), conv(32, 64, 3), conv(64, 8, 1, relu=False)]
+
+
 def out_shape(layers: Sequence[LayerSpec], c: int, h: int, w: int) -> List[Tuple[int, int, int]]:
     """Shape (C, H, W) after every layer."""
     shapes = []
