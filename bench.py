@@ -99,6 +99,7 @@ def time_steps(net, frames_dev, out, order):
     t0 = time.perf_counter()
     for p in ptrs:
         net.process_frame_ptr(p, optr)
+    net.flush()
     torch.cuda.synchronize()
     return time.perf_counter() - t0
 
@@ -186,7 +187,7 @@ def measure(cfg, args, *, steps, warmup, blocks, profile=True):
     conv_ids = [l for l, L in enumerate(cfg.layers) if L.kind == "conv"]
     net = cb.CBInfer(cfg.layers, params, in_shape, cfg.tau, n_streams=cfg.n_streams,
                      dtype=cb.BF16 if bf16 else cb.F32, hold_reference=args.hold,
-                     propagate_layers=conv_ids[1:] if args.propagate else ())
+                     propagate_layers=conv_ids[1:] if args.propagate else (), pipeline_frames=args.pipeline)
     out = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
 
     sec_cb = timed_blocks(net, frames_dev, out, cfg.n_frames, warmup, steps, blocks)
@@ -314,6 +315,8 @@ def parse_args(argv=None):
                     help="refresh the stored previous input only where a change was flagged")
     ap.add_argument("--propagate", action="store_true",
                     help="no change detection behind the first layer (worst-case propagation)")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="throughput mode: consecutive frames overlap on two streams of the library")
     ap.add_argument("--frames", type=int, default=0, help="frames generated (default: the workload's)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg (0: skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel timing pass")

@@ -54,7 +54,18 @@ enum {
      * map itself.  Results are the same; cbinfer_read_list / cbinfer_layer_counts then find the
      * lists ready instead of extracting them on demand, at the price of two or three more
      * launches per layer and frame. */
-    CBINFER_FLAG_LISTS_EVERY_FRAME = 2u
+    CBINFER_FLAG_LISTS_EVERY_FRAME = 2u,
+    /* Throughput mode: consecutive frames may overlap on the device.  The library enqueues frames
+     * alternately on two streams of its own (default priority) and keeps two sets of per-frame
+     * scratch (change maps, index lists, partial sums); events make every kernel that overwrites a
+     * stored map of Section 3.2 wait for the previous frame's kernels that still read it, so each
+     * frame sees exactly the state the frame before it left -- results are the same as without the
+     * flag.  What changes is when a frame's output is complete for the caller: cbinfer_process_frame
+     * no longer orders the state's stream behind the frame; cbinfer_flush does (all frames so far),
+     * and so does every introspection call.  Work pending on the state's stream when a frame is
+     * passed in still comes first; frame and output buffers must stay untouched until a flush has
+     * covered their frame.  Costs a second scratch set (cbinfer_workspace_bytes says how much). */
+    CBINFER_FLAG_PIPELINE_FRAMES = 4u
 };
 
 /* One operation of the network, in execution order. */
@@ -134,6 +145,11 @@ size_t cbinfer_static_workspace_bytes(void); /* CBINFER_STATIC_WORKSPACE_BYTES o
  * (cbinfer_set_profiling), when the call returns only after the frame has run and its kernel
  * times have been collected.  Both buffers must stay valid until that work has run. */
 int cbinfer_process_frame(cbinfer_state *s, const void *frame_dev, void *out_dev);
+
+/* With CBINFER_FLAG_PIPELINE_FRAMES: make the state's stream wait for the frame enqueued last (and
+ * with it for all before), so that work enqueued on it afterwards sees their outputs.  Without the
+ * flag: nothing to do.  Does not block the host. */
+int cbinfer_flush(cbinfer_state *s);
 
 /* Forget the video history: the stored previous inputs and outputs of Section 3.2 count as
  * absent, so the next frame is evaluated densely like the first one (all positions flagged, identity

@@ -13,6 +13,7 @@ OP_CONV, OP_MAXPOOL = 0, 1
 F32, BF16 = 0, 1
 FLAG_HOLD_REFERENCE = 1
 FLAG_LISTS_EVERY_FRAME = 2
+FLAG_PIPELINE_FRAMES = 4
 LIST_CHANGED, LIST_UPDATE, LIST_POOLED = 0, 1, 2
 MAP_REFERENCE, MAP_OUTPUT = 0, 1
 STEP_NAMES = ["detect", "dilate", "compact", "gemm", "pool", "output"]
@@ -21,7 +22,7 @@ EXPORTS = [
     "cbinfer_workspace_bytes", "cbinfer_create", "cbinfer_process_frame", "cbinfer_reset",
     "cbinfer_destroy", "cbinfer_last_error", "cbinfer_set_mode", "cbinfer_layer_shape",
     "cbinfer_layer_counts", "cbinfer_read_list", "cbinfer_read_map", "cbinfer_set_profiling",
-    "cbinfer_read_profile", "cbinfer_create_static", "cbinfer_static_workspace_bytes",
+    "cbinfer_read_profile", "cbinfer_create_static", "cbinfer_static_workspace_bytes", "cbinfer_flush",
 ]
 
 
@@ -78,6 +79,8 @@ def load_library():
     lib.cbinfer_static_workspace_bytes.restype = C.c_size_t
     lib.cbinfer_process_frame.argtypes = [st, C.c_void_p, C.c_void_p]
     lib.cbinfer_process_frame.restype = C.c_int
+    lib.cbinfer_flush.argtypes = [st]
+    lib.cbinfer_flush.restype = C.c_int
     lib.cbinfer_reset.argtypes = [st]
     lib.cbinfer_reset.restype = C.c_int
     lib.cbinfer_destroy.argtypes = [st]
@@ -158,7 +161,7 @@ class CBInfer:
     def __init__(self, layers, params, in_shape, tau, *, n_streams: int = 1, hold_reference: bool = False,
                  dense_layers: Sequence[int] = (), caller_workspace: bool = True, dtype: int = F32,
                  propagate_layers: Sequence[int] = (), lists_every_frame: bool = False,
-                 static_workspace: bool = False):
+                 static_workspace: bool = False, pipeline_frames: bool = False):
         import torch
         self._torch = torch
         self.lib = load_library()
@@ -170,7 +173,8 @@ class CBInfer:
         per_layer = None if np.isscalar(tau) else [(-1.0 if t is None else float(t)) for t in tau]
         global_tau = float(tau) if np.isscalar(tau) else 0.0
         keep: list = []
-        flags = (FLAG_HOLD_REFERENCE if hold_reference else 0) | (FLAG_LISTS_EVERY_FRAME if lists_every_frame else 0)
+        flags = ((FLAG_HOLD_REFERENCE if hold_reference else 0) | (FLAG_LISTS_EVERY_FRAME if lists_every_frame else 0) |
+                 (FLAG_PIPELINE_FRAMES if pipeline_frames else 0))
         self.dtype = int(dtype)
         net = _describe(self.layers, params, self.in_shape, n_streams, flags, per_layer, set(dense_layers), keep,
                         self.dtype, set(propagate_layers))
@@ -215,6 +219,9 @@ class CBInfer:
         rc = self.lib.cbinfer_process_frame(self._state, frame_ptr, out_ptr)
         if rc != 0:
             raise CBInferError(rc, _last_error(self.lib))
+
+    def flush(self):
+        self._check(self.lib.cbinfer_flush(self._state))
 
     def reset(self):
         self._check(self.lib.cbinfer_reset(self._state))

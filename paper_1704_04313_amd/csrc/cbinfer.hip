@@ -63,6 +63,9 @@ struct Plan {
     bool hold = false;
     int dtype = cbk::kF32; // storage of maps and filter matrices
     size_t o_iota = 0, o_const = 0, o_partial = 0, o_tickets = 0;
+    bool pipeline = false;     // two sets of per-frame scratch, so that consecutive frames may overlap
+    size_t o_set0 = 0;         // first byte of the per-frame scratch (everything a frame writes except the stored maps)
+    size_t set_bytes = 0;      // its size; with `pipeline` a second set follows directly behind it
     size_t o_flags = 0;        // the byte change maps of all layers behind the first, contiguous
     long long flag_words = 0;  // their total size in 64-bit words
     int compute_units = 256; // sizes the GEMM grids; the device's count replaces it in cbinfer_create
@@ -91,7 +94,7 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
     if (net->n_streams <= 0) return fail(CBINFER_EINVAL, "n_streams must be >= 1");
     if (net->dtype != CBINFER_F32 && net->dtype != CBINFER_BF16)
         return fail(CBINFER_EINVAL, "dtype must be CBINFER_F32 or CBINFER_BF16");
-    if (net->flags & ~(uint32_t)(CBINFER_FLAG_HOLD_REFERENCE | CBINFER_FLAG_LISTS_EVERY_FRAME))
+    if (net->flags & ~(uint32_t)(CBINFER_FLAG_HOLD_REFERENCE | CBINFER_FLAG_LISTS_EVERY_FRAME | CBINFER_FLAG_PIPELINE_FRAMES))
         return fail(CBINFER_EINVAL, "unknown flag bits");
     if (need_threshold && !(threshold >= 0.0f && std::isfinite(threshold))) {
         bool all_own = true;
@@ -104,6 +107,7 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
     P.in_h = net->in_h;
     P.in_w = net->in_w;
     P.hold = (net->flags & CBINFER_FLAG_HOLD_REFERENCE) != 0;
+    P.pipeline = (net->flags & CBINFER_FLAG_PIPELINE_FRAMES) != 0;
     P.dtype = net->dtype == CBINFER_BF16 ? cbk::kBF16 : cbk::kF32;
     const int eu = cbk::elems_per_unit(P.dtype);
     const size_t esz = (size_t)cbk::elem_bytes(P.dtype);
@@ -179,15 +183,13 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
         max_px = std::max(max_px, std::max((long long)P.S * op.H * op.W, (long long)P.S * op.Ho * op.Wo));
         P.ops.push_back(op);
     }
-    // workspace layout
+    // workspace layout: what persists from frame to frame first ...
     Carver cv;
     for (size_t l = 0; l < P.ops.size(); ++l) {
         Op &op = P.ops[l];
         const size_t in_px = (size_t)P.S * op.H * op.W, out_px = (size_t)P.S * op.Ho * op.Wo;
         // every map is followed by one 16-byte unit of zeros, which gathers outside the image read
         op.o_out = cv.take(out_px * op.Ms * esz + 16);
-        op.o_ulist = cv.take(out_px * 4);
-        op.o_counts = cv.take(4 * 4);
         if (op.kind == CBINFER_OP_CONV) {
             // Layers behind the first keep no copy of their previous input unless asked to hold it
             // or to run densely: their previous input is the stored output of the op before them.
@@ -196,6 +198,21 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
             op.o_wt = cv.take((size_t)op.Mpad * op.Kpad * esz);
             op.o_bias = cv.take((size_t)op.Mpad * 4);
             op.o_taps = cv.take((size_t)op.Kpad / eu * sizeof(int2));
+        }
+    }
+    P.iota_len = (int)max_px;
+    P.o_iota = cv.take((size_t)P.iota_len * 4);
+    P.o_const = cv.take(P.ops.size() * 2 * 4);
+    // ... then everything a frame writes besides the stored maps: change maps, index lists, counters,
+    // the multiplication kernel's partial sums and tickets.  Two such sets when consecutive frames
+    // may overlap; state->at() picks the set of the frame in hand.
+    P.o_set0 = cv.off;
+    for (size_t l = 0; l < P.ops.size(); ++l) {
+        Op &op = P.ops[l];
+        const size_t in_px = (size_t)P.S * op.H * op.W, out_px = (size_t)P.S * op.Ho * op.Wo;
+        op.o_ulist = cv.take(out_px * 4);
+        op.o_counts = cv.take(4 * 4);
+        if (op.kind == CBINFER_OP_CONV) {
             // change map of the first layer: one bit per pixel
             if (l == 0) op.o_chg = cv.take(((size_t)words_for((long long)in_px) + 1) * 8);
             op.o_upd = cv.take(((size_t)words_for((long long)out_px) + 1) * 8);
@@ -222,9 +239,6 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
             op.select = !(net->flags & CBINFER_FLAG_LISTS_EVERY_FRAME) &&
                         words_for((long long)P.S * op.Ho * op.Wo) <= cbk::gemm_select_max_words() &&
                         words_for((long long)P.S * op.H * op.W) <= cbk::gemm_select_max_words();
-    P.iota_len = (int)max_px;
-    P.o_iota = cv.take((size_t)P.iota_len * 4);
-    P.o_const = cv.take(P.ops.size() * 2 * 4);
     {
         // sized for the largest grid the GEMM may use (its cap), whatever the device turns out to be
         size_t pb = 0;
@@ -233,6 +247,8 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
         P.o_partial = cv.take(pb);
         P.o_tickets = cv.take(cbk::gemm_ticket_bytes(kMaxGemmGrid));
     }
+    P.set_bytes = cv.off - P.o_set0;
+    if (P.pipeline) cv.off += P.set_bytes;
     P.bytes = cv.off;
     return CBINFER_OK;
 }
@@ -249,6 +265,19 @@ struct cbinfer_state {
     hipStream_t stream = nullptr;
     char *ws = nullptr;
     bool owns_ws = false;
+    // Frames in flight (CBINFER_FLAG_PIPELINE_FRAMES): consecutive frames alternate between two
+    // streams of the library's own and between the two scratch sets; events order every kernel that
+    // overwrites a stored map behind the previous frame's readers of that map.
+    hipStream_t pstream[2] = {nullptr, nullptr};
+    hipEvent_t ev_in = nullptr;
+    std::vector<hipEvent_t> ev_op[2]; // per slot: one per operation (its last kernel) and one for the output copy
+    hipStream_t work = nullptr;       // the stream the kernels of the frame in hand (and of later queries) go to
+    int par = 0;                      // scratch set of the frame in hand / of the last frame
+    bool have_prev = false;           // a frame is (possibly still) running on the other stream
+    int pipe_gap = 3;                 // every pipe_gap-th operation waits for the previous frame (see enqueue_frame):
+                                      // a wait on an event that has not completed costs the host several microseconds,
+                                      // and the frame rate of a small network is bound by exactly that
+    long long frame_index = 0;
     int static_device = -1;   // >= 0: the workspace is that device's static array (cbinfer_create_static)
     bool initialised = false; // a frame has been processed since create/reset
     bool force_dense = false;
@@ -264,8 +293,11 @@ struct cbinfer_state {
     template <class T>
     T *at(size_t off) const
     {
-        return off == SIZE_MAX ? nullptr : reinterpret_cast<T *>(ws + off);
+        if (off == SIZE_MAX) return nullptr;
+        if (off >= plan.o_set0 && off < plan.o_set0 + plan.set_bytes) off += (size_t)par * plan.set_bytes;
+        return reinterpret_cast<T *>(ws + off);
     }
+    bool pipelined() const { return plan.pipeline && !profiling; }
 };
 
 namespace {
@@ -301,7 +333,7 @@ struct StepTimer {
 int collect_profile(cbinfer_state *s)
 {
     if (!s->profiling || s->events_used == 0) return CBINFER_OK;
-    HIP_TRY(hipStreamSynchronize(s->stream));
+    HIP_TRY(hipStreamSynchronize(s->work));
     for (size_t i = 0; i < s->events_used; ++i) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, s->events[i].a, s->events[i].b) == hipSuccess) {
@@ -438,9 +470,9 @@ hipError_t dilate_maps(const cbinfer_state *s, int l, const LayerMaps &m, bool *
         const GroupCounts gc = group_counts(s, l);
         const cbk::DilateGroups dg = {gc.upd, gc.pool, gc.chg};
         *counted = cbk::dilate_counts(g) && (gc.pool != nullptr || !m.pool);
-        return cbk::dilate(s->stream, m.chg, m.upd, m.pool, g, &dg, tm);
+        return cbk::dilate(s->work, m.chg, m.upd, m.pool, g, &dg, tm);
     }
-    return cbk::dilate(s->stream, m.chg, m.upd, m.pool, g, nullptr, tm);
+    return cbk::dilate(s->work, m.chg, m.upd, m.pool, g, nullptr, tm);
 }
 
 // Change-index extraction for op l (and the pooling op behind it): maps -> ascending lists and counts.
@@ -462,14 +494,40 @@ hipError_t extract_lists(const cbinfer_state *s, int l, const LayerMaps &m, bool
         jobs[nj++] = {m.pool, 0, words_for((long long)P.S * pp.Ho * pp.Wo), s->at<int>(pp.o_ulist),
                       s->at<int>(pp.o_counts) + 1, gc.pool};
     }
-    return cbk::compact(s->stream, jobs, nj, counted, tm);
+    return cbk::compact(s->work, jobs, nj, counted, tm);
 }
 
 
 int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
 {
     const Plan &P = s->plan;
-    hipStream_t st = s->stream;
+    const bool pipe = s->pipelined();
+    const int slot = pipe ? (int)(s->frame_index & 1) : s->par, prev = slot ^ 1;
+    hipStream_t st = pipe ? s->pstream[slot] : s->stream;
+    if (pipe && hipStreamQuery(s->stream) != hipSuccess) {
+        // whatever the caller's stream still does (to the frame buffer, say) comes first
+        HIP_TRY(hipEventRecord(s->ev_in, s->stream));
+        HIP_TRY(hipStreamWaitEvent(st, s->ev_in, 0));
+    }
+    s->par = slot;
+    s->work = st;
+    // An operation's kernels overwrite its stored output map, which the previous frame's kernels of
+    // the operation behind it (at the end: the output copy) read; the first layer's detection
+    // overwrites its stored input, which its own multiplication reads.  So before operation l this
+    // frame's stream waits for the previous frame's operation l + 1 -- or for a later one: only every
+    // gap-th operation waits, then for operation l + gap, which covers the operations up to the next
+    // wait as well (both streams run their kernels in order).  Event n_ops stands for the output copy.
+    // An event is recorded by the launch itself: the last kernel of an operation that somebody will
+    // wait for hands it to the launch as its completion event.
+    const int gap = s->pipe_gap, nops_ = (int)P.ops.size();
+    auto after_previous = [&](int l) -> hipError_t {
+        if (!pipe || !s->have_prev || l % gap != 0) return hipSuccess;
+        return hipStreamWaitEvent(st, s->ev_op[prev][l + gap < nops_ ? l + gap : nops_], 0);
+    };
+    auto completion = [&](int ev, cbk::Timing tm) -> cbk::Timing {
+        if (pipe && (ev == nops_ || (ev >= gap && ev % gap == 0))) tm.stop = s->ev_op[slot][ev];
+        return tm;
+    };
     const bool first = !s->initialised;
     s->lists_stale = false;
     const int S = P.S;
@@ -492,10 +550,11 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             const bool fused_in = fuses_detection(P, l, s->force_dense);
             // --- change detection (also turns the planar frame into a map for layer 0)
             if (l == 0) {
+                HIP_TRY(after_previous(0));
                 StepTimer t(s, l, CBINFER_STEP_DETECT);
                 const int hold = (P.hold && !s->force_dense) ? 1 : 0;
                 // the same launch zeroes the byte change maps that this frame's kernels fill in
-                uint64_t *flags = s->force_dense ? nullptr : reinterpret_cast<uint64_t *>(s->ws + P.o_flags);
+                uint64_t *flags = s->force_dense ? nullptr : s->at<uint64_t>(P.o_flags);
                 HIP_TRY(cbk::detect_frame(st, frame, ref, s->at<void>(op.o_cur), s->at<uint64_t>(op.o_chg), op.C,
                                           op.Cs / eu, N, S, op.tau, hold, all ? 1 : 0, P.dtype,
                                           op.pix_words == op.C && op.C % 4 != 0, flags, P.flag_words, t.timing()));
@@ -508,6 +567,7 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                                             P.hold ? 1 : 0, all ? 1 : 0, P.dtype, t.timing()));
                 }
             }
+            if (l > 0) HIP_TRY(after_previous(l));
             const int *ulist = iota;
             const int *ucount = consts + 2 * l;
             const uint64_t *sel_map = nullptr;
@@ -568,9 +628,10 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
             cbk::gemm_set_divisors(a);
             {
                 StepTimer t(s, l, CBINFER_STEP_GEMM);
-                HIP_TRY(cbk::gemm_gather(st, a, t.timing()));
+                HIP_TRY(cbk::gemm_gather(st, a, completion(l, t.timing())));
             }
         } else {
+            HIP_TRY(after_previous(l));
             const Op &cv = P.ops[op.conv_before];
             const int Np = op.Ho * op.Wo;
             const int *plist = s->force_dense ? iota : s->at<int>(op.o_ulist);
@@ -589,19 +650,23 @@ int enqueue_frame(cbinfer_state *s, const float *frame, float *out)
                 HIP_TRY(cbk::pool_masked(st, cm.in_gemm ? cm.upd : cm.pool, cm.in_gemm ? 1 : 0, S * Np,
                                          s->at<void>(cv.o_out), s->at<void>(op.o_out),
                                          op.Ms / cbk::elems_per_unit(P.dtype), op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np,
-                                         next_flags, next_tau, first ? 1 : 0, P.dtype, t.timing()));
+                                         next_flags, next_tau, first ? 1 : 0, P.dtype, completion(l, t.timing())));
             }
             else
                 HIP_TRY(cbk::pool_sparse(st, plist, pcount, S * Np, s->at<void>(cv.o_out), s->at<void>(op.o_out),
                                          op.Ms / cbk::elems_per_unit(P.dtype), op.kh, cv.Wo, cv.Ho * cv.Wo, op.Wo, Np,
-                                         next_flags, next_tau, first ? 1 : 0, P.dtype, t.timing()));
+                                         next_flags, next_tau, first ? 1 : 0, P.dtype, completion(l, t.timing())));
         }
     }
     const Op &last = P.ops.back();
     {
         StepTimer t(s, nops - 1, CBINFER_STEP_OUTPUT);
         HIP_TRY(cbk::map_to_planar(st, s->at<void>(last.o_out), out, last.M, last.Ms / cbk::elems_per_unit(P.dtype),
-                                   last.Ho * last.Wo, S, P.dtype, t.timing()));
+                                   last.Ho * last.Wo, S, P.dtype, completion(nops, t.timing())));
+    }
+    if (pipe) {
+        s->have_prev = true;
+        ++s->frame_index;
     }
     s->initialised = true;
     s->have_frame = true;
@@ -621,6 +686,19 @@ size_t cbinfer_workspace_bytes(const cbinfer_network *net)
     return P.bytes;
 }
 
+static void release_pipeline(cbinfer_state *s)
+{
+    for (int i = 0; i < 2; ++i) {
+        for (hipEvent_t e : s->ev_op[i])
+            if (e) (void)hipEventDestroy(e);
+        s->ev_op[i].clear();
+        if (s->pstream[i]) (void)hipStreamDestroy(s->pstream[i]);
+        s->pstream[i] = nullptr;
+    }
+    if (s->ev_in) (void)hipEventDestroy(s->ev_in);
+    s->ev_in = nullptr;
+}
+
 // Common part of cbinfer_create and cbinfer_create_static.  ws: device memory for the whole
 // workspace (P.bytes, 256-byte aligned) or nullptr to allocate it here.
 static cbinfer_state *create_state(const cbinfer_network *net, const Plan &P, char *ws, int static_device)
@@ -628,6 +706,7 @@ static cbinfer_state *create_state(const cbinfer_network *net, const Plan &P, ch
     cbinfer_state *s = new cbinfer_state();
     s->plan = P;
     s->stream = reinterpret_cast<hipStream_t>(net->stream);
+    s->work = s->stream;
     s->static_device = static_device;
     if (ws) {
         s->ws = ws;
@@ -661,6 +740,15 @@ static cbinfer_state *create_state(const cbinfer_network *net, const Plan &P, ch
 
     auto setup = [&]() -> int {
         HIP_TRY(cbk::gemm_prepare());
+        if (P.pipeline) {
+            // two streams of the library's own (default priority) and the events that order frames in flight
+            HIP_TRY(hipEventCreateWithFlags(&s->ev_in, hipEventDisableTiming));
+            for (int i = 0; i < 2; ++i) {
+                HIP_TRY(hipStreamCreateWithFlags(&s->pstream[i], hipStreamNonBlocking));
+                s->ev_op[i].assign(P.ops.size() + 1, nullptr);
+                for (hipEvent_t &e : s->ev_op[i]) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+            }
+        }
         // everything starts at zero: stored maps and their zero units, change maps, counters, tickets
         // (the static workspace keeps whatever the state before this one left in it)
         HIP_TRY(hipMemsetAsync(s->ws, 0, P.bytes, s->stream));
@@ -690,6 +778,7 @@ static cbinfer_state *create_state(const cbinfer_network *net, const Plan &P, ch
         return CBINFER_OK;
     };
     if (setup() != CBINFER_OK) {
+        release_pipeline(s);
         if (s->owns_ws) (void)hipFree(s->ws);
         delete s;
         return nullptr;
@@ -799,6 +888,17 @@ int cbinfer_process_frame(cbinfer_state *s, const void *frame_dev, void *out_dev
     return enqueue_frame(s, static_cast<const float *>(frame_dev), static_cast<float *>(out_dev));
 }
 
+int cbinfer_flush(cbinfer_state *s)
+{
+    if (!s) return fail(CBINFER_EINVAL, "state is NULL");
+    if (s->broken) return fail(CBINFER_EDEVICE, "a previous HIP call failed; destroy this state");
+    if (s->plan.pipeline && s->have_prev) {
+        const int last = (int)((s->frame_index + 1) & 1); // slot of the frame enqueued last
+        HIP_TRY(hipStreamWaitEvent(s->stream, s->ev_op[last][s->plan.ops.size()], 0));
+    }
+    return CBINFER_OK;
+}
+
 int cbinfer_reset(cbinfer_state *s)
 {
     if (!s) return fail(CBINFER_EINVAL, "state is NULL");
@@ -809,7 +909,10 @@ int cbinfer_reset(cbinfer_state *s)
 void cbinfer_destroy(cbinfer_state *s)
 {
     if (!s) return;
+    for (int i = 0; i < 2; ++i)
+        if (s->pstream[i]) (void)hipStreamSynchronize(s->pstream[i]);
     (void)hipStreamSynchronize(s->stream);
+    release_pipeline(s);
     for (auto &e : s->events) {
         if (e.a) (void)hipEventDestroy(e.a);
         if (e.b) (void)hipEventDestroy(e.b);
@@ -820,6 +923,16 @@ void cbinfer_destroy(cbinfer_state *s)
         g_scratch_in_use[s->static_device] = false;
     }
     delete s;
+}
+
+// Waits until no frame is in flight any more (and nothing else on the caller's stream).
+static int drain(cbinfer_state *s)
+{
+    for (int i = 0; i < 2; ++i)
+        if (s->pstream[i]) HIP_TRY(hipStreamSynchronize(s->pstream[i]));
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    s->have_prev = false;
+    return CBINFER_OK;
 }
 
 // Layers in selection mode keep their maps and skip index extraction in the frame itself; the
@@ -843,7 +956,8 @@ int cbinfer_set_mode(cbinfer_state *s, int force_dense)
 {
     if (!s) return fail(CBINFER_EINVAL, "state is NULL");
     if (!s->broken && s->have_frame) {
-        const int rc = refresh_lists(s); // under the mode the last frame ran in
+        int rc = drain(s);
+        if (rc == CBINFER_OK) rc = refresh_lists(s); // under the mode the last frame ran in
         if (rc) return rc;
     }
     s->force_dense = force_dense != 0;
@@ -875,14 +989,14 @@ int cbinfer_layer_counts(cbinfer_state *s, int layer, int64_t *n_changed, int64_
 {
     int rc = check_query(s, layer);
     if (rc) return rc;
-    if ((rc = refresh_lists(s)) != CBINFER_OK) return rc;
+    if ((rc = drain(s)) != CBINFER_OK || (rc = refresh_lists(s)) != CBINFER_OK) return rc;
     const Op &op = s->plan.ops[layer];
     int c[2] = {0, 0};
     if (s->force_dense) {
         c[0] = op.kind == CBINFER_OP_CONV ? s->plan.S * op.H * op.W : -1;
         c[1] = s->plan.S * op.Ho * op.Wo;
     } else {
-        HIP_TRY(hipStreamSynchronize(s->stream));
+        HIP_TRY(hipStreamSynchronize(s->work));
         HIP_TRY(hipMemcpy(c, s->at<int>(op.o_counts), 8, hipMemcpyDeviceToHost));
         if (op.kind != CBINFER_OP_CONV) c[0] = -1;
     }
@@ -909,8 +1023,8 @@ int cbinfer_read_list(cbinfer_state *s, int layer, int which, int32_t *host, int
     if (which == CBINFER_LIST_CHANGED && op.kind != CBINFER_OP_CONV)
         return fail(CBINFER_EINVAL, "layer %d is a pooling layer and has no changed-input list", layer);
     if (cap < 0 || (cap > 0 && !host)) return fail(CBINFER_EINVAL, "bad host buffer");
-    if ((rc = refresh_lists(s)) != CBINFER_OK) return rc;
-    HIP_TRY(hipStreamSynchronize(s->stream));
+    if ((rc = drain(s)) != CBINFER_OK || (rc = refresh_lists(s)) != CBINFER_OK) return rc;
+    HIP_TRY(hipStreamSynchronize(s->work));
     int count = 0;
     const int *src = nullptr;
     if (s->force_dense) {
@@ -950,7 +1064,7 @@ int cbinfer_read_map(cbinfer_state *s, int layer, int which, float *host, size_t
     const size_t need = (size_t)s->plan.S * C * HW;
     if (count != need) return fail(CBINFER_EINVAL, "map has %zu values, buffer holds %zu", need, count);
     const size_t n_el = (size_t)s->plan.S * HW * Cs;
-    HIP_TRY(hipStreamSynchronize(s->stream));
+    if ((rc = drain(s)) != CBINFER_OK) return rc;
     if (s->plan.dtype == cbk::kBF16) {
         std::vector<unsigned short> tmp(n_el);
         HIP_TRY(hipMemcpy(tmp.data(), src, n_el * 2, hipMemcpyDeviceToHost));
@@ -973,7 +1087,7 @@ int cbinfer_set_profiling(cbinfer_state *s, int enable)
 {
     if (!s) return fail(CBINFER_EINVAL, "state is NULL");
     if (s->broken) return fail(CBINFER_EDEVICE, "a previous HIP call failed; destroy this state");
-    HIP_TRY(hipStreamSynchronize(s->stream));
+    if (drain(s) != CBINFER_OK) return CBINFER_EDEVICE;
     s->profiling = enable != 0;
     s->events_used = 0;
     std::fill(s->prof_ms.begin(), s->prof_ms.end(), 0.0);

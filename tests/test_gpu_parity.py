@@ -302,7 +302,7 @@ def _integer_video(H, W, C, n_frames, seed):
     frames = []
     for t in range(n_frames):
         f = bg.copy()
-        y, x = 3 + t, 2 + 2 * t
+        y, x = 3 + t % (H - 8), 2 + (2 * t) % (W - 8)     # wraps around on long videos
         f[:, y:y + 5, x:x + 6] = tex
         for _ in range(6):
             c, yy, xx = r.integers(0, C), r.integers(0, H), r.integers(0, W)
@@ -497,11 +497,10 @@ def test_integer_network_three_streams_every_layer_bit_exact(lists):
     net.destroy()
 
 
-@pytest.mark.parametrize("seed", range(24))
-def test_random_integer_networks_bit_exact(seed):
-    """Random stacks of 2-5 convolution layers (1x1 to 7x7, pooling in between, one to three
-    streams, either reference mode, either list path, some layers propagating): integer weights,
-    so every layer's lists and maps must match the oracle bit for bit on every frame."""
+def _random_integer_case(seed, n_frames=5):
+    """A random stack of 2-5 convolution layers (1x1 to 7x7, pooling in between, one to three
+    streams, either reference mode, either list path, some layers propagating) with integer
+    weights and integer videos."""
     r = np.random.default_rng(4242 + seed)
     H, W = int(r.integers(12, 40)) * 2, int(r.integers(12, 50)) * 2
     C, S = int(r.integers(1, 6)), int(r.choice([1, 1, 2, 3]))
@@ -518,32 +517,104 @@ def test_random_integer_networks_bit_exact(seed):
     prop = [l for l, L in enumerate(layers) if L.kind == "conv" and l > 0 and r.integers(0, 5) == 0 and not hold]
     params = _integer_params(layers, int(r.integers(0, 1000)))
     taus = [float(r.choice([0.5, 1.5, 2.5])) if L.kind == "conv" else None for L in layers]
-    vids = [_integer_video(H, W, C, 5, 300 + seed * 7 + s) for s in range(S)]
-    net = cb.CBInfer(layers, params, (C, H, W), taus, n_streams=S, hold_reference=hold, lists_every_frame=lists,
-                     propagate_layers=prop)
-    orcs = [oracle.OracleCBNet(layers, params, [0.0 if t is None else t for t in taus], ref_mode=1 if hold else 0,
-                               propagate_layers=prop) for _ in range(S)]
+    vids = [_integer_video(H, W, C, n_frames, 300 + seed * 7 + s) for s in range(S)]
+    return dict(layers=layers, params=params, taus=taus, vids=vids, H=H, W=W, C=C, S=S, hold=hold, lists=lists, prop=prop)
+
+
+def _compare_all_layers(net, orcs, layers, S, what):
+    for l, L in enumerate(layers):
+        size = orcs[0].out[l].shape[1] * orcs[0].out[l].shape[2]
+        if L.kind == "conv":
+            n_in = orcs[0].trace[l]["x"][0].size
+            cl = np.concatenate([orcs[s].trace[l]["C"] + s * n_in for s in range(S)])
+            ul = np.concatenate([orcs[s].trace[l]["U"] + s * size for s in range(S)])
+            np.testing.assert_array_equal(net.read_list(l, cb.LIST_CHANGED), cl, err_msg="%s layer %d" % (what, l))
+            np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), ul, err_msg="%s layer %d" % (what, l))
+        else:
+            pl = np.concatenate([orcs[s].trace[l]["P"] + s * size for s in range(S)])
+            np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), pl, err_msg="%s layer %d" % (what, l))
+        m = net.read_map(l, cb.MAP_OUTPUT)
+        for s in range(S):
+            np.testing.assert_array_equal(m[s], orcs[s].out[l], err_msg="%s layer %d" % (what, l))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_integer_networks_bit_exact(seed):
+    """Random networks with integer weights: every layer's lists and maps must match the oracle
+    bit for bit on every frame."""
+    k = _random_integer_case(seed)
+    layers, S = k["layers"], k["S"]
+    net = cb.CBInfer(layers, k["params"], (k["C"], k["H"], k["W"]), k["taus"], n_streams=S, hold_reference=k["hold"],
+                     lists_every_frame=k["lists"], propagate_layers=k["prop"])
+    orcs = [oracle.OracleCBNet(layers, k["params"], [0.0 if t is None else t for t in k["taus"]],
+                               ref_mode=1 if k["hold"] else 0, propagate_layers=k["prop"]) for _ in range(S)]
     for t in range(5):
-        fr = np.stack([vids[s][t] for s in range(S)])
+        fr = np.stack([k["vids"][s][t] for s in range(S)])
         want = np.stack([orcs[s].process_frame(fr[s]) for s in range(S)])
         got = net.process_frame(to_dev(fr)).cpu().numpy()
-        for l, L in enumerate(layers):
-            what = "seed %d layer %d frame %d" % (seed, l, t)
-            size = orcs[0].out[l].shape[1] * orcs[0].out[l].shape[2]
-            if L.kind == "conv":
-                n_in = orcs[0].trace[l]["x"][0].size
-                cl = np.concatenate([orcs[s].trace[l]["C"] + s * n_in for s in range(S)])
-                ul = np.concatenate([orcs[s].trace[l]["U"] + s * size for s in range(S)])
-                np.testing.assert_array_equal(net.read_list(l, cb.LIST_CHANGED), cl, err_msg=what)
-                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), ul, err_msg=what)
-            else:
-                pl = np.concatenate([orcs[s].trace[l]["P"] + s * size for s in range(S)])
-                np.testing.assert_array_equal(net.read_list(l, cb.LIST_UPDATE), pl, err_msg=what)
-            m = net.read_map(l, cb.MAP_OUTPUT)
-            for s in range(S):
-                np.testing.assert_array_equal(m[s], orcs[s].out[l], err_msg=what)
+        _compare_all_layers(net, orcs, layers, S, "seed %d frame %d" % (seed, t))
         np.testing.assert_array_equal(got, want)
     net.destroy()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_frames_in_flight_bit_exact(seed):
+    """Throughput mode (consecutive frames overlap on two streams of the library): 16 frames are
+    enqueued back to back without waiting for any of them, each with an output buffer of its own;
+    every frame's output, and the lists and maps left by the last one, must equal the oracle's bit
+    for bit -- each frame has to see exactly the state the frame before it left."""
+    import torch
+    T = 16
+    k = _random_integer_case(seed, n_frames=T)
+    layers, S = k["layers"], k["S"]
+    net = cb.CBInfer(layers, k["params"], (k["C"], k["H"], k["W"]), k["taus"], n_streams=S, hold_reference=k["hold"],
+                     lists_every_frame=k["lists"], propagate_layers=k["prop"], pipeline_frames=True)
+    orcs = [oracle.OracleCBNet(layers, k["params"], [0.0 if t is None else t for t in k["taus"]],
+                               ref_mode=1 if k["hold"] else 0, propagate_layers=k["prop"]) for _ in range(S)]
+    frames = [to_dev(np.stack([k["vids"][s][t] for s in range(S)])) for t in range(T)]
+    outs = [torch.empty(net.out_shape, dtype=torch.float32, device="cuda") for _ in range(T)]
+    torch.cuda.synchronize()
+    for t in range(T):
+        net.process_frame(frames[t], outs[t])
+    net.flush()
+    torch.cuda.synchronize()
+    for t in range(T):
+        want = np.stack([orcs[s].process_frame(k["vids"][s][t]) for s in range(S)])
+        np.testing.assert_array_equal(outs[t].cpu().numpy(), want, err_msg="seed %d frame %d" % (seed, t))
+    _compare_all_layers(net, orcs, layers, S, "seed %d after the last frame" % seed)
+    # and onwards after a query (which waits for everything in flight), a reset and a mode switch
+    net.reset()
+    for s in range(S):
+        orcs[s].reset()
+    for t in (3, 4, 5):
+        fr = np.stack([k["vids"][s][t] for s in range(S)])
+        want = np.stack([orcs[s].process_frame(fr[s]) for s in range(S)])
+        got = net.process_frame(to_dev(fr))
+        net.flush()
+        np.testing.assert_array_equal(got.cpu().numpy(), want, err_msg="seed %d frame %d after reset" % (seed, t))
+    net.destroy()
+
+
+def test_frames_in_flight_scene_network_matches_ordinary_mode():
+    """The scene-labeling network on noisy video, 24 frames in flight against the same frames one
+    at a time: same kernels, same state per frame, so every output must be identical."""
+    import torch
+    layers = scene_labeling_net()
+    params = make_weights(layers, 77)
+    v = _video(96, 128, sigma=0.005, n_objects=3, seed=70)
+    frames = [to_dev(v.frame(t)) for t in range(24)]
+    a = cb.CBInfer(layers, params, (3, 96, 128), 0.02)
+    ref = [a.process_frame(f).cpu().numpy().copy() for f in frames]
+    a.destroy()
+    b = cb.CBInfer(layers, params, (3, 96, 128), 0.02, pipeline_frames=True)
+    outs = [torch.empty(b.out_shape, dtype=torch.float32, device="cuda") for _ in frames]
+    for f, o in zip(frames, outs):
+        b.process_frame(f, o)
+    b.flush()
+    torch.cuda.synchronize()
+    for t, (o, r) in enumerate(zip(outs, ref)):
+        np.testing.assert_array_equal(o.cpu().numpy(), r, err_msg="frame %d" % t)
+    b.destroy()
 
 
 def test_large_multi_stream_frames_without_padding_channels():
