@@ -9,6 +9,8 @@ starts.  Prints ONE JSON line.
 The default run measures
   * `value`: the 320x240 scene-labeling workload as written (sigma 0.005, tau 0.02), median over
     --blocks timed blocks of --steps frames each, next to the dense HIP baseline of the same library;
+    both in the library's throughput mode (two frames in flight), with the figures for one frame
+    at a time beside them;
   * `sweep`: the same network and frame size, noise-free, with the motion chosen for about 1, 5
     and 20 % changed input pixels: change-based and dense frames/s, speed-up, measured rates;
   * `hbm`: the memory-bound kernels (detection, dilation, index extraction, pooling) on one
@@ -168,7 +170,7 @@ def kernel_entries(cfg, net, prof, sums, P, in_shape):
     return kernels, rates
 
 
-def measure(cfg, args, *, steps, warmup, blocks, profile=True):
+def measure(cfg, args, *, steps, warmup, blocks, profile=True, one_at_a_time=False):
     """Change-based and dense frames/s of one workload (medians over timed blocks) and, with
     `profile`, per-kernel times from events attached to every launch plus measured change rates."""
     import torch
@@ -185,23 +187,40 @@ def measure(cfg, args, *, steps, warmup, blocks, profile=True):
     in_shape = (cfg.channels, cfg.height, cfg.width)
     bf16 = cfg.dtype == "bf16"
     conv_ids = [l for l, L in enumerate(cfg.layers) if L.kind == "conv"]
-    net = cb.CBInfer(cfg.layers, params, in_shape, cfg.tau, n_streams=cfg.n_streams,
-                     dtype=cb.BF16 if bf16 else cb.F32, hold_reference=args.hold,
-                     propagate_layers=conv_ids[1:] if args.propagate else (), pipeline_frames=args.pipeline)
-    out = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
+    def make_net(pipeline):
+        return cb.CBInfer(cfg.layers, params, in_shape, cfg.tau, n_streams=cfg.n_streams,
+                          dtype=cb.BF16 if bf16 else cb.F32, hold_reference=args.hold,
+                          propagate_layers=conv_ids[1:] if args.propagate else (), pipeline_frames=pipeline)
 
-    sec_cb = timed_blocks(net, frames_dev, out, cfg.n_frames, warmup, steps, blocks)
-    # dense HIP baseline: same kernels, identity lists, no change detection
-    net.set_mode(True)
-    sec_dense = timed_blocks(net, frames_dev, out, cfg.n_frames, warmup, steps, blocks)
-    net.set_mode(False)
+    def both_modes(net):
+        sec_cb = timed_blocks(net, frames_dev, out, cfg.n_frames, warmup, steps, blocks)
+        # dense HIP baseline: same kernels, identity lists, no change detection
+        net.set_mode(True)
+        sec_dense = timed_blocks(net, frames_dev, out, cfg.n_frames, warmup, steps, blocks)
+        net.set_mode(False)
+        return sec_cb, sec_dense
+
+    pipelined = not args.no_pipeline
+    net = make_net(pipelined)
+    out = torch.empty(net.out_shape, dtype=torch.float32, device="cuda")
+    sec_cb, sec_dense = both_modes(net)
     med_cb, med_dense = float(np.median(sec_cb)), float(np.median(sec_dense))
     fps = [cfg.n_streams * steps / s for s in sec_cb]
     res = {
         "fps": cfg.n_streams * steps / med_cb, "ms_per_step": 1e3 * med_cb / steps,
         "fps_blocks": fps, "fps_spread": (max(fps) - min(fps)) / (cfg.n_streams * steps / med_cb),
         "dense_fps": cfg.n_streams * steps / med_dense, "speedup": med_dense / med_cb,
+        "frames_in_flight": 2 if pipelined else 1,
     }
+    if pipelined and one_at_a_time:
+        # the same without overlapping consecutive frames: every frame's kernels behind the previous frame's
+        net1 = make_net(False)
+        s1, d1 = both_modes(net1)
+        net1.destroy()
+        m1, md1 = float(np.median(s1)), float(np.median(d1))
+        res["one_frame_at_a_time"] = {"frames_per_s": cfg.n_streams * steps / m1, "ms_per_step": 1e3 * m1 / steps,
+                                      "dense_hip_frames_per_s": cfg.n_streams * steps / md1,
+                                      "speedup_vs_dense_hip": md1 / m1}
     if profile:
         n_ops = len(cfg.layers)
         net.reset()
@@ -257,12 +276,13 @@ def roofline_of(cfg, kernels):
 def sweep_rows(configs, args, steps, warmup, blocks):
     rows = []
     for nominal, cfg in configs:
-        m = measure(cfg, args, steps=steps, warmup=warmup, blocks=blocks)
+        m = measure(cfg, args, steps=steps, warmup=warmup, blocks=blocks, one_at_a_time=True)
         cr = m["change_rates"]
         g = max((k for k in m["kernels"] if k.endswith(".gemm")), key=lambda k: m["kernels"][k]["us"])
         rows.append({"nominal_changed": nominal, "workload": cfg.name, "n_objects": cfg.video_kwargs.get("n_objects"),
                      "sigma": cfg.sigma, "frames_per_s": m["fps"], "dense_hip_frames_per_s": m["dense_fps"],
                      "speedup_vs_dense_hip": m["speedup"], "fps_spread": m["fps_spread"],
+                     "one_frame_at_a_time": m.get("one_frame_at_a_time"),
                      "changed_input_pixels": cr["L0"]["changed_in"], "change_rates": cr,
                      "largest_gemm": {"kernel": g, "us": m["kernels"][g]["us"], "TFLOPs": m["kernels"][g]["TFLOPs"]}})
         print("sweep %s: %.0f vs %.0f frames/s" % (cfg.name, m["fps"], m["dense_fps"]), file=sys.stderr, flush=True)
@@ -315,8 +335,9 @@ def parse_args(argv=None):
                     help="refresh the stored previous input only where a change was flagged")
     ap.add_argument("--propagate", action="store_true",
                     help="no change detection behind the first layer (worst-case propagation)")
-    ap.add_argument("--pipeline", action="store_true",
-                    help="throughput mode: consecutive frames overlap on two streams of the library")
+    ap.add_argument("--no-pipeline", action="store_true",
+                    help="one frame at a time (default: throughput mode, consecutive frames overlap on two "
+                         "streams of the library)")
     ap.add_argument("--frames", type=int, default=0, help="frames generated (default: the workload's)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the cpu_baseline leg (0: skip)")
     ap.add_argument("--no-profile", action="store_true", help="skip the per-kernel timing pass")
@@ -367,7 +388,7 @@ def run(args) -> dict:
 
     cfg = build_workload(args)
     in_shape = (cfg.channels, cfg.height, cfg.width)
-    m = measure(cfg, args, steps=K, warmup=W, blocks=B, profile=not args.no_profile)
+    m = measure(cfg, args, steps=K, warmup=W, blocks=B, profile=not args.no_profile, one_at_a_time=True)
     result = {
         "metric": METRIC,
         "value": m["fps"], "unit": "frames/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -378,9 +399,11 @@ def run(args) -> dict:
                    "reference_update": "where flagged" if args.hold else "previous frame",
                    "detection": "first layer only, changes propagated" if args.propagate else "every layer"},
         "timing": {"blocks": B, "frames_per_block": K, "value_is": "median block",
-                   "frames_per_s_blocks": m["fps_blocks"], "spread": m["fps_spread"]},
+                   "frames_per_s_blocks": m["fps_blocks"], "spread": m["fps_spread"],
+                   "frames_in_flight": m["frames_in_flight"]},
         "dense_hip_frames_per_s": m["dense_fps"],
         "speedup_vs_dense_hip": m["speedup"],
+        "one_frame_at_a_time": m.get("one_frame_at_a_time"),
         "paper_context": "8.6x (Tegra X1) / 7.6x (GTX 1080) over cuDNN, 327.6 GOp/s/W; other hardware, other data",
     }
     if not args.no_profile:

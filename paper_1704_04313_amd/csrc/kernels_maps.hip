@@ -431,7 +431,7 @@ __global__ __launch_bounds__(kBlock) void dilate_kernel(const uint64_t *__restri
 // dilation with that window at stride 2.  The workgroup also leaves the number of set bits of
 // its words, which is what the index extraction needs to place its output.
 // ------------------------------------------------------------------------------------------
-static constexpr int kCompactWords = 512; // words per workgroup of the index extraction: two per thread
+static constexpr int kCompactTwoWordsFrom = 65536; // maps of more words than this: two words per thread in the index extraction
 static constexpr int kCompactStage = 4096; // list entries a workgroup stages in LDS (16 KiB); more go straight to the list
 static constexpr int kCompactDense = 12;   // words with more set bits than this are expanded by a whole wave
 static constexpr int kCountWords = 32;    // words per entry of the group-count arrays
@@ -709,8 +709,8 @@ hipError_t dilate(hipStream_t st, const uint64_t *chg_bits, uint64_t *upd_bits, 
 }
 
 // ------------------------------------------------------------------------------------------
-// Change-index extraction.  A workgroup owns kCompactWords bitmap words, two consecutive ones per
-// thread.  Where its output starts it finds out itself, without waiting for anybody: by adding the
+// Change-index extraction.  A workgroup owns 256 or 512 bitmap words, one or two consecutive ones
+// per thread.  Where its output starts it finds out itself, without waiting for anybody: by adding the
 // set-bit counts of all groups of words before its own (left by the dilation kernel or by
 // compact_count_kernel; 16-byte loads, at most 32 KiB from L2), or for small maps by counting the
 // preceding words.  Ordered and deterministic.  The threads scan the popcounts of their words and
@@ -762,39 +762,46 @@ __global__ __launch_bounds__(kBlock) void compact_count_kernel(CompactJobs jobs)
 
 typedef int intx4_a4 __attribute__((ext_vector_type(4), aligned(4))); // four list entries starting at any of them
 
-template <bool TWO_LEVEL>
+// WPT words per thread: two for maps of millions of positions (fewer workgroups, fewer counts to
+// add up per workgroup), one below that (more workgroups to spread a small map's set words over).
+template <bool TWO_LEVEL, int WPT>
 __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
 {
+    constexpr int kWords = WPT * kBlock; // words per workgroup
+    static_assert(WPT == 1 || WPT == 2, "one or two words per thread");
+    static_assert(kWords % (4 * kCountWords) == 0, "whole 16-byte loads of group counts");
     __shared__ __align__(16) int stage[kCompactStage + 4];
-    __shared__ uint64_t sword[kCompactWords];
-    __shared__ int soff[kCompactWords];
-    __shared__ int2 sfull[kBlock / 64][2 * 64]; // per wave: offset and first position of its completely set words
+    __shared__ uint64_t sword[kWords];
+    __shared__ int soff[kWords];
+    __shared__ int2 sfull[kBlock / 64][WPT * 64]; // per wave: offset and first position of its completely set words
     __shared__ int swave[kBlock / 64];
     __shared__ int swave2[kBlock / 64];
     const CompactJob job = jobs.j[blockIdx.y];
-    const int w0 = blockIdx.x * kCompactWords;
+    const int w0 = blockIdx.x * kWords;
     if (w0 >= job.nwords) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    // this workgroup's words: for the scan thread t holds words 2t and 2t + 1 of them
+    // this workgroup's words: for the scan thread t holds the WPT consecutive words WPT t ... of them
     {
-        const int i0 = w0 + 2 * tid;
+        const int i0 = w0 + WPT * tid;
         uint64_t m0 = 0, m1 = 0;
-        if (!job.bytes && i0 + 1 < job.nwords) {
+        if (WPT == 2 && !job.bytes && i0 + 1 < job.nwords) {
             const ulonglong2 v = *reinterpret_cast<const ulonglong2 *>(job.bits + i0);
             m0 = v.x;
             m1 = v.y;
         } else {
             if (i0 < job.nwords) m0 = map_word(job, i0);
-            if (i0 + 1 < job.nwords) m1 = map_word(job, i0 + 1);
+            if (WPT == 2 && i0 + 1 < job.nwords) m1 = map_word(job, i0 + 1);
         }
         const int c0 = __popcll(m0), sum = c0 + __popcll(m1);
         const int incl = wave_incl_scan(sum, lane);
         if (lane == 63) swave2[wave] = incl;
-        sword[2 * tid] = m0;
-        sword[2 * tid + 1] = m1;
-        soff[2 * tid] = incl - sum;          // still without the waves before this one
-        soff[2 * tid + 1] = incl - sum + c0;
+        sword[WPT * tid] = m0;
+        soff[WPT * tid] = incl - sum;        // still without the waves before this one
+        if (WPT == 2) {
+            sword[2 * tid + 1] = m1;
+            soff[2 * tid + 1] = incl - sum + c0;
+        }
     }
     __syncthreads();
     int total = 0, wave_off[kBlock / 64];
@@ -803,14 +810,14 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
         wave_off[i] = total;
         total += swave2[i];
     }
-    const bool last = w0 + kCompactWords >= job.nwords;
+    const bool last = w0 + kWords >= job.nwords;
     if (total == 0 && !last) return; // nothing to write: most workgroups of a quiet scene end here
 
     // set bits in all words before this workgroup's
     int before = 0;
     if (TWO_LEVEL) {
         const int4 *g4 = reinterpret_cast<const int4 *>(job.group_counts);
-        const int n4 = (int)blockIdx.x * (kCompactWords / kCountWords / 4);
+        const int n4 = (int)blockIdx.x * (kWords / kCountWords / 4);
         for (int i = tid; i < n4; i += kBlock) {
             const int4 v = g4[i];
             before += v.x + v.y + v.z + v.w;
@@ -825,17 +832,17 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
     int prefix = 0;
 #pragma unroll
     for (int i = 0; i < kBlock / 64; ++i) prefix += swave[i];
-    // For the expansion the words are dealt out again: lane l of wave v takes words 4 l + v and
-    // 256 + 4 l + v, so that of any run of consecutive words -- a solid block of set words, say --
+    // For the expansion the words are dealt out again: lane l of wave v takes word 4 l + v (and
+    // 256 + 4 l + v), so that of any run of consecutive words -- a solid block of set words, say --
     // each wave holds a quarter.
-    uint64_t m[2];
-    int c[2], o[2], pos[2];
+    uint64_t m[WPT];
+    int c[WPT], o[WPT], pos[WPT];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < WPT; ++h) {
         const int wi = 256 * h + 4 * lane + wave;
         m[h] = sword[wi];
         c[h] = __popcll(m[h]);
-        o[h] = soff[wi] + wave_off[h * 2 + (lane >> 5)]; // word wi was scanned by thread wi / 2, of wave wi / 128
+        o[h] = soff[wi] + wave_off[wi / (64 * WPT)]; // word wi was scanned by thread wi / WPT
         pos[h] = (w0 + wi) * 64;
     }
     int *dst = job.list + prefix;
@@ -847,7 +854,7 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
         const uint64_t below = (1ull << lane) - 1ull;
         int nfull = 0;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < WPT; ++h) {
             const bool full = c[h] == 64;
             const uint64_t fb = __ballot(full);
             if (full) sfull[wave][nfull + __popcll(fb & below)] = make_int2(o[h], pos[h]);
@@ -872,7 +879,7 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
         // few: through the staging buffer, shifted so that dst[e] and stage[e + shift] are aligned alike
         const int shift = (int)((reinterpret_cast<uintptr_t>(dst) >> 2) & 3);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < WPT; ++h) {
             if (c[h] > 0 && c[h] <= kCompactDense) { // a word with few set bits: its holder walks them
                 int e = o[h] + shift;
                 uint64_t r = m[h];
@@ -922,20 +929,22 @@ hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, bool group
     }
     for (int i = 0; i < njobs; ++i) // 16-byte loads of word pairs
         if (!jobs[i].bits || reinterpret_cast<uintptr_t>(jobs[i].bits) % 16 || !jobs[i].list || !jobs[i].count) return hipErrorInvalidValue;
-    const int gx = (maxw + kCompactWords - 1) / kCompactWords;
+    const bool two = maxw > kCompactTwoWordsFrom; // words per thread
+    const int gx = (maxw + (two ? 2 : 1) * kBlock - 1) / ((two ? 2 : 1) * kBlock);
     if (groups_ready || compact_two_level(maxw)) {
         for (int i = 0; i < njobs; ++i)
-            if (!jobs[i].group_counts) return hipErrorInvalidValue;
-        for (int i = 0; i < njobs; ++i)
-            if (reinterpret_cast<uintptr_t>(jobs[i].group_counts) % 16) return hipErrorInvalidValue;
-        if (groups_ready) {
-            launch_kernel(tm, compact_kernel<true>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
-        } else {
+            if (!jobs[i].group_counts || reinterpret_cast<uintptr_t>(jobs[i].group_counts) % 16) return hipErrorInvalidValue;
+        Timing t2 = tm;
+        if (!groups_ready) {
             launch_kernel(Timing{tm.start, nullptr}, compact_count_kernel, dim3((maxw + kBlock - 1) / kBlock, njobs), dim3(kBlock), 0, st, js);
-            launch_kernel(Timing{nullptr, tm.stop}, compact_kernel<true>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+            t2 = Timing{nullptr, tm.stop};
         }
+        if (two)
+            launch_kernel(t2, compact_kernel<true, 2>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+        else
+            launch_kernel(t2, compact_kernel<true, 1>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
     } else {
-        launch_kernel(tm, compact_kernel<false>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
+        launch_kernel(tm, compact_kernel<false, 1>, dim3(gx, njobs), dim3(kBlock), 0, st, js);
     }
     return hipGetLastError();
 }
