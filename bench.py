@@ -49,16 +49,18 @@ def frame_order(n_frames: int, count: int, start: int = 0):
         yield u if u < n_frames else period - u
 
 
-def hbm_config(frames: int, busy: bool = True):
-    """One 1x1 layer and a 2x2 pooling on a 3x4096x4096 frame: a frame's traffic (0.6 GB for the
-    detection alone) exceeds the 256 MB last-level cache, so kernel rates are HBM rates.
+def hbm_config(frames: int, busy: bool = True, streams: int = 4):
+    """One 1x1 layer and a 2x2 pooling on 3x4096x4096 frames (four cameras at once): a step's
+    traffic (2.4 GB for the detection alone) exceeds the 256 MB last-level cache many times and
+    dwarfs the few microseconds a launch costs, so kernel rates are HBM rates.
     busy: 48 textured rectangles of 100-400 pixels moving 4-16 pixels per frame, a fifth of the
     pixels changed per frame (measured 19.6 % over frames 1-2; a busy scene in the sense of
     Section 4.4), noise-free: index lists of millions of entries.  Not busy: two small objects,
     everything but the detection pass is negligible."""
     from workloads import Config, conv, pool
     if busy:
-        return Config("hbm-4096x4096x3-busy", 0, [conv(3, 8, 1), pool()], 4096, 4096, 3, frames or 3, 0.02, 0.0,
+        return Config("hbm-%dx4096x4096x3-busy" % streams, 0, [conv(3, 8, 1), pool()], 4096, 4096, 3, frames or 3,
+                      0.02, 0.0, n_streams=streams,
                       video_kwargs={"n_objects": 48, "size_range": (100, 400), "speed_range": (4, 16)})
     return Config("hbm-detect-4096x4096x3", 0, [conv(3, 4, 1, relu=False)], 4096, 4096, 3,
                   frames or 3, 0.02, 0.0, video_kwargs={"n_objects": 2})

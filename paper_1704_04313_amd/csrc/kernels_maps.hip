@@ -781,6 +781,23 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
     if (w0 >= job.nwords) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
+    // set bits in all words before this workgroup's (the loads go out together with those of the
+    // workgroup's own words below: one round trip, not two)
+    int before = 0;
+    if (TWO_LEVEL) {
+        const int4 *g4 = reinterpret_cast<const int4 *>(job.group_counts);
+        const int n4 = (int)blockIdx.x * (kWords / kCountWords / 4);
+        for (int i = tid; i < n4; i += kBlock) {
+            const int4 v = g4[i];
+            before += v.x + v.y + v.z + v.w;
+        }
+    } else {
+        for (int i = tid; i < w0; i += kBlock) before += __popcll(map_word(job, i));
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) before += __shfl_xor(before, d, 64);
+    if (lane == 0) swave[wave] = before;
+
     // this workgroup's words: for the scan thread t holds the WPT consecutive words WPT t ... of them
     {
         const int i0 = w0 + WPT * tid;
@@ -812,23 +829,6 @@ __global__ __launch_bounds__(kBlock) void compact_kernel(CompactJobs jobs)
     }
     const bool last = w0 + kWords >= job.nwords;
     if (total == 0 && !last) return; // nothing to write: most workgroups of a quiet scene end here
-
-    // set bits in all words before this workgroup's
-    int before = 0;
-    if (TWO_LEVEL) {
-        const int4 *g4 = reinterpret_cast<const int4 *>(job.group_counts);
-        const int n4 = (int)blockIdx.x * (kWords / kCountWords / 4);
-        for (int i = tid; i < n4; i += kBlock) {
-            const int4 v = g4[i];
-            before += v.x + v.y + v.z + v.w;
-        }
-    } else {
-        for (int i = tid; i < w0; i += kBlock) before += __popcll(map_word(job, i));
-    }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) before += __shfl_xor(before, d, 64);
-    if (lane == 0) swave[wave] = before;
-    __syncthreads();
     int prefix = 0;
 #pragma unroll
     for (int i = 0; i < kBlock / 64; ++i) prefix += swave[i];
@@ -1205,16 +1205,63 @@ __global__ __launch_bounds__(kBlock) void map_to_planar_kernel(const uint4 *__re
     }
 }
 
+// The same for maps of at most kPlanarUnits units per pixel: a thread takes a whole pixel, so that
+// a wave reads one contiguous run of the map (with a thread per unit each load instruction would
+// touch every V-th unit only and leave the rest of every line to a later instruction).
+static constexpr int kPlanarUnits = 4;
+
+template <int DT, int V>
+__global__ __launch_bounds__(kBlock) void map_to_planar_pixel_kernel(const uint4 *__restrict__ map,
+                                                                     float *__restrict__ planar, int M, int No,
+                                                                     int total_px, FastDiv dNo)
+{
+    constexpr int E = Unit<DT>::N;
+    for (int g = (int)blockIdx.x * kBlock + (int)threadIdx.x; g < total_px; g += (int)gridDim.x * kBlock) {
+        const int st = fast_div(g, dNo), q = g - st * No;
+        uint4 a[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) a[v] = map[(size_t)g * V + v];
+        float *dst = planar + (size_t)st * M * No + q;
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+#pragma unroll
+            for (int i = 0; i < E; ++i)
+                if (E * v + i < M) dst[(size_t)(E * v + i) * No] = Unit<DT>::get(a[v], i);
+    }
+}
+
 hipError_t map_to_planar(hipStream_t st, const void *map, float *planar, int M, int V, int No, int S, int dtype,
                          const Timing &tm)
 {
     const long long total = (long long)S * V * No; // units of the map
     if (total >= (1ll << 30) || V < 1 || No < 1) return hipErrorInvalidValue; // 32-bit indices, with room for the grid stride
+    const uint4 *m4 = static_cast<const uint4 *>(map);
+    const FastDiv dNo = make_fastdiv(No), dV = make_fastdiv(V);
+    if (V <= kPlanarUnits) {
+        const int px = S * No;
+        int grid = (px + kBlock - 1) / kBlock;
+        if (grid > 16384) grid = 16384;
+#define CBK_LAUNCH(DT_, V_)                                                                                            \
+    launch_kernel(tm, map_to_planar_pixel_kernel<DT_, V_>, dim3(grid), dim3(kBlock), 0, st, m4, planar, M, No, px, dNo)
+#define CBK_BY_V(DT_)                                                                                                  \
+    switch (V) {                                                                                                       \
+    case 1: CBK_LAUNCH(DT_, 1); break;                                                                                 \
+    case 2: CBK_LAUNCH(DT_, 2); break;                                                                                 \
+    case 3: CBK_LAUNCH(DT_, 3); break;                                                                                 \
+    default: CBK_LAUNCH(DT_, 4); break;                                                                                \
+    }
+        if (dtype == kBF16) {
+            CBK_BY_V(kBF16)
+        } else {
+            CBK_BY_V(kF32)
+        }
+#undef CBK_BY_V
+#undef CBK_LAUNCH
+        return hipGetLastError();
+    }
     long long grid = (total + kBlock - 1) / kBlock;
     if (grid > 8192) grid = 8192;
     if (grid < 1) grid = 1;
-    const uint4 *m4 = static_cast<const uint4 *>(map);
-    const FastDiv dNo = make_fastdiv(No), dV = make_fastdiv(V);
     if (dtype == kBF16)
         launch_kernel(tm, map_to_planar_kernel<kBF16>, dim3((int)grid), dim3(kBlock), 0, st, m4, planar, M, V, No,
                       (int)total, dNo, dV);
