@@ -117,7 +117,7 @@ def timed_blocks(net, frames_dev, out, n_frames, warmup, steps, blocks):
             for b in range(blocks)]
 
 
-def kernel_entries(cfg, net, prof, sums, P, in_shape):
+def kernel_entries(cfg, net, prof, sums, P, in_shape, propagate=False):
     """Per-kernel records (mean microseconds, algorithmic bytes or flops per launch, rates) and
     the measured change rates per layer."""
     import paper_1704_04313_amd as cb
@@ -138,6 +138,8 @@ def kernel_entries(cfg, net, prof, sums, P, in_shape):
         else:
             rates["L%d" % l] = {"updated_pooled": n_u / (S * h_out * w_out)}
         pooled_next = l + 1 < n_ops and cfg.layers[l + 1].kind == "pool"
+        # a layer feeding a convolution also reads the values it replaces, to flag that layer's changed inputs
+        compares = l + 1 < n_ops and cfg.layers[l + 1].kind == "conv" and not propagate
         n_p = sums[l + 1][1] / P if pooled_next else 0.0
         for (ll, name), (ms, n) in prof.items():
             if ll != l:
@@ -150,6 +152,12 @@ def kernel_entries(cfg, net, prof, sums, P, in_shape):
             elif name == "gemm":
                 fl = 2.0 * L.cout * L.cin * L.kh * L.kw * n_u
                 e.update(flops=fl, TFLOPs=fl / (ms * 1e-3) / 1e12, frac_mfma=fl / (ms * 1e-3) / 1e12 / mfma_peak)
+                # the least it has to move: the filters, the input values under the updated outputs'
+                # receptive fields (each once, never more than the whole map), a list entry and the
+                # output values per updated position; what counts for layers of few channels
+                by = esz * L.cout * L.cin * L.kh * L.kw + \
+                    esz * c_in * min(n_u * L.kh * L.kw, float(S * h_in * w_in)) + \
+                    (4.0 + (2.0 if compares else 1.0) * esz * c_out) * n_u
             elif name == "dilate":
                 # change map read (one bit per pixel; one byte behind the first layer), update and pooled bitmaps written
                 chg = S * h_in * w_in * (1.0 if l > 0 else 0.125)
@@ -161,8 +169,9 @@ def kernel_entries(cfg, net, prof, sums, P, in_shape):
                     maps += S * h_out * w_out / 32.0
                 by = maps + 4.0 * (n_c + n_u + n_p)
             elif name == "pool":
-                # list entry, k*k window values read, one value written, per pooled position and channel
-                by = 4.0 * n_u + (L.kh * L.kw + 1.0) * esz * c_out * n_u
+                # list entry, k*k window values (and the replaced value) read, one value written, per pooled
+                # position and channel
+                by = 4.0 * n_u + (L.kh * L.kw + (2.0 if compares else 1.0)) * esz * c_out * n_u
             elif name == "output":
                 by = S * (esz + 4.0) * c_out * h_out * w_out
             if by is not None:
@@ -242,7 +251,7 @@ def measure(cfg, args, *, steps, warmup, blocks, profile=True, one_at_a_time=Fal
                 if n:
                     prof[(l, name)] = (ms / n, n)
         net.set_profiling(False)
-        res["kernels"], res["change_rates"] = kernel_entries(cfg, net, prof, sums, P, in_shape)
+        res["kernels"], res["change_rates"] = kernel_entries(cfg, net, prof, sums, P, in_shape, propagate=args.propagate)
     net.destroy()
     del frames_dev, out
     torch.cuda.empty_cache()
@@ -254,7 +263,7 @@ def roofline_of(cfg, kernels):
     bf16 = cfg.dtype == "bf16"
     dom = max(kernels, key=lambda k: kernels[k]["us"])
     d = kernels[dom]
-    if "TFLOPs" in d:
+    if "TFLOPs" in d and d["frac_mfma"] >= d.get("frac_hbm", 0.0):
         roof = {"bound": "mfma", "achieved": d["TFLOPs"],
                 "peak": MI355X_BF16_MFMA_TFLOPS if bf16 else MI355X_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": d["frac_mfma"], "traffic": None}

@@ -64,7 +64,8 @@ enum {
      * no longer orders the state's stream behind the frame; cbinfer_flush does (all frames so far),
      * and so does every introspection call.  Work pending on the state's stream when a frame is
      * passed in still comes first; frame and output buffers must stay untouched until a flush has
-     * covered their frame.  Costs a second scratch set (cbinfer_workspace_bytes says how much). */
+     * covered their frame.  Costs a second scratch set (cbinfer_workspace_bytes says how much).
+     * Networks of fewer than three operations ignore the flag (nothing to overlap). */
     CBINFER_FLAG_PIPELINE_FRAMES = 4u
 };
 

@@ -107,7 +107,9 @@ int make_plan(const cbinfer_network *net, float threshold, bool need_threshold, 
     P.in_h = net->in_h;
     P.in_w = net->in_w;
     P.hold = (net->flags & CBINFER_FLAG_HOLD_REFERENCE) != 0;
-    P.pipeline = (net->flags & CBINFER_FLAG_PIPELINE_FRAMES) != 0;
+    // Frames in flight pay with event traffic between the two streams; a network of one or two
+    // operations has nothing to overlap that would be worth it and runs on the caller's stream.
+    P.pipeline = (net->flags & CBINFER_FLAG_PIPELINE_FRAMES) != 0 && net->n_layers >= 3;
     P.dtype = net->dtype == CBINFER_BF16 ? cbk::kBF16 : cbk::kF32;
     const int eu = cbk::elems_per_unit(P.dtype);
     const size_t esz = (size_t)cbk::elem_bytes(P.dtype);
@@ -276,7 +278,9 @@ struct cbinfer_state {
     bool have_prev = false;           // a frame is (possibly still) running on the other stream
     int pipe_gap = 3;                 // every pipe_gap-th operation waits for the previous frame (see enqueue_frame):
                                       // a wait on an event that has not completed costs the host several microseconds,
-                                      // and the frame rate of a small network is bound by exactly that
+                                      // and the frame rate of a small network is bound by exactly that.  Networks of
+                                      // few operations wait more often: a frame that waited for the end of the previous
+                                      // one before its first kernel would overlap nothing
     long long frame_index = 0;
     int static_device = -1;   // >= 0: the workspace is that device's static array (cbinfer_create_static)
     bool initialised = false; // a frame has been processed since create/reset
@@ -745,6 +749,7 @@ static cbinfer_state *create_state(const cbinfer_network *net, const Plan &P, ch
             HIP_TRY(hipEventCreateWithFlags(&s->ev_in, hipEventDisableTiming));
             for (int i = 0; i < 2; ++i) {
                 HIP_TRY(hipStreamCreateWithFlags(&s->pstream[i], hipStreamNonBlocking));
+                s->pipe_gap = P.ops.size() >= 6 ? 3 : (P.ops.size() >= 4 ? 2 : 1);
                 s->ev_op[i].assign(P.ops.size() + 1, nullptr);
                 for (hipEvent_t &e : s->ev_op[i]) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
             }
