@@ -66,6 +66,28 @@ def hbm_config(frames: int, busy: bool = True, streams: int = 4):
                   frames or 3, 0.02, 0.0, video_kwargs={"n_objects": 2})
 
 
+def plain_memory_rates(n_bytes: int = 1 << 30, reps: int = 5):
+    """What the runtime's own plain kernels reach on this machine, for scale: a device-to-device copy
+    (bytes read + bytes written per second) and a fill (bytes written per second) of n_bytes."""
+    import torch
+    src = torch.empty(n_bytes // 4, dtype=torch.float32, device="cuda").fill_(1.0)
+    dst = torch.empty_like(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    out = {}
+    for name, op, moved in (("copy", lambda: dst.copy_(src), 2 * n_bytes), ("fill", lambda: dst.zero_(), n_bytes)):
+        op()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            op()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_GBps"] = moved * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    torch.cuda.empty_cache()
+    return out
+
+
 def build_workload(args):
     from workloads import get_config
     w = args.workload
@@ -424,6 +446,8 @@ def run(args) -> dict:
         result["dense_gflop_per_frame"] = sum(dense_flops(cfg.layers, *in_shape)) / 1e9    # per stream
     else:
         result["roofline"] = None
+    if args.workload == "hbm":
+        result["plain_torch_kernels"] = plain_memory_rates()
 
     default_run = args.workload == "cfg2" and args.rate is None and not args.no_extras and not args.no_profile
     if default_run:
@@ -438,8 +462,11 @@ def run(args) -> dict:
                          "peak_GBps": MI355X_HBM_GBS, "change_rates": h["change_rates"],
                          "kernels": {k: {"us": v["us"], "bytes": v["bytes"], "GBps": v["GBps"], "frac_hbm": v["frac_hbm"]}
                                      for k, v in pick.items()},
+                         "plain_torch_kernels": plain_memory_rates(),
                          "note": "algorithmic bytes per launch / mean kernel time (events attached to the launch); "
-                                 "there is no stand-alone scatter kernel: the output update is the GEMM's epilogue"}
+                                 "there is no stand-alone scatter kernel: the output update is the GEMM's epilogue; "
+                                 "plain_torch_kernels: a 1 GiB device copy (read + written) and fill (written) of "
+                                 "torch on the same box, for scale"}
         print("hbm leg done", file=sys.stderr, flush=True)
 
     result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds) if args.cpu_seconds > 0 else None

@@ -432,7 +432,7 @@ __global__ __launch_bounds__(kBlock) void dilate_kernel(const uint64_t *__restri
 // its words, which is what the index extraction needs to place its output.
 // ------------------------------------------------------------------------------------------
 static constexpr int kCompactTwoWordsFrom = 65536; // maps of more words than this: two words per thread in the index extraction
-static constexpr int kCompactStage = 4096; // list entries a workgroup stages in LDS (16 KiB); more go straight to the list
+static constexpr int kCompactStage = 2048; // list entries a workgroup stages in LDS (8 KiB); more go straight to the list
 static constexpr int kCompactDense = 12;   // words with more set bits than this are expanded by a whole wave
 static constexpr int kCountWords = 32;    // words per entry of the group-count arrays
 static constexpr int kWordLanes = 8;
