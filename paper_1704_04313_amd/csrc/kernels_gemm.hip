@@ -485,20 +485,36 @@ typedef __attribute__((address_space(3))) void *LdsPtr;
 // loads of a wave complete in order, so "at most (STAGES - 3) slices' worth of instructions
 // outstanding" means slice kc + 2 is in LDS.  No LDS reads and no other vector memory
 // instructions occur in this loop, which keeps the instruction count per slice exact.
-template <int DT, int BM, int BN, int STAGES, int PA>
+// While two consumer waves keep the matrix pipeline of a SIMD busy, a vector-ALU instruction of the
+// producer wave on that SIMD gets issued about once per MFMA (measured: 40 cycles per instruction),
+// so the producers' instruction count per slice, not the memory system, is what can hold up the loop.
+// Hence: everything wave-uniform is computed on the scalar unit (the ring slot and the LDS
+// destinations; with UT also the filter tap of the slice), filter rows are addressed as a uniform
+// base plus a per-lane 32-bit offset that never changes, and what is left per image-matrix row is
+// the bounds test of its tap and the choice between the pixel's address and the zero unit.
+// UT ("uniform tap"): the units per pixel are a multiple of the eight units of a slice, so a slice
+// lies inside one filter tap and the tap is the same for all lanes; base[] then already contains
+// the lane's own unit offset.
+template <int DT, int BM, int BN, int STAGES, int PA, bool UT>
 __device__ __forceinline__ void direct_producer(const GemmArgs &a, float *As, float *Bs, int kc0, int kc1, int mt,
-                                                int krow, int pw, int r0, int vf, const int (&iy0)[PA],
+                                                int krow, int pw_, int r0, int vf, const int (&iy0)[PA],
                                                 const int (&ix0)[PA], const int (&base)[PA])
 {
     constexpr int PB = (BM + kRP - 1) / kRP; // filter-row passes (a tile of 16 channels: two waves repeat the others' rows)
     constexpr int PS = PA + PB;              // instructions per slice and wave
     constexpr int ASZ = BN * LDK, BSZ = BM * LDK;
     static_assert((STAGES - 3) * PS < 64, "outstanding loads must fit the counter");
+    const int pw = __builtin_amdgcn_readfirstlane(pw_); // the wave's number among the producers, as a scalar
     const float *x = static_cast<const float *>(a.x);
-    const floatx4 *wrow = static_cast<const floatx4 *>(a.wt) + (size_t)(mt * BM + (r0 % BM)) * krow + vf;
+    // this channel tile's rows of the filter matrix; the lane's rows and unit as byte offsets from there
+    // (below 4 GiB: the host checks BM * Kpad)
+    const char *wtile = reinterpret_cast<const char *>(static_cast<const floatx4 *>(a.wt) + (size_t)mt * BM * krow);
+    unsigned wofs[PB];
+#pragma unroll
+    for (int ps = 0; ps < PB; ++ps) wofs[ps] = (unsigned)((r0 % BM + kRP * ps) * krow + vf) * 16u;
     auto issue = [&](int kc, int slot) {
         // tap of this lane's unit in slice kc: unit index -> (filter tap, channel unit) -> (j, i)
-        const int q = kc * KU + vf;
+        const int q = kc * KU + (UT ? 0 : vf);
         const int tap = fast_div(q, a.dVin), cu = q - tap * a.dVin.d;
         const int tj = fast_div(tap, a.dKw), ti = tap - tj * a.kw;
         const bool tv = tj < a.kh;
@@ -507,13 +523,15 @@ __device__ __forceinline__ void direct_producer(const GemmArgs &a, float *As, fl
 #pragma unroll
         for (int ps = 0; ps < PA; ++ps) {
             const bool ok = tv && (unsigned)(iy0[ps] + tj) < (unsigned)a.H && (unsigned)(ix0[ps] + ti) < (unsigned)a.W;
+            // outside the image (or no pixel in this row): the zero unit kept behind the map, so that the
+            // load needs no predication
             const unsigned idx = ok ? (unsigned)(base[ps] + off) : (unsigned)a.zero_word;
             __builtin_amdgcn_global_load_lds((GlobalPtr)(x + idx), (LdsPtr)(A + kRP * ps * LDK), 16, 0, 0);
         }
+        const char *wslice = wtile + (size_t)kc * (KU * 16);
 #pragma unroll
         for (int ps = 0; ps < PB; ++ps)
-            __builtin_amdgcn_global_load_lds((GlobalPtr)(wrow + (size_t)(kRP * ps) * krow + kc * KU),
-                                             (LdsPtr)(B + kRP * ps * LDK), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((GlobalPtr)(wslice + wofs[ps]), (LdsPtr)(B + kRP * ps * LDK), 16, 0, 0);
     };
     // Nothing of this wave is in flight here; saying so keeps the compiler, which tracks loads into
     // registers along every path through the kernel, from waiting for imagined ones inside the loop.
@@ -674,7 +692,16 @@ __device__ __forceinline__ void gemm_gather_body(const GemmArgs &a, const int n,
                 }
             }
             if constexpr (DIRECT) {
-                direct_producer<DT, BM, BN, STAGES>(a, As, Bs, kc0, kc1, mt, krow, wave - kConsWaves, r0, vs, iy0, ix0, base);
+                if ((a.dVin.d & (KU - 1)) == 0) {
+                    // a slice lies inside one filter tap: the lane's unit goes into its pixel offsets once
+#pragma unroll
+                    for (int ps = 0; ps < PA; ++ps) base[ps] += vs * 4;
+                    direct_producer<DT, BM, BN, STAGES, PA, true>(a, As, Bs, kc0, kc1, mt, krow, wave - kConsWaves, r0, vs, iy0,
+                                                                  ix0, base);
+                } else {
+                    direct_producer<DT, BM, BN, STAGES, PA, false>(a, As, Bs, kc0, kc1, mt, krow, wave - kConsWaves, r0, vs,
+                                                                   iy0, ix0, base);
+                }
             } else {
             // NS register sets: in iteration kc the slice kc+2, loaded NS iterations ago, is stored to
             // the LDS ring and the loads of slice kc+2+NS are issued into the same registers.  The
@@ -1078,6 +1105,8 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm)
     if (a.Mpad % bm != 0 || a.Kpad % gemm_k_multiple(a.dtype) != 0 || a.Ms % eu != 0 || a.pix_words < 1 || !a.partial ||
         !a.tickets || a.grid < 8 || (a.grid & 7) || a.grid > kMaxGrid)
         return hipErrorInvalidValue;
+    // the direct-to-LDS producers address a channel tile's filter rows with 32-bit byte offsets
+    if ((long long)bm * a.Kpad * 4 >= (1ll << 32)) return hipErrorInvalidValue;
     // the divisors must belong to these arguments, and the schedule's 32-bit arithmetic must hold
     if (a.kh < 1 || a.kw < 1 || a.dKw.d != a.kw || a.dVin.d != (a.pix_words + 3) / 4) return hipErrorInvalidValue;
     if (a.dNo.d != a.No || a.dWo.d != a.Wo || a.dHo.d * a.Wo != a.No || a.dGrid.d != a.grid ||
