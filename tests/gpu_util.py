@@ -29,6 +29,25 @@ def assert_features_close(got, want, what="", bf16=False):
                                                  got.ravel()[k], want.ravel()[k]))
 
 
+def assert_bf16_roundings(got, pre, what=""):
+    """bfloat16 storage, the sharp form of the tolerance above: `pre` are the oracle's values before
+    the rounding to bfloat16 (double accumulation, rounded to float32).  The library rounds its own
+    float32 sum, which agrees with `pre` within the float32 tolerance; rounding is monotonic, so
+    the stored value must lie between the bfloat16 roundings of the two ends of that interval --
+    the rounding of `pre` itself, or its neighbour when `pre` is that close to a rounding boundary."""
+    got = np.asarray(got, dtype=np.float32)
+    pre = np.asarray(pre, dtype=np.float64)
+    tol = ATOL + RTOL * np.abs(pre)
+    lo = oracle.round_bf16((pre - tol).astype(np.float32))
+    hi = oracle.round_bf16((pre + tol).astype(np.float32))
+    bad = (got < lo) | (got > hi)
+    if bad.any():
+        k = int(np.argmax(bad.ravel()))
+        raise AssertionError("%s: %d of %d stored values are not the bfloat16 rounding of any value within the float32 "
+                             "tolerance of the oracle's unrounded one; first: got %r, oracle %r before rounding" %
+                             (what, int(bad.sum()), bad.size, got.ravel()[k], pre.ravel()[k]))
+
+
 def to_dev(a):
     import torch
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
@@ -146,6 +165,11 @@ def compare_sampled(layer, params, frames, tau, *, n_samples=600, n_streams=1, s
                     assert_features_close(g, want.reshape(L.cout, -1)[:, sel],
                                           "%s stream %d, positions last recomputed in frame %d" % (what, ss, tt),
                                           bf16)
+                    if bf16:
+                        pre = np.zeros((L.cout, Ho, Wo), np.float32)
+                        oracle.conv_update(frames[int(tt)][ss], w, b, sel, pre, L.stride, L.pad, L.relu, False)
+                        assert_bf16_roundings(g, pre.reshape(L.cout, -1)[:, sel],
+                                              "%s stream %d, frame %d" % (what, ss, tt))
     finally:
         net.destroy()
 
