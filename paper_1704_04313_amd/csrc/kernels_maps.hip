@@ -431,6 +431,7 @@ __global__ __launch_bounds__(kBlock) void dilate_kernel(const uint64_t *__restri
 // dilation with that window at stride 2.  The workgroup also leaves the number of set bits of
 // its words, which is what the index extraction needs to place its output.
 // ------------------------------------------------------------------------------------------
+static constexpr int kCompactTwoLevelBytesFrom = 768; // byte maps of more words than this: set bits counted per group first
 static constexpr int kCompactTwoWordsFrom = 65536; // maps of more words than this: two words per thread in the index extraction
 static constexpr int kCompactStage = 2048; // list entries a workgroup stages in LDS (8 KiB); more go straight to the list
 static constexpr int kCompactDense = 12;   // words with more set bits than this are expanded by a whole wave
@@ -931,7 +932,11 @@ hipError_t compact(hipStream_t st, const CompactJob *jobs, int njobs, bool group
         if (!jobs[i].bits || reinterpret_cast<uintptr_t>(jobs[i].bits) % 16 || !jobs[i].list || !jobs[i].count) return hipErrorInvalidValue;
     const bool two = maxw > kCompactTwoWordsFrom; // words per thread
     const int gx = (maxw + (two ? 2 : 1) * kBlock - 1) / ((two ? 2 : 1) * kBlock);
-    if (groups_ready || compact_two_level(maxw)) {
+    // a byte map costs eight loads per word: letting every workgroup recount all preceding words is
+    // worth it for much smaller maps only
+    bool any_bytes = false;
+    for (int i = 0; i < njobs; ++i) any_bytes = any_bytes || jobs[i].bytes != 0;
+    if (groups_ready || compact_two_level(maxw) || (any_bytes && maxw > kCompactTwoLevelBytesFrom)) {
         for (int i = 0; i < njobs; ++i)
             if (!jobs[i].group_counts || reinterpret_cast<uintptr_t>(jobs[i].group_counts) % 16) return hipErrorInvalidValue;
         Timing t2 = tm;
