@@ -93,6 +93,11 @@ CASES = [
     (12, 70, 3, 5, 1, 2, 17, 64, True),
     (2, 6, 9, 16, 1, 7, 20, 40, False),
     (3, 5, 6, 4, 1, 2, 23, 31, True),
+    # more than 64 output channels (direct-to-LDS producers), with inputs whose K slices lie inside one
+    # filter tap (32 and 64 channels) and one whose slices straddle taps (40 channels)
+    (32, 130, 3, 3, 2, 1, 21, 26, False),
+    (64, 96, 5, 3, 1, 2, 18, 22, True),
+    (40, 100, 3, 3, 1, 1, 15, 17, False),
 ]
 
 
