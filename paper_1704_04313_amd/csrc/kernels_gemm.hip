@@ -30,6 +30,10 @@
 // partial accumulators; the last workgroup to finish a tile (an atomic ticket, nobody waits)
 // adds all parts in ascending K order, which keeps results deterministic, and performs the
 // output update.
+//
+// Layers with short filter-matrix rows and few output channels (a first layer on camera frames, 1x1
+// layers) would spend such a launch filling and draining the ring; they run gemm_thin_kernel, in
+// which every wave multiplies 16 positions by the whole reduction out of its own registers.
 #include "kernels.h"
 
 #include <cstdio>
@@ -1007,6 +1011,259 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT + 255) /
         gemm_gather_body<DT, BM, BNS, WMS, WNS, SS, DS>(a, n, smem, sel);
 }
 
+// ---- layers whose whole reduction fits a wave's registers ----------------------------------
+//
+// A filter-matrix row of at most kThinGroups * 4 units (256 floats, 512 bfloat16) and at most
+// kThinChannels output channels: first layers on camera frames, 1x1 layers on few channels.  The
+// tile pipeline above spends most of such a launch filling and draining its ring -- a tile has a
+// handful of K slices -- so here a wave works alone: 16 listed positions x 16 channels x the whole
+// reduction.  Lane (pixel l % 16, slot l / 16) gathers units slot, 4 + slot, 8 + slot ... of its pixel's
+// image-matrix row straight into registers, all loads in flight at once, and feeds them to the
+// matrix cores against filter fragments read from an LDS copy of the filter matrix (rows one unit
+// apart in the banks).  No barrier after set-up: the three waves of a SIMD hide each other's
+// gather latency.  The positions come from the ranked map (each lane finds its own position with
+// a binary search over the ranks) or from the list.  Every sum is formed in ascending k by one
+// wave, so results do not depend on the number of positions.
+static constexpr int kThinGroups = 16;
+static constexpr int kThinChannels = 64;
+static constexpr int kThinMaxWork = 32;     // groups x channel tiles up to which this kernel is used
+static constexpr int kThinWholeFactor = 2; // tiles of 16 positions per wave from which a wave takes all channel tiles
+static constexpr int kThinScratchBytes = (2 * kSelMaxWords + 4) * 8;                           // front-end scratch
+static constexpr int kThinFilterBytes = kThinChannels * (kThinGroups * 4 + 1) * 16;              // [Mpad][units + 1]
+static constexpr int kThinTapBytes = kThinGroups * 4 * (int)sizeof(int2);
+static constexpr int kThinSelOffset = kThinScratchBytes + kThinFilterBytes + kThinTapBytes;
+static constexpr int kThinSmemBytes = kThinSelOffset + kSelSlots * 12 + 64;
+static_assert(kThinSmemBytes <= 160 * 1024, "a workgroup has 160 KiB of LDS");
+
+// The position of rank r (0 <= r < number of selected positions) in a ranked selection map.
+__device__ __forceinline__ int select_rank(const Selection &sel, int r)
+{
+    // the last word whose exclusive rank is <= r holds it: later words start at a higher rank,
+    // and of the words sharing its rank it is the last (the others are empty)
+    int w = 0;
+#pragma unroll
+    for (int step = kSelMaxWords; step; step >>= 1)
+        if (w + step < sel.nwords && sel.rank[w + step] <= r) w += step;
+    const uint64_t bits = sel.words[w];
+    int k = r - sel.rank[w], pos = 0; // the k-th set bit of the word, counted from 0
+#pragma unroll
+    for (int sh = 32; sh; sh >>= 1) {
+        const int c = __popcll((bits >> pos) & ((1ull << sh) - 1ull));
+        if (k >= c) {
+            k -= c;
+            pos += sh;
+        }
+    }
+    return w * 64 + pos;
+}
+
+// One wave's share of the tiles: 16 positions x TC channel tiles of 16.  In program order per tile:
+// find the next tile's positions, multiply the current tile (its gathers were issued a tile ago),
+// issue the next tile's gathers into the registers the MFMAs have just read, update the outputs of
+// the current tile -- so a tile's gather latency passes during the update before it and the search
+// after it.
+template <int DT, int TC>
+__device__ __forceinline__ void thin_tiles(const GemmArgs &a, const int n, const Selection &sel, const uintx4 *sB,
+                                           const int2 *sTap, const int G, const int pitch)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cgroups = (a.Mpad >> 4) / TC; // wave tiles per pixel tile: 1, 2 or 4
+    const int cshift = cgroups == 1 ? 0 : (cgroups == 2 ? 1 : 2);
+    const long long T = (long long)((n + 15) >> 4) << cshift; // wave tiles, channel group fastest
+    const int W = gridDim.x;
+    // workgroups are dealt round-robin over the 8 XCDs: number them so that each XCD gets a contiguous range
+    const int w = (int)(blockIdx.x & 7) * (W >> 3) + (int)(blockIdx.x >> 3);
+    const int t_begin = (int)(T * w / W), t_end = (int)(T * (w + 1) / W);
+    const int lrow = lane & 15, lk = lane >> 4;
+    const float *x = static_cast<const float *>(a.x);
+    const bool detect = a.next_flags != nullptr && !a.next_force;
+
+    struct Where {
+        int g, iy0, ix0, base;
+    };
+    auto locate = [&](int t) {
+        const int r = (t >> cshift) * 16 + lrow;
+        Where p = {-1, -(1 << 28), -(1 << 28), 0};
+        if (r < n) p.g = sel.words ? select_rank(sel, r) : a.list[r];
+        if (p.g >= 0) {
+            const int st = fast_div(p.g, a.dNo), q = p.g - st * a.No;
+            const int qy = fast_div(q, a.dWo), qx = q - qy * a.Wo;
+            p.iy0 = qy * a.stride - a.pad;
+            p.ix0 = qx * a.stride - a.pad;
+            p.base = ((st * a.H + p.iy0) * a.W + p.ix0) * a.pix_words;
+        }
+        return p;
+    };
+    floatx4 ra[kThinGroups];
+    uintx4 replaced[TC];
+    auto gather = [&](const Where &p, int cg) {
+#pragma unroll
+        for (int gg = 0; gg < kThinGroups; ++gg) {
+            if (gg < G) {
+                const int2 tp = sTap[4 * gg + lk];
+                const int tj = tp.y & 0xff, ti = (tp.y >> 8) & 0xff;
+                const bool ok = (tp.y >> 16) != 0 && (unsigned)(p.iy0 + tj) < (unsigned)a.H && (unsigned)(p.ix0 + ti) < (unsigned)a.W;
+                // outside the image (or no pixel in this row): the zero unit kept behind the map
+                const unsigned idx = ok ? (unsigned)(p.base + tp.x) : (unsigned)a.zero_word;
+                ra[gg] = *reinterpret_cast<const floatx4_a4 *>(x + idx);
+            }
+        }
+        // the values about to be replaced, for the change detection of the layer this map feeds
+#pragma unroll
+        for (int j = 0; j < TC; ++j) {
+            const int ch = (cg * TC + j) * 16 + lk * 4;
+            replaced[j] = (uintx4){0u, 0u, 0u, 0u};
+            if (detect && p.g >= 0 && ch < a.Ms) {
+                if constexpr (DT == kBF16) {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(static_cast<const unsigned short *>(a.out) + (size_t)p.g * a.Ms + ch);
+                    replaced[j][0] = v.x;
+                    replaced[j][1] = v.y;
+                } else {
+                    replaced[j] = *reinterpret_cast<const uintx4 *>(static_cast<const float *>(a.out) + (size_t)p.g * a.Ms + ch);
+                }
+            }
+        }
+    };
+
+    int t = t_begin + wave;
+    if (t >= t_end) return;
+    Where cur = locate(t);
+    gather(cur, t & (cgroups - 1));
+    while (t < t_end) {
+        const int tn = t + NT / 64;
+        const bool more = tn < t_end;
+        Where nxt = {-1, 0, 0, 0};
+        if (more) nxt = locate(tn);
+        const int cg = t & (cgroups - 1);
+        // MFMA step s of group gg contracts k = 16 gg + 4 slot + s over the four slots (bfloat16: the
+        // eight k of a unit at once); D[4 slot + i][pixel] lands in this lane: four consecutive channels
+        floatx4 acc[TC];
+#pragma unroll
+        for (int j = 0; j < TC; ++j) acc[j] = (floatx4){0.f, 0.f, 0.f, 0.f};
+        const uintx4 *brow = sB + (cg * TC * 16 + lrow) * pitch + lk;
+#pragma unroll
+        for (int gg = 0; gg < kThinGroups; ++gg) {
+            if (gg < G) {
+#pragma unroll
+                for (int j = 0; j < TC; ++j) {
+                    const uintx4 bq = brow[j * 16 * pitch + 4 * gg];
+                    if constexpr (DT == kBF16) {
+                        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bq),
+                                                                     __builtin_bit_cast(bf16x8, ra[gg]), acc[j], 0, 0, 0);
+                    } else {
+                        const floatx4 bf = __builtin_bit_cast(floatx4, bq);
+#pragma unroll
+                        for (int s = 0; s < 4; ++s) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(bf[s], ra[gg][s], acc[j], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        uintx4 old[TC];
+#pragma unroll
+        for (int j = 0; j < TC; ++j) old[j] = replaced[j];
+        if (more) gather(nxt, tn & (cgroups - 1));
+        // output update: bias, activation, scatter to the stored map
+        bool changed = false;
+#pragma unroll
+        for (int j = 0; j < TC; ++j) {
+            const int ch = (cg * TC + j) * 16 + lk * 4;
+            if (cur.g >= 0 && ch < a.Ms) {
+                const float4 bv = *reinterpret_cast<const float4 *>(a.bias + ch);
+                float4 o;
+                o.x = acc[j][0] + bv.x;
+                o.y = acc[j][1] + bv.y;
+                o.z = acc[j][2] + bv.z;
+                o.w = acc[j][3] + bv.w;
+                if (a.relu) {
+                    o.x = fmaxf(o.x, 0.f);
+                    o.y = fmaxf(o.y, 0.f);
+                    o.z = fmaxf(o.z, 0.f);
+                    o.w = fmaxf(o.w, 0.f);
+                }
+                if constexpr (DT == kBF16) {
+                    uint2 nv;
+                    nv.x = (unsigned)bf16_bits(o.x) | ((unsigned)bf16_bits(o.y) << 16);
+                    nv.y = (unsigned)bf16_bits(o.z) | ((unsigned)bf16_bits(o.w) << 16);
+                    if (detect)
+                        changed |= fabsf(bf16_value(nv.x & 0xffff) - bf16_value(old[j][0] & 0xffff)) > a.next_tau ||
+                                   fabsf(bf16_value(nv.x >> 16) - bf16_value(old[j][0] >> 16)) > a.next_tau ||
+                                   fabsf(bf16_value(nv.y & 0xffff) - bf16_value(old[j][1] & 0xffff)) > a.next_tau ||
+                                   fabsf(bf16_value(nv.y >> 16) - bf16_value(old[j][1] >> 16)) > a.next_tau;
+                    *reinterpret_cast<uint2 *>(static_cast<unsigned short *>(a.out) + (size_t)cur.g * a.Ms + ch) = nv;
+                } else {
+                    if (detect)
+                        changed |= fabsf(o.x - __uint_as_float(old[j][0])) > a.next_tau ||
+                                   fabsf(o.y - __uint_as_float(old[j][1])) > a.next_tau ||
+                                   fabsf(o.z - __uint_as_float(old[j][2])) > a.next_tau ||
+                                   fabsf(o.w - __uint_as_float(old[j][3])) > a.next_tau;
+                    *reinterpret_cast<float4 *>(static_cast<float *>(a.out) + (size_t)cur.g * a.Ms + ch) = o;
+                }
+            }
+        }
+        if (a.next_flags) {
+            int f = a.next_force ? 1 : (int)changed;
+            // the other channels of this pixel sit in the lanes 16, 32 and 48 further on
+            f |= __shfl_xor(f, 16);
+            f |= __shfl_xor(f, 32);
+            if (lk == 0 && f && cur.g >= 0) a.next_flags[cur.g] = 1;
+        }
+        cur = nxt;
+        t = tn;
+    }
+}
+
+// MT: channel tiles of the layer (Mpad / 16).  A wave takes all of them for its 16 positions when
+// there are enough positions to occupy every wave that way, else one each.
+template <int DT, int MT>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT + 255) / 256, (NT + 255) / 256))) void gemm_thin_kernel(GemmArgs a)
+{
+    extern __shared__ __align__(16) float smem[];
+    char *lds = reinterpret_cast<char *>(smem);
+    uintx4 *sB = reinterpret_cast<uintx4 *>(lds + kThinScratchBytes);
+    int2 *sTap = reinterpret_cast<int2 *>(lds + kThinScratchBytes + kThinFilterBytes);
+    const int tid = threadIdx.x;
+    const int nu = a.Kpad / Unit<DT>::N; // units per filter-matrix row: a multiple of eight
+    const int G = nu >> 2, pitch = nu + 1;
+    {
+        const uintx4 *wt = static_cast<const uintx4 *>(a.wt);
+        for (int i = tid; i < a.Mpad * nu; i += NT) {
+            const int r = fast_div(i >> 3, a.dNk), u = i - r * nu;
+            sB[r * pitch + u] = wt[i];
+        }
+        for (int i = tid; i < nu; i += NT) sTap[i] = a.taps[i];
+    }
+    Selection sel = {nullptr, nullptr, 0};
+    int n;
+    if (a.sel_words > 0) {
+        uint64_t *sW = reinterpret_cast<uint64_t *>(lds + kThinSelOffset);
+        int *sRank = reinterpret_cast<int *>(lds + kThinSelOffset + kSelSlots * 8);
+        n = rank_selection(a, sW, sRank, sRank + kSelSlots, reinterpret_cast<uint64_t *>(lds));
+        sel.words = sW;
+        sel.rank = sRank;
+        sel.nwords = a.sel_words;
+    } else {
+        n = *a.count;
+    }
+    __syncthreads();
+    if constexpr (MT > 1) {
+        if (((n + 15) >> 4) >= kThinWholeFactor * (NT / 64) * (int)gridDim.x) {
+            thin_tiles<DT, MT>(a, n, sel, sB, sTap, G, pitch);
+            return;
+        }
+    }
+    thin_tiles<DT, 1>(a, n, sel, sB, sTap, G, pitch);
+}
+
+// Measured against the tile pipeline on 3..256 input and 8..64 output channels, 4 800 to 4 million
+// positions: the lone waves win as long as (groups of four units) x (channel tiles) stays at or
+// below 32 -- beyond that a wave's chain of MFMAs per tile gets long and the big tiles' reuse of
+// filter fragments pays.
+static bool gemm_is_thin(const GemmArgs &a)
+{
+    const int nu = a.Kpad / elems_per_unit(a.dtype);
+    return nu <= kThinGroups * 4 && (a.Mpad == 16 || a.Mpad == 32 || a.Mpad == 64) && (nu / 4) * (a.Mpad / 16) <= kThinMaxWork;
+}
+
 // ---- host side --------------------------------------------------------------------------
 int gemm_k_multiple(int dtype) { return BK * 4 / elem_bytes(dtype); }
 
@@ -1082,6 +1339,12 @@ hipError_t gemm_prepare(void)
                                 hipFuncAttributeMaxDynamicSharedMemorySize, KernelSmem<BM_, BNB_, SB_, BNS_, SS_>::bytes);
     CBK_VARIANTS(X)
 #undef X
+#define T(DT_, MT_)                                                                                                \
+    if (e == hipSuccess)                                                                                           \
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_thin_kernel<DT_, MT_>),                       \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kThinSmemBytes);
+    T(kF32, 1) T(kF32, 2) T(kF32, 4) T(kBF16, 1) T(kBF16, 2) T(kBF16, 4)
+#undef T
     return e;
 }
 
@@ -1120,6 +1383,15 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm)
     if (a.sel_words < 0 || a.sel_words > kSelMaxWords || (a.sel_words > 0 && !a.sel_map) ||
         (a.sel_words == 0 && (!a.list || !a.count)) || (long long)a.sel_words * 64 < a.max_pixels * (a.sel_words > 0))
         return hipErrorInvalidValue;
+    if (gemm_is_thin(a)) {
+#define T(DT_, MT_)                                                                                      \
+    if (a.dtype == DT_ && a.Mpad == 16 * MT_) {                                                           \
+        launch_kernel(tm, gemm_thin_kernel<DT_, MT_>, dim3(a.grid), dim3(NT), kThinSmemBytes, st, a);    \
+        return hipGetLastError();                                                                        \
+    }
+        T(kF32, 1) T(kF32, 2) T(kF32, 4) T(kBF16, 1) T(kBF16, 2) T(kBF16, 4)
+#undef T
+    }
 #define X(BM_, BNB_, WMB_, WNB_, SB_, DB_, BNS_, WMS_, WNS_, SS_, DS_) \
     if (bm == BM_) return launch<BM_, BNB_, WMB_, WNB_, SB_, DB_, BNS_, WMS_, WNS_, SS_, DS_>(st, a, tm);
     CBK_VARIANTS(X)

@@ -95,6 +95,27 @@ def test_strided_workload_layers_full_size_sampled(l):
     compare_sampled(L, params[l], frames, cfg.tau, label="strided workload layer %d" % l)
 
 
+@pytest.mark.parametrize("shape", [
+    # C, M, k, H, W, bf16 -- layers whose filter rows are short enough for the kernel in which a wave
+    # multiplies 16 positions by itself: 2 and 4 channel tiles of 16, taken together by one wave (many
+    # positions) or one per wave (few), in both storage types
+    (3, 64, 3, 480, 640, False),
+    (3, 32, 3, 480, 640, False),
+    (16, 32, 3, 60, 80, False),
+    (32, 64, 1, 60, 80, False),
+    (128, 16, 1, 120, 160, False),
+    (3, 32, 3, 480, 640, True),
+    (16, 32, 3, 60, 80, True),
+    (64, 64, 1, 240, 320, True),
+])
+def test_short_reduction_layers_sampled(shape):
+    C, M, k, H, W, bf16 = shape
+    L = conv(C, M, k)
+    params = make_weights([L], 4000 + C + M)[0]
+    frames = _patched_sequence(C, H, W, 3, seed=C * 11 + M)
+    compare_sampled(L, params, frames, 0.02, label="short reduction %s" % (shape,), bf16=bf16)
+
+
 def test_config2_dominant_layer_thirty_frames_every_tile_shared():
     """The 64 -> 256 7x7 layer at the benchmark's size (4800 positions: 150 tiles over 256
     workgroups, every tile's sum split along K and added up by whichever workgroup finishes last),
