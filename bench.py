@@ -303,6 +303,10 @@ def roofline_of(cfg, kernels):
     roof["kernel"] = dom
     roof["avg_us"] = d["us"]
     roof["sum_kernel_us_per_frame"] = sum(k["us"] for k in kernels.values())
+    # each launch's own first-wave-to-last-wave interval from the events attached to it; the dispatch of a
+    # launch overlaps the completion of the one before by up to a microsecond, so the sum of a frame's
+    # intervals can exceed the frame's time by a few per cent
+    roof["sum_kernel_us_is"] = "sum of per-launch intervals of one frame, one frame at a time; neighbours overlap by < 1 us each"
     return roof
 
 
