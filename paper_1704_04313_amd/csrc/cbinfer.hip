@@ -749,7 +749,7 @@ static cbinfer_state *create_state(const cbinfer_network *net, const Plan &P, ch
             HIP_TRY(hipEventCreateWithFlags(&s->ev_in, hipEventDisableTiming));
             for (int i = 0; i < 2; ++i) {
                 HIP_TRY(hipStreamCreateWithFlags(&s->pstream[i], hipStreamNonBlocking));
-                s->pipe_gap = P.ops.size() >= 6 ? 3 : (P.ops.size() >= 4 ? 2 : 1);
+                s->pipe_gap = P.ops.size() >= 12 ? 4 : (P.ops.size() >= 6 ? 3 : (P.ops.size() >= 4 ? 2 : 1));
                 s->ev_op[i].assign(P.ops.size() + 1, nullptr);
                 for (hipEvent_t &e : s->ev_op[i]) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
             }

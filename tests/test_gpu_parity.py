@@ -622,6 +622,32 @@ def test_frames_in_flight_scene_network_matches_ordinary_mode():
     b.destroy()
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_frames_in_flight_deep_network_matches_ordinary_mode(bf16):
+    """A network of thirteen operations (the VGG-style recipe at 64x80), where only every fourth
+    operation waits for the previous frame: 20 frames in flight against the same frames one at a
+    time, every output identical."""
+    import torch
+    cfg = get_config(4, height=64, width=80, n_frames=20)
+    params = cfg.weights()
+    v = cfg.video()
+    frames = [to_dev(v.frame(t)) for t in range(cfg.n_frames)]
+    dt = cb.BF16 if bf16 else cb.F32
+    assert len(cfg.layers) >= 12
+    a = cb.CBInfer(cfg.layers, params, (3, 64, 80), cfg.tau, dtype=dt)
+    ref = [a.process_frame(f).cpu().numpy().copy() for f in frames]
+    a.destroy()
+    b = cb.CBInfer(cfg.layers, params, (3, 64, 80), cfg.tau, dtype=dt, pipeline_frames=True)
+    outs = [torch.empty(b.out_shape, dtype=torch.float32, device="cuda") for _ in frames]
+    for f, o in zip(frames, outs):
+        b.process_frame(f, o)
+    b.flush()
+    torch.cuda.synchronize()
+    for t, (o, r) in enumerate(zip(outs, ref)):
+        np.testing.assert_array_equal(o.cpu().numpy(), r, err_msg="frame %d" % t)
+    b.destroy()
+
+
 def test_large_multi_stream_frames_without_padding_channels():
     """Two streams whose frames together pass 2^18 pixels (stored with three values per pixel), an
     odd number of pixels per stream: waves and float4 of the stored map straddle the stream boundary."""
