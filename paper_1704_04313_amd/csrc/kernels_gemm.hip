@@ -1289,13 +1289,21 @@ int gemm_channel_tile(int M)
     return 128;
 }
 
-static int pixel_tile(int bm) { return bm == 128 ? 128 : 256; }
+// Pixels per big tile.  The 64-channel kernel takes 128 instead of 256 on maps of at most
+// kNarrowTilePixels positions, where a 256-pixel tile would leave most workgroups a third of a tile's K
+// range (16->64 7x7: 35.5 -> 33.6 us at 160x120, but 230 -> 248 us at 640x360).
+static constexpr int kNarrowTilePixels = 65536;
+static int pixel_tile(int bm, int max_pixels)
+{
+    if (bm == 128) return 128;
+    return bm == 64 && max_pixels <= kNarrowTilePixels ? 128 : 256;
+}
 
 // Two partial-accumulator slabs per workgroup.
 size_t gemm_partial_bytes(int M, int grid)
 {
     const int bm = gemm_channel_tile(M);
-    return (size_t)2 * grid * bm * pixel_tile(bm) * sizeof(float);
+    return (size_t)2 * grid * bm * pixel_tile(bm, 0x7fffffff) * sizeof(float); // the widest tile of that channel tile
 }
 
 // One ticket counter per shared tile (fewer than the workgroup count); zero between launches.
@@ -1304,7 +1312,7 @@ size_t gemm_ticket_bytes(int grid) { return (size_t)grid * sizeof(int); }
 // Workgroups to launch: one per compute unit, fewer if even the longest list gives less work.
 int gemm_grid(const GemmArgs &a, int compute_units)
 {
-    const int bm = gemm_channel_tile(a.M), bn = pixel_tile(bm);
+    const int bm = gemm_channel_tile(a.M), bn = pixel_tile(bm, a.max_pixels);
     int W = compute_units & ~7;
     if (W < 8) W = 8;
     if (W > kMaxGrid) W = kMaxGrid;
@@ -1323,6 +1331,7 @@ int gemm_grid(const GemmArgs &a, int compute_units)
     X(16, 256, 1, 8, 3, false, 128, 1, 8, 3, false)             \
     X(32, 256, 1, 8, 3, false, 64, 2, 4, 3, false)              \
     X(64, 256, 2, 4, 3, false, 64, 2, 4, 3, false)              \
+    X(64, 128, 2, 4, 3, false, 64, 2, 4, 3, false)              \
     X(128, 128, 2, 4, 4, true, 64, 4, 2, 5, true)
 
 hipError_t gemm_prepare(void)
@@ -1363,7 +1372,7 @@ static hipError_t launch(hipStream_t st, const GemmArgs &a, const Timing &tm)
 
 hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm)
 {
-    const int bm = gemm_channel_tile(a.M);
+    const int bm = gemm_channel_tile(a.M), bn = pixel_tile(bm, a.max_pixels);
     const int eu = elems_per_unit(a.dtype);
     if (a.Mpad % bm != 0 || a.Kpad % gemm_k_multiple(a.dtype) != 0 || a.Ms % eu != 0 || a.pix_words < 1 || !a.partial ||
         !a.tickets || a.grid < 8 || (a.grid & 7) || a.grid > kMaxGrid)
@@ -1393,7 +1402,7 @@ hipError_t gemm_gather(hipStream_t st, const GemmArgs &a, const Timing &tm)
 #undef T
     }
 #define X(BM_, BNB_, WMB_, WNB_, SB_, DB_, BNS_, WMS_, WNS_, SS_, DS_) \
-    if (bm == BM_) return launch<BM_, BNB_, WMB_, WNB_, SB_, DB_, BNS_, WMS_, WNS_, SS_, DS_>(st, a, tm);
+    if (bm == BM_ && bn == BNB_) return launch<BM_, BNB_, WMB_, WNB_, SB_, DB_, BNS_, WMS_, WNS_, SS_, DS_>(st, a, tm);
     CBK_VARIANTS(X)
 #undef X
     return hipErrorInvalidValue;
