@@ -1316,6 +1316,14 @@ int gemm_grid(const GemmArgs &a, int compute_units)
     int W = compute_units & ~7;
     if (W < 8) W = 8;
     if (W > kMaxGrid) W = kMaxGrid;
+    if (gemm_is_thin(a)) {
+        // a workgroup per four wave tiles of 16 positions x 16 channels (one per SIMD: spreading a short
+        // list over more compute units shortens the launch, 128->16 1x1 at 160x120: 6.6 -> 5.4 us)
+        const long long wave_tiles = (long long)((a.max_pixels + 15) / 16) * (a.Mpad / 16);
+        long long need = ((wave_tiles + 3) / 4 + 7) / 8 * 8;
+        if (need < 8) need = 8;
+        return (int)(need < W ? need : W);
+    }
     const int nk = a.Kpad / gemm_k_multiple(a.dtype);
     const int parts = nk / kMinIters > 1 ? nk / kMinIters : 1;
     // with few pixels the small tile (64 pixels) is used: count those
